@@ -1,0 +1,537 @@
+/*
+ * CPU oracle for history-drafted speculative decoding (HistoSpec hot path).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, written-from-the-
+ * definition version of what the GPU library computes.  It shares no code,
+ * header, table or helper with the HIP path and must never be called by it.
+ * Only the test-suite, the smoke check and the benchmark's cpu_baseline leg
+ * load it.
+ *
+ * Arithmetic: every floating-point quantity is fp64.  Weights arrive as bf16
+ * bit patterns (uint16) and are widened exactly; the RoPE table arrives as
+ * fp32 values and is widened exactly.  No blocking, fusion or reordering is
+ * applied beyond what each definition states; OpenMP only splits independent
+ * output rows of a matrix-vector product.
+ *
+ * What each function follows (paper = "History Rhymes", arXiv 2508.18588):
+ *   orc_suffix_match*      Sec. 5.2 (last generated tokens searched in the
+ *                          historical response, following tokens are the
+ *                          draft) and Sec. 5.4 (pattern length 7 shrinking
+ *                          to 3 when nothing matches).
+ *   orc_trace_sim          Sec. 5.1 token-similarity study (3-token key).
+ *   orc_k_policy, orc_aimd Sec. 5.4 (window starts at 2, +2 when every draft
+ *                          token is accepted, cap 32, back to 2 on a reject).
+ *   orc_seq_*              Sec. 2.2: the target model's forward pass (a
+ *                          standard pre-norm decoder; shape from the
+ *                          benchmark configurations).
+ *   orc_accept_greedy,
+ *   orc_accept_stochastic  Sec. 2.2: verification accepts the valid draft
+ *                          tokens and preserves the output distribution; the
+ *                          rule is standard speculative sampling with a
+ *                          point-mass draft distribution.
+ *   orc_philox4x32_10      Salmon et al., "Parallel random numbers: as easy
+ *                          as 1, 2, 3" (SC'11), Philox-4x32 with 10 rounds.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ draft */
+
+/* Longest common suffix between hist[..p) and x[..n), capped at w. */
+static int common_suffix(const int32_t* hist, int p, const int32_t* x, int n, int w) {
+    int m = 0;
+    while (m < w && m < p && m < n && hist[p - 1 - m] == x[n - 1 - m]) m++;
+    return m;
+}
+
+/*
+ * Plain definition of the draft position.  Over every end position p in
+ * [1, lh-1] (at least one history token must follow p), m(p) is the length
+ * of the longest common suffix of hist[..p) and x[..n), capped at w.  The
+ * chosen p maximises m(p) subject to m(p) >= m_min; among equal m the
+ * smallest p wins.  Returns 1 and sets *p_out, *m_out if a match exists, else
+ * returns 0 with *p_out = -1 and *m_out = 0.
+ */
+int orc_suffix_match(const int32_t* hist, int lh, const int32_t* x, int n, int w, int m_min,
+                     int* p_out, int* m_out) {
+    int best_p = -1, best_m = 0;
+    for (int p = 1; p <= lh - 1; p++) {
+        int m = common_suffix(hist, p, x, n, w);
+        if (m >= m_min && m > best_m) { best_m = m; best_p = p; }
+    }
+    *p_out = best_p;
+    *m_out = best_m;
+    return best_p >= 0;
+}
+
+/*
+ * The same choice stated the way Sec. 5.4 words it: try a pattern of the w
+ * last tokens; if it occurs nowhere, shorten it by one, down to m_min.  The
+ * first (leftmost) occurrence of the longest pattern that occurs is taken.
+ */
+int orc_suffix_match_backoff(const int32_t* hist, int lh, const int32_t* x, int n, int w, int m_min,
+                             int* p_out, int* m_out) {
+    for (int len = (w < n ? w : n); len >= m_min && len >= 1; len--) {
+        for (int p = len; p <= lh - 1; p++) {
+            int ok = 1;
+            for (int j = 0; j < len; j++)
+                if (hist[p - len + j] != x[n - len + j]) { ok = 0; break; }
+            if (ok) { *p_out = p; *m_out = len; return 1; }
+        }
+    }
+    *p_out = -1;
+    *m_out = 0;
+    return 0;
+}
+
+/*
+ * Offline similarity routine of Sec. 5.1: replay `cur` from its start; with
+ * the last `key` replayed tokens as pattern, look for an exact occurrence in
+ * `hist`; on a hit count the run of tokens that follow identically in both
+ * (those are "accepted"), otherwise advance by one generated token.  Returns
+ * the number of accepted tokens.  The leftmost occurrence with the longest
+ * following run is not specified by the paper; this takes the occurrence
+ * whose following run is longest (best case), first such on ties.
+ */
+int orc_trace_sim(const int32_t* cur, int n, const int32_t* hist, int lh, int key) {
+    int accepted = 0;
+    int i = 0; /* number of tokens replayed so far */
+    while (i < n) {
+        int best_run = 0;
+        if (i >= key) {
+            for (int p = key; p <= lh - 1; p++) {
+                int ok = 1;
+                for (int j = 0; j < key; j++)
+                    if (hist[p - key + j] != cur[i - key + j]) { ok = 0; break; }
+                if (!ok) continue;
+                int run = 0;
+                while (p + run < lh && i + run < n && hist[p + run] == cur[i + run]) run++;
+                if (run > best_run) best_run = run;
+            }
+        }
+        if (best_run > 0) { accepted += best_run; i += best_run; }
+        else i += 1;
+    }
+    return accepted;
+}
+
+/* --------------------------------------------------------------- K policy */
+
+enum { ORC_K_FIXED = 0, ORC_K_MATCHLEN = 1, ORC_K_AIMD = 2 };
+
+/* Requested draft length before truncation (0 when there was no match). */
+int orc_k_policy(int mode, int k_fixed, int k_state, int match_len, int k_max) {
+    if (match_len <= 0) return 0;
+    int k;
+    if (mode == ORC_K_FIXED) k = k_fixed;
+    else if (mode == ORC_K_MATCHLEN) k = match_len < 1 ? 1 : match_len;
+    else k = k_state;
+    if (k > k_max) k = k_max;
+    if (k < 0) k = 0;
+    return k;
+}
+
+/* Truncate by what the history still holds after p and by the response budget
+ * (one emitted token always comes from the model itself). */
+int orc_draft_len(int k_policy, int lh, int p, int budget_left) {
+    if (p < 0) return 0;
+    int k = k_policy;
+    if (k > lh - p) k = lh - p;
+    if (k > budget_left - 1) k = budget_left - 1;
+    if (k < 0) k = 0;
+    return k;
+}
+
+/* Window update of Sec. 5.4.  `drafted` = were there draft tokens at all,
+ * `full` = every token on the verified path down to a leaf was accepted. */
+int orc_aimd(int k, int drafted, int full, int inc, int cap, int reset) {
+    if (!drafted) return k;
+    if (full) { k += inc; if (k > cap) k = cap; return k; }
+    return reset;
+}
+
+/* ------------------------------------------------------------- draft tree */
+
+/*
+ * Merge C draft chains into a token tree.  Node 0 is the root (the last
+ * committed token, position l_cached).  Chains are inserted in candidate
+ * order; a chain follows existing nodes while its tokens agree with them and
+ * opens new nodes from its first differing token on.  Nodes are numbered in
+ * creation order.  anc_mask bit i of node r is set iff node i lies on the
+ * path root..r (r included).  Returns the node count.
+ */
+int orc_build_tree(int n_cand, const int32_t* const* chains, const int* chain_len, int32_t root_tok,
+                   int l_cached, int32_t* tok, int32_t* pos, int32_t* parent, uint64_t* anc_mask,
+                   int max_nodes) {
+    int n = 0;
+    tok[0] = root_tok; pos[0] = l_cached; parent[0] = -1; anc_mask[0] = 1ull; n = 1;
+    for (int c = 0; c < n_cand; c++) {
+        int cur = 0;
+        for (int j = 0; j < chain_len[c]; j++) {
+            int32_t t = chains[c][j];
+            int found = -1;
+            for (int i = 1; i < n; i++)
+                if (parent[i] == cur && tok[i] == t) { found = i; break; }
+            if (found < 0) {
+                if (n >= max_nodes) return -1;
+                tok[n] = t; pos[n] = pos[cur] + 1; parent[n] = cur;
+                anc_mask[n] = anc_mask[cur] | (1ull << n);
+                found = n++;
+            }
+            cur = found;
+        }
+    }
+    return n;
+}
+
+/* ------------------------------------------------------------------ model */
+
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, max_pos;
+    double rms_eps;
+    const uint16_t* embed;          /* [vocab, d] bf16 bits */
+    const uint16_t* lm_head;        /* [vocab, d] */
+    const float* norm_f;            /* [d] */
+    const uint16_t* const* wqkv;    /* per layer [(hq+2hkv)*h, d] */
+    const uint16_t* const* wo;      /* per layer [d, hq*h] */
+    const uint16_t* const* wgate;   /* per layer [f, d] */
+    const uint16_t* const* wup;     /* per layer [f, d] */
+    const uint16_t* const* wdown;   /* per layer [d, f] */
+    const float* const* norm1;      /* per layer [d] */
+    const float* const* norm2;      /* per layer [d] */
+    const float* rope;              /* [max_pos, h/2, 2] (cos, sin) */
+} orc_model;
+
+typedef struct {
+    const orc_model* m;
+    int len, cap;
+    int32_t* tokens;  /* tokens whose K/V are cached */
+    double* k;        /* [layer][cap][hkv*h] */
+    double* v;
+} orc_seq;
+
+double orc_bf16(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/* y[n_out] = W[n_out, n_in] . x[n_in], W in bf16 bits. */
+static void matvec(const uint16_t* w, int n_out, int n_in, const double* x, double* y) {
+#pragma omp parallel for schedule(static)
+    for (int o = 0; o < n_out; o++) {
+        const uint16_t* row = w + (size_t)o * n_in;
+        double acc = 0.0;
+        for (int i = 0; i < n_in; i++) acc += orc_bf16(row[i]) * x[i];
+        y[o] = acc;
+    }
+}
+
+static void rmsnorm(const double* x, const float* w, int d, double eps, double* y) {
+    double ss = 0.0;
+    for (int i = 0; i < d; i++) ss += x[i] * x[i];
+    double r = 1.0 / sqrt(ss / d + eps);
+    for (int i = 0; i < d; i++) y[i] = x[i] * r * (double)w[i];
+}
+
+/* Rotate-half pairing: element i is paired with i + h/2. */
+static void rope_apply(double* vec, int h, const float* cs /* [h/2][2] */) {
+    int half = h / 2;
+    for (int i = 0; i < half; i++) {
+        double c = (double)cs[2 * i], s = (double)cs[2 * i + 1];
+        double a = vec[i], b = vec[i + half];
+        vec[i] = a * c - b * s;
+        vec[i + half] = b * c + a * s;
+    }
+}
+
+/*
+ * Softmax attention of one query over n keys: out = sum_j softmax_j(q.k_j *
+ * scale) v_j.  k and v are [n][stride] with the head's h values at the front
+ * of each row.
+ */
+void orc_attention_row(const double* q, const double* k, const double* v, int n, int stride, int h,
+                       double scale, double* out) {
+    double* s = (double*)malloc(sizeof(double) * (size_t)n);
+    double mx = -INFINITY;
+    for (int j = 0; j < n; j++) {
+        double acc = 0.0;
+        for (int i = 0; i < h; i++) acc += q[i] * k[(size_t)j * stride + i];
+        s[j] = acc * scale;
+        if (s[j] > mx) mx = s[j];
+    }
+    double z = 0.0;
+    for (int j = 0; j < n; j++) { s[j] = exp(s[j] - mx); z += s[j]; }
+    for (int i = 0; i < h; i++) {
+        double acc = 0.0;
+        for (int j = 0; j < n; j++) acc += s[j] * v[(size_t)j * stride + i];
+        out[i] = acc / z;
+    }
+    free(s);
+}
+
+orc_seq* orc_seq_new(const orc_model* m, int cap) {
+    orc_seq* s = (orc_seq*)calloc(1, sizeof(orc_seq));
+    size_t kvw = (size_t)m->n_kv_heads * m->head_dim;
+    s->m = m; s->cap = cap; s->len = 0;
+    s->tokens = (int32_t*)calloc((size_t)cap, sizeof(int32_t));
+    s->k = (double*)calloc((size_t)m->n_layers * cap * kvw, sizeof(double));
+    s->v = (double*)calloc((size_t)m->n_layers * cap * kvw, sizeof(double));
+    if (!s->tokens || !s->k || !s->v) { free(s->tokens); free(s->k); free(s->v); free(s); return NULL; }
+    return s;
+}
+
+void orc_seq_free(orc_seq* s) {
+    if (!s) return;
+    free(s->tokens); free(s->k); free(s->v); free(s);
+}
+
+int orc_seq_len(const orc_seq* s) { return s->len; }
+
+/* Forget every position >= len (used to re-evaluate another draft branch). */
+int orc_seq_truncate(orc_seq* s, int len) {
+    if (len < 0 || len > s->len) return -1;
+    s->len = len;
+    return 0;
+}
+
+/* Copy out the cached K and V of one layer/position ([hkv*h] each). */
+int orc_seq_kv(const orc_seq* s, int layer, int pos, double* k_out, double* v_out) {
+    const orc_model* m = s->m;
+    size_t kvw = (size_t)m->n_kv_heads * m->head_dim;
+    if (layer < 0 || layer >= m->n_layers || pos < 0 || pos >= s->len) return -1;
+    memcpy(k_out, s->k + ((size_t)layer * s->cap + pos) * kvw, kvw * sizeof(double));
+    memcpy(v_out, s->v + ((size_t)layer * s->cap + pos) * kvw, kvw * sizeof(double));
+    return 0;
+}
+
+/*
+ * Feed one token at position s->len: standard pre-norm decoder,
+ *   h0 = E[token]
+ *   per layer: n1 = RMSNorm(h); q,k,v = Wqkv n1; RoPE(q), RoPE(k) at pos;
+ *              h += Wo Attn(q, K[0..pos], V[0..pos])       (causal, GQA, scale 1/sqrt(head_dim))
+ *              n2 = RMSNorm(h); h += Wdown (silu(Wgate n2) * Wup n2)
+ *   logits = Wlm RMSNorm(h).
+ * Appends K/V to the cache.  `logits` (length vocab) may be NULL, in which
+ * case the LM head is skipped.  Returns 0, or -1 when out of capacity.
+ */
+int orc_seq_push(orc_seq* s, int32_t token, double* logits) {
+    const orc_model* m = s->m;
+    int d = m->d_model, hq = m->n_q_heads, hkv = m->n_kv_heads, h = m->head_dim, f = m->d_ffn;
+    int g = hq / hkv, pos = s->len;
+    size_t kvw = (size_t)hkv * h;
+    if (pos >= s->cap || pos >= m->max_pos || token < 0 || token >= m->vocab) return -1;
+    int nqkv = (hq + 2 * hkv) * h;
+    double* x = (double*)malloc(sizeof(double) * d);
+    double* nx = (double*)malloc(sizeof(double) * d);
+    double* qkv = (double*)malloc(sizeof(double) * nqkv);
+    double* att = (double*)malloc(sizeof(double) * hq * h);
+    double* proj = (double*)malloc(sizeof(double) * d);
+    double* gate = (double*)malloc(sizeof(double) * f);
+    double* up = (double*)malloc(sizeof(double) * f);
+    const float* cs = m->rope + (size_t)pos * (h / 2) * 2;
+    double scale = 1.0 / sqrt((double)h);
+
+    for (int i = 0; i < d; i++) x[i] = orc_bf16(m->embed[(size_t)token * d + i]);
+    for (int l = 0; l < m->n_layers; l++) {
+        rmsnorm(x, m->norm1[l], d, m->rms_eps, nx);
+        matvec(m->wqkv[l], nqkv, d, nx, qkv);
+        double* q = qkv;
+        double* kk = qkv + (size_t)hq * h;
+        double* vv = kk + kvw;
+        for (int i = 0; i < hq; i++) rope_apply(q + (size_t)i * h, h, cs);
+        for (int i = 0; i < hkv; i++) rope_apply(kk + (size_t)i * h, h, cs);
+        double* kc = s->k + (size_t)l * s->cap * kvw;
+        double* vc = s->v + (size_t)l * s->cap * kvw;
+        memcpy(kc + (size_t)pos * kvw, kk, kvw * sizeof(double));
+        memcpy(vc + (size_t)pos * kvw, vv, kvw * sizeof(double));
+        for (int i = 0; i < hq; i++) {
+            int j = i / g;
+            orc_attention_row(q + (size_t)i * h, kc + (size_t)j * h, vc + (size_t)j * h, pos + 1,
+                              (int)kvw, h, scale, att + (size_t)i * h);
+        }
+        matvec(m->wo[l], d, hq * h, att, proj);
+        for (int i = 0; i < d; i++) x[i] += proj[i];
+        rmsnorm(x, m->norm2[l], d, m->rms_eps, nx);
+        matvec(m->wgate[l], f, d, nx, gate);
+        matvec(m->wup[l], f, d, nx, up);
+        for (int i = 0; i < f; i++) gate[i] = gate[i] / (1.0 + exp(-gate[i])) * up[i];
+        matvec(m->wdown[l], d, f, gate, proj);
+        for (int i = 0; i < d; i++) x[i] += proj[i];
+    }
+    if (logits) {
+        rmsnorm(x, m->norm_f, d, m->rms_eps, nx);
+        matvec(m->lm_head, m->vocab, d, nx, logits);
+    }
+    s->tokens[pos] = token;
+    s->len = pos + 1;
+    free(x); free(nx); free(qkv); free(att); free(proj); free(gate); free(up);
+    return 0;
+}
+
+/* Lowest index among the largest values. */
+int orc_argmax(const double* x, int n) {
+    int best = 0;
+    for (int i = 1; i < n; i++) if (x[i] > x[best]) best = i;
+    return best;
+}
+
+/*
+ * Logits of every node of a draft tree.  The cache must hold exactly the
+ * l_cached positions before the root token.  Node r's logits are those of the
+ * plain causal model fed cached-prefix + the tokens on the path root..r: the
+ * tree is walked depth-first by truncating the sequence back to the parent
+ * and pushing the node's token.  On return the cache is back at l_cached.
+ * logits is [n_nodes][vocab].
+ */
+int orc_tree_logits(orc_seq* s, int n_nodes, const int32_t* tok, const int32_t* parent, double* logits) {
+    int base = s->len;
+    int V = s->m->vocab;
+    for (int r = 0; r < n_nodes; r++) {
+        /* path root..r */
+        int path[80], np_ = 0;
+        for (int c = r; c >= 0; c = parent[c]) { if (np_ >= 80) return -1; path[np_++] = c; }
+        if (orc_seq_truncate(s, base) != 0) return -1;
+        for (int j = np_ - 1; j >= 0; j--) {
+            double* out = (j == 0) ? logits + (size_t)r * V : NULL;
+            if (orc_seq_push(s, tok[path[j]], out) != 0) return -1;
+        }
+    }
+    return orc_seq_truncate(s, base);
+}
+
+/* ----------------------------------------------------------------- accept */
+
+/*
+ * Greedy acceptance given each node's greedy choice (arg[r] = argmax of node
+ * r's logits, lowest id on ties).  Walk from the root: the model's choice g
+ * at the current node is emitted; if a child carries exactly g the walk moves
+ * there (the draft token is accepted), otherwise it stops.  Returns the
+ * number of accepted draft tokens a; out_tok[0..a] are the a+1 emitted
+ * tokens, path[0..a] the nodes visited (root first).
+ */
+int orc_accept_greedy(int n_nodes, const int32_t* tok, const int32_t* parent, const int32_t* arg,
+                      int32_t* out_tok, int32_t* path) {
+    int cur = 0, a = 0;
+    path[0] = 0;
+    for (;;) {
+        int32_t g = arg[cur];
+        out_tok[a] = g;
+        int next = -1;
+        for (int i = 1; i < n_nodes; i++)
+            if (parent[i] == cur && tok[i] == g) { next = i; break; }
+        if (next < 0) break;
+        cur = next;
+        a++;
+        path[a] = cur;
+    }
+    return a;
+}
+
+/* Philox-4x32, 10 rounds (Salmon et al., SC'11). */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; r++) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/*
+ * The uniform in [0,1) that decides the token at absolute position `position`
+ * of sequence `seq_id`: key = seed, counter = (position, draw_kind, seq_id);
+ * the first output word's top 24 bits.  draw_kind j < 7 is the acceptance
+ * test of the j-th child tried at a node, 7 is the final sample.
+ */
+double orc_uniform(uint64_t seed, uint64_t seq_id, uint32_t position, uint32_t draw_kind) {
+    uint32_t ctr[4] = {position, draw_kind, (uint32_t)seq_id, (uint32_t)(seq_id >> 32)};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t out[4];
+    orc_philox4x32_10(ctr, key, out);
+    return (double)(out[0] >> 8) * (1.0 / 16777216.0);
+}
+
+/*
+ * Rejection-sampling acceptance along a draft tree (speculative sampling
+ * with a deterministic draft, so the draft distribution is a point mass and
+ * the acceptance probability of a draft token is its target probability).
+ * At the current node: p = softmax(logits / temperature).  Children are
+ * tried in node order; child j is accepted iff u_j < p(tok_j); on a rejection
+ * p(tok_j) is set to zero and p is renormalised.  When a child is accepted
+ * the walk moves there.  When none is (or the node is a leaf) one token is
+ * drawn from the remaining p by inverse CDF in increasing token id (first id
+ * whose cumulative weight reaches u * total) and the walk ends.
+ * logits is [n_nodes][vocab]; pos[r] is node r's absolute position, so the
+ * token it decides sits at pos[r] + 1.  Returns a; out_tok[0..a], path[0..a]
+ * as for the greedy rule.  margin_out (may be NULL) receives the smallest
+ * distance between a uniform and the threshold it was compared with, as a
+ * probability, so callers can flag decisions too close to call.
+ */
+int orc_accept_stochastic(int n_nodes, int vocab, const int32_t* tok, const int32_t* parent,
+                          const int32_t* pos, const double* logits, double temperature, uint64_t seed,
+                          uint64_t seq_id, int32_t* out_tok, int32_t* path, double* margin_out) {
+    double* w = (double*)malloc(sizeof(double) * (size_t)vocab);
+    int cur = 0, a = 0;
+    double margin = 1.0;
+    path[0] = 0;
+    for (;;) {
+        const double* lg = logits + (size_t)cur * vocab;
+        double mx = -INFINITY;
+        for (int i = 0; i < vocab; i++) if (lg[i] > mx) mx = lg[i];
+        for (int i = 0; i < vocab; i++) w[i] = exp((lg[i] - mx) / temperature);
+        uint32_t position = (uint32_t)(pos[cur] + 1);
+        int next = -1, tried = 0;
+        for (int i = 1; i < n_nodes && next < 0; i++) {
+            if (parent[i] != cur) continue;
+            double z = 0.0;
+            for (int t = 0; t < vocab; t++) z += w[t];
+            double p = w[tok[i]] / z;
+            double u = orc_uniform(seed, seq_id, position, (uint32_t)tried);
+            if (fabs(u - p) < margin) margin = fabs(u - p);
+            if (u < p) next = i;
+            else w[tok[i]] = 0.0;
+            tried++;
+        }
+        if (next >= 0) {
+            out_tok[a] = tok[next];
+            cur = next;
+            a++;
+            path[a] = cur;
+            continue;
+        }
+        double z = 0.0;
+        for (int t = 0; t < vocab; t++) z += w[t];
+        double u = orc_uniform(seed, seq_id, position, 7u);
+        double target = u * z, cum = 0.0;
+        int pick = -1, last_nz = 0;
+        for (int t = 0; t < vocab; t++) {
+            if (w[t] > 0.0) last_nz = t;
+            cum += w[t];
+            if (w[t] > 0.0 && cum >= target) {
+                pick = t;
+                double lo = (cum - w[t]) / z, hi = cum / z;
+                double dm = fmin(fabs(u - lo), fabs(hi - u));
+                if (dm < margin) margin = dm;
+                break;
+            }
+        }
+        if (pick < 0) pick = last_nz;
+        out_tok[a] = pick;
+        break;
+    }
+    if (margin_out) *margin_out = margin;
+    free(w);
+    return a;
+}
