@@ -1,0 +1,222 @@
+/*
+ * histospec.h -- C ABI of the history-drafted speculative decoding hot path for AMD MI355X (gfx950).
+ *
+ * One decode iteration of the HistoSpec rollout engine ("History Rhymes", arXiv 2508.18588, Sec. 5.2-5.4 and
+ * Sec. 2.2) is four calls enqueued on one HIP stream, with no host synchronisation in between:
+ *
+ *     hs_draft      every in-flight response matches its last generated tokens against its previous-epoch
+ *                   response and takes the following tokens as draft              (Sec. 5.2, Sec. 5.4)
+ *     hs_verify     the target decoder computes the logits of all draft positions in one forward pass over
+ *                   the paged KV cache                                            (Sec. 2.2, Sec. 5.2)
+ *     hs_accept     the valid draft tokens are kept (greedy comparison or rejection sampling), plus one token
+ *                   from the model itself                                         (Sec. 2.2)
+ *     hs_kv_commit  sequence length, KV cache, pattern tail and speculation window move forward by what was
+ *                   accepted                                                      (Sec. 5.4 window rule)
+ *
+ * Conventions
+ *   - Every pointer marked DEVICE is device memory allocated by the caller (e.g. through PyTorch) that outlives
+ *     the call; the library allocates no device memory, creates no stream and never synchronises one (except
+ *     hs_poll_error).  HOST pointers are read during the call only.
+ *   - All calls return an hs_status.  Errors the host can see (NULL pointers, sizes beyond hs_limits, missing
+ *     workspace) are returned immediately and nothing is launched.  Conditions only the device can see (a
+ *     sequence that outgrows its block table) set a sticky device error word, skip the offending sequence's
+ *     writes, and are reported by hs_poll_error.
+ *   - hs_stream is a hipStream_t passed as an opaque pointer (NULL = the null stream).
+ *   - Token ids, positions and indices are int32.  bf16 means the upper 16 bits of an IEEE fp32.
+ *
+ * Sequence model.  Sequence b has n_b = seq_len[b] committed tokens (prompt + response so far).  The KV cache
+ * holds positions 0 .. n_b-2; the newest committed token (the "root", position L_b = n_b-1) gets its K/V from
+ * the next hs_verify.  A sequence with budget_left[b] <= 0 is finished and contributes no rows.
+ *
+ * Rows.  hs_draft flattens the batch into M = sum_b n_nodes_b rows; row_off[b] .. row_off[b+1] are sequence b's
+ * draft-tree nodes: node 0 is the root, nodes 1.. are draft tokens in creation order (candidate 0's chain, then
+ * for each later candidate the part after its shared prefix).  M is known on the device only (row_off[batch]).
+ */
+#ifndef HISTOSPEC_H
+#define HISTOSPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hs_ctx hs_ctx;
+typedef void* hs_stream;
+
+typedef enum hs_status {
+    HS_OK = 0,
+    HS_ERR_INVALID_ARG = -1, /* NULL / out-of-range argument */
+    HS_ERR_CAPACITY = -2,    /* exceeds hs_limits or the bound workspace */
+    HS_ERR_UNSUPPORTED = -3, /* model shape or option this build has no kernel for */
+    HS_ERR_HIP = -4          /* a HIP runtime call failed; see hs_last_error */
+} hs_status;
+
+/* Device error word bits (hs_poll_error). */
+enum { HS_DEV_BLOCK_TABLE_OVERFLOW = 1, HS_DEV_POSITION_OVERFLOW = 2, HS_DEV_ROW_OVERFLOW = 4 };
+
+enum { HS_K_FIXED = 0, HS_K_MATCHLEN = 1, HS_K_AIMD = 2 }; /* hs_policy.k_mode */
+enum { HS_ACCEPT_GREEDY = 0, HS_ACCEPT_REJECTION = 1 };    /* hs_accept_args.mode */
+enum { HS_FLAG_REFERENCE_KERNELS = 1 };                    /* hs_set_flags: plain (slow) GEMM/attention kernels */
+
+/* Pre-norm decoder: RMSNorm, rotary embedding (pairs i, i + head_dim/2), grouped-query attention with scale
+ * 1/sqrt(head_dim), SwiGLU feed-forward, untied LM head, no biases. */
+typedef struct hs_model_desc {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t kv_block; /* tokens per KV page; must be 16 */
+    float rms_eps;
+} hs_model_desc;
+
+/* Weights.  Matrices are bf16, row-major [out_features, in_features].  The per-layer members are HOST arrays
+ * of n_layers DEVICE pointers (copied by hs_create). */
+typedef struct hs_weights {
+    const void* embed;          /* DEVICE bf16 [vocab, d_model] */
+    const void* lm_head;        /* DEVICE bf16 [vocab, d_model] */
+    const float* norm_f;        /* DEVICE f32 [d_model] */
+    const void* const* wqkv;    /* bf16 [(n_q_heads + 2 n_kv_heads) head_dim, d_model]: q rows, then k, then v */
+    const void* const* wo;      /* bf16 [d_model, n_q_heads head_dim] */
+    const void* const* wgate;   /* bf16 [d_ffn, d_model] */
+    const void* const* wup;     /* bf16 [d_ffn, d_model] */
+    const void* const* wdown;   /* bf16 [d_model, d_ffn] */
+    const float* const* norm1;  /* f32 [d_model], attention pre-norm */
+    const float* const* norm2;  /* f32 [d_model], feed-forward pre-norm */
+    const float* rope_cs;       /* DEVICE f32 [max_pos, head_dim/2, 2] = (cos, sin) of position * inv_freq */
+} hs_weights;
+
+typedef struct hs_limits {
+    int32_t max_batch;          /* sequences in flight */
+    int32_t k_max;              /* longest draft chain, 0..32 */
+    int32_t c_max;              /* history candidates per sequence, 1 or 2; 1 + c_max*k_max <= 64 nodes, and
+                                   (n_q_heads / n_kv_heads) * (1 + c_max*k_max) <= 256 query rows per KV head */
+    int32_t max_rows;           /* capacity of the per-row arrays, >= max_batch * (1 + c_max * k_max) */
+    int32_t max_blocks_per_seq; /* row length of block_table */
+    int32_t max_pos;            /* rows of rope_cs; no position may reach it.  A history candidate is scanned
+                                   up to max_pos + 32 tokens */
+    int32_t w_max;              /* row length of the pattern tail, 1..32 */
+} hs_limits;
+
+/* Paged KV cache (DEVICE, bf16, zero-initialised by the caller).
+ *   k: [n_layers][n_blocks][n_kv_heads][kv_block][head_dim]
+ *   v: [n_layers][n_blocks][n_kv_heads][head_dim][kv_block]   (token index fastest)
+ * Position t of sequence b lives in page block_table[b][t / kv_block], slot t % kv_block. */
+typedef struct hs_kv_cache {
+    void* k;
+    void* v;
+    int32_t n_blocks;
+} hs_kv_cache;
+
+/* Per-sequence state, DEVICE arrays of max_batch entries (caller-owned, updated by hs_kv_commit). */
+typedef struct hs_seq_state {
+    int32_t batch;            /* HOST: sequences in this batch, <= max_batch */
+    int32_t* seq_len;         /* n_b */
+    const int32_t* block_table; /* [batch][max_blocks_per_seq], filled by the caller for the sequence's maximum length */
+    int32_t* tail;            /* [batch][w_max]: last committed tokens, right-aligned */
+    int32_t* tail_len;        /* valid entries at the right end of tail[b] */
+    int32_t* k_state;         /* speculation window (HS_K_AIMD) */
+    int32_t* budget_left;     /* response tokens the sequence may still emit */
+    const uint64_t* seq_id;   /* random-stream identity of the sequence */
+    int32_t* tokens;          /* optional [batch][tokens_stride]: committed tokens are also appended here at n_b */
+    int32_t tokens_stride;
+    uint64_t* counters;       /* optional [4]: sequence-steps, drafted, accepted, emitted tokens (accumulated) */
+} hs_seq_state;
+
+/* Draft policy (Sec. 5.4).  Pattern = the last `window` committed tokens; a match must cover at least m_min
+ * of them.  HS_K_FIXED drafts k_fixed tokens, HS_K_MATCHLEN as many as matched (clamped to 1..k_max),
+ * HS_K_AIMD k_state[b] tokens; all are cut by the history's end and by budget_left - 1.  hs_kv_commit applies
+ * the window rule: +aimd_inc up to aimd_cap when every drafted token on the path was accepted, aimd_reset on
+ * a rejection, unchanged when nothing was drafted. */
+typedef struct hs_policy {
+    int32_t window, m_min;
+    int32_t k_mode, k_fixed, k_max;
+    int32_t aimd_inc, aimd_cap, aimd_reset;
+} hs_policy;
+
+/* History of the previous epoch.  Candidate c of sequence b is hist[hist_off[b*n_cand+c] .. hist_off[b*n_cand+c+1]).
+ * The caller prepends the last window-1 prompt tokens to each response so the response start is matchable. */
+typedef struct hs_draft_args {
+    int32_t n_cand;           /* 1..c_max */
+    const int32_t* hist;      /* DEVICE */
+    const int32_t* hist_off;  /* DEVICE [batch*n_cand + 1] */
+    hs_policy policy;
+} hs_draft_args;
+
+/* One iteration's arrays (DEVICE, caller-owned).  Sizes: per-candidate arrays batch*c_max, per-row arrays
+ * max_rows, per-sequence arrays max_batch. */
+typedef struct hs_step {
+    int32_t* draft_start;  /* [batch*n_cand] index in the candidate's history of the first draft token, -1 = no match */
+    int32_t* match_len;    /* [batch*n_cand] matched pattern length (0 = none) */
+    int32_t* draft_len;    /* [batch*n_cand] draft tokens taken from that candidate */
+    int32_t* row_off;      /* [batch+1] */
+    int32_t* tok;          /* [M] token of each node */
+    int32_t* pos;          /* [M] absolute position (rotary position) = L_b + depth */
+    int32_t* parent;       /* [M] parent node index within the sequence, -1 for the root */
+    uint64_t* anc_mask;    /* [M] bit i: node i of the same sequence is this node or an ancestor */
+    int32_t* row2seq;      /* [M] */
+    float* logits;         /* optional [max_rows][vocab]; NULL keeps logits in the workspace */
+    int32_t* argmax;       /* [M] lowest index of the largest logit */
+    int32_t* accept_len;   /* [batch] accepted draft tokens a_b */
+    int32_t* n_out;        /* [batch] emitted tokens (a_b + 1; 0 for a finished sequence) */
+    int32_t* out_tok;      /* [batch][k_max+1] emitted tokens */
+    int32_t* path_row;     /* [batch][k_max+1] node index of the root and of each accepted node */
+} hs_step;
+
+typedef struct hs_accept_args {
+    int32_t mode;
+    float temperature;  /* HS_ACCEPT_REJECTION only, > 0 */
+    uint64_t seed;      /* Philox key */
+} hs_accept_args;
+
+/* Validates the shape and copies the descriptors.  Supported: head_dim 64 or 128, kv_block 16, n_q_heads a
+ * multiple of n_kv_heads with at most 8 query heads per KV head, d_model / d_ffn / n_q_heads*head_dim multiples
+ * of 64. */
+hs_status hs_create(const hs_model_desc* desc, const hs_weights* weights, const hs_limits* limits, hs_ctx** out);
+void hs_destroy(hs_ctx* ctx);
+const char* hs_last_error(const hs_ctx* ctx);
+hs_status hs_set_flags(hs_ctx* ctx, uint32_t flags);
+
+/* Scratch the kernels need (activations, split-KV partials, logits).  The caller allocates at least
+ * hs_workspace_bytes(ctx) DEVICE bytes, 256-byte aligned, zero-filled, and binds them before the first step. */
+size_t hs_workspace_bytes(const hs_ctx* ctx);
+hs_status hs_bind_workspace(hs_ctx* ctx, void* dev_ptr, size_t bytes);
+
+/* Longest-suffix-match draft (Sec. 5.2; pattern backoff of Sec. 5.4 == longest match capped at `window`,
+ * at least m_min; leftmost on ties).  Writes draft_start/match_len/draft_len, builds the node arrays and
+ * row_off.  Reads seq.tail/tail_len/seq_len/k_state/budget_left. */
+hs_status hs_draft(hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step, hs_stream stream);
+
+/* One target-model forward pass over all M rows (Sec. 2.2).  Writes every row's K/V into the cache at slot
+ * L_b + node index, attends over positions [0, L_b) plus the node's ancestors-or-self, and writes
+ * step.argmax and the logits (step.logits, or the workspace if NULL). */
+hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* seq, hs_step* step, hs_stream stream);
+
+/* Acceptance (Sec. 2.2).  Greedy: follow children whose token equals the parent's argmax.  Rejection: accept
+ * child j at a node with probability p(tok), p = softmax(logits/temperature) with earlier rejected tokens
+ * removed; finish with one inverse-CDF sample (token-id order).  Uniforms: Philox-4x32-10, key = seed, counter
+ * = (position of the token being decided, j or 7 for the final sample, seq_id lo, seq_id hi), word 0 >> 8. */
+hs_status hs_accept(hs_ctx* ctx, const hs_accept_args* args, const hs_seq_state* seq, hs_step* step, hs_stream stream);
+
+/* Moves accepted nodes' K/V to consecutive slots L_b+1.. (a no-op for a chain), then seq_len += n_out,
+ * budget_left -= n_out, tail/tokens/k_state/counters updated. */
+hs_status hs_kv_commit(hs_ctx* ctx, const hs_kv_cache* cache, hs_seq_state* seq, const hs_step* step,
+                       const hs_policy* policy, hs_stream stream);
+
+/* Synchronises `stream`, returns and clears the sticky device error word. */
+hs_status hs_poll_error(hs_ctx* ctx, hs_stream stream, uint32_t* error_bits);
+
+/* Debug view of workspace buffers, valid after hs_verify: 0 final hidden state bf16 [max_rows][d_model]
+ * (after the last RMSNorm), 1 last layer's queries bf16 [max_rows][n_q_heads*head_dim] (after rotation),
+ * 2 last layer's attention output bf16 (same shape), 3 logits f32 [max_rows][vocab]. */
+hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size_t* bytes);
+
+/* Timing of the most recent hs_verify: with hs_set_profile(ctx, 1) every kernel launch is bracketed by HIP events
+ * on the call's stream; hs_get_profile waits for the call and returns total milliseconds and launch counts per
+ * class: 0 attention kernel, 1 projection GEMMs (QKV, O, gate/up, down), 2 LM-head GEMM, 3 everything else
+ * (norms, rotary/KV write, split-KV merge, argmax), 4 the whole call. */
+hs_status hs_set_profile(hs_ctx* ctx, int32_t enabled);
+hs_status hs_get_profile(hs_ctx* ctx, float ms[5], int32_t launches[5]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HISTOSPEC_H */

@@ -1,0 +1,205 @@
+"""Python binding of libhistospec (history-drafted speculative decoding on MI355X).
+
+Argument marshalling only: every step of the path (draft, verify, accept, KV
+commit) runs in the HIP kernels behind the C ABI declared in
+`include/histospec.h`.  PyTorch is used by callers for device memory and
+streams; nothing here computes on tensors.  If the shared library has not been
+built the import of the binding fails loudly -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+_CSRC = os.path.join(_HERE, "csrc")
+LIB_PATH = os.path.join(_HERE, "libhistospec.so")
+
+HS_OK, HS_ERR_INVALID_ARG, HS_ERR_CAPACITY, HS_ERR_UNSUPPORTED, HS_ERR_HIP = 0, -1, -2, -3, -4
+HS_DEV_BLOCK_TABLE_OVERFLOW, HS_DEV_POSITION_OVERFLOW, HS_DEV_ROW_OVERFLOW = 1, 2, 4
+HS_K_FIXED, HS_K_MATCHLEN, HS_K_AIMD = 0, 1, 2
+HS_ACCEPT_GREEDY, HS_ACCEPT_REJECTION = 0, 1
+HS_FLAG_REFERENCE_KERNELS = 1
+
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def sources():
+    return sorted(os.path.join(_CSRC, f) for f in os.listdir(_CSRC) if f.endswith(".hip"))
+
+
+def build(force: bool = True) -> str:
+    """Compile every HIP source for gfx950 into libhistospec.so (in-tree)."""
+    srcs = sources()
+    deps = srcs + [os.path.join(_CSRC, "hs_internal.h"), os.path.join(_ROOT, "include", "histospec.h")]
+    if not force and os.path.exists(LIB_PATH) and all(os.path.getmtime(LIB_PATH) >= os.path.getmtime(d) for d in deps):
+        return LIB_PATH
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + HIPCC_FLAGS + ["-I" + os.path.join(_ROOT, "include"), "-I" + _CSRC] + srcs + ["-o", LIB_PATH]
+    subprocess.check_call(cmd, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    return LIB_PATH
+
+
+class hs_model_desc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn",
+                                         "vocab", "kv_block")] + [("rms_eps", C.c_float)]
+
+
+class hs_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("norm_f", C.c_void_p),
+                ("wqkv", C.POINTER(C.c_void_p)), ("wo", C.POINTER(C.c_void_p)), ("wgate", C.POINTER(C.c_void_p)),
+                ("wup", C.POINTER(C.c_void_p)), ("wdown", C.POINTER(C.c_void_p)),
+                ("norm1", C.POINTER(C.c_void_p)), ("norm2", C.POINTER(C.c_void_p)), ("rope_cs", C.c_void_p)]
+
+
+class hs_limits(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("max_batch", "k_max", "c_max", "max_rows", "max_blocks_per_seq", "max_pos",
+                                         "w_max")]
+
+
+class hs_kv_cache(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("n_blocks", C.c_int32)]
+
+
+class hs_seq_state(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("seq_len", C.c_void_p), ("block_table", C.c_void_p), ("tail", C.c_void_p),
+                ("tail_len", C.c_void_p), ("k_state", C.c_void_p), ("budget_left", C.c_void_p),
+                ("seq_id", C.c_void_p), ("tokens", C.c_void_p), ("tokens_stride", C.c_int32),
+                ("counters", C.c_void_p)]
+
+
+class hs_policy(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("window", "m_min", "k_mode", "k_fixed", "k_max", "aimd_inc", "aimd_cap",
+                                         "aimd_reset")]
+
+
+class hs_draft_args(C.Structure):
+    _fields_ = [("n_cand", C.c_int32), ("hist", C.c_void_p), ("hist_off", C.c_void_p), ("policy", hs_policy)]
+
+
+class hs_step(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("draft_start", "match_len", "draft_len", "row_off", "tok", "pos", "parent",
+                                          "anc_mask", "row2seq", "logits", "argmax", "accept_len", "n_out",
+                                          "out_tok", "path_row")]
+
+
+class hs_accept_args(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("temperature", C.c_float), ("seed", C.c_uint64)]
+
+
+EXPORTS = ("hs_create", "hs_destroy", "hs_last_error", "hs_set_flags", "hs_workspace_bytes", "hs_bind_workspace",
+           "hs_draft", "hs_verify", "hs_accept", "hs_kv_commit", "hs_poll_error", "hs_debug_buffer",
+           "hs_set_profile", "hs_get_profile")
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library.  Raises if it has not been built: there is no other implementation."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run __graft_entry__.build() (hipcc, gfx950) first; "
+                               "the HIP library is the only implementation of this path")
+        L = C.CDLL(LIB_PATH)
+        vp = C.c_void_p
+        L.hs_create.argtypes = [C.POINTER(hs_model_desc), C.POINTER(hs_weights), C.POINTER(hs_limits), C.POINTER(vp)]
+        L.hs_destroy.argtypes = [vp]
+        L.hs_destroy.restype = None
+        L.hs_last_error.argtypes = [vp]
+        L.hs_last_error.restype = C.c_char_p
+        L.hs_set_flags.argtypes = [vp, C.c_uint32]
+        L.hs_workspace_bytes.argtypes = [vp]
+        L.hs_workspace_bytes.restype = C.c_size_t
+        L.hs_bind_workspace.argtypes = [vp, vp, C.c_size_t]
+        L.hs_draft.argtypes = [vp, C.POINTER(hs_draft_args), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
+        L.hs_verify.argtypes = [vp, C.POINTER(hs_kv_cache), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
+        L.hs_accept.argtypes = [vp, C.POINTER(hs_accept_args), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
+        L.hs_kv_commit.argtypes = [vp, C.POINTER(hs_kv_cache), C.POINTER(hs_seq_state), C.POINTER(hs_step),
+                                   C.POINTER(hs_policy), vp]
+        L.hs_poll_error.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
+        L.hs_debug_buffer.argtypes = [vp, C.c_int32, C.POINTER(vp), C.POINTER(C.c_size_t)]
+        L.hs_set_profile.argtypes = [vp, C.c_int32]
+        L.hs_get_profile.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+        _lib = L
+    return _lib
+
+
+class HsError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"histospec status {status}: {message}")
+        self.status = status
+
+
+def _check(ctx, status: int):
+    if status != HS_OK:
+        msg = lib().hs_last_error(ctx).decode() if ctx else ""
+        raise HsError(status, msg)
+
+
+# Same names as the C entry points; each takes the ctypes structs above.
+
+def hs_create(desc: hs_model_desc, weights: hs_weights, limits: hs_limits):
+    ctx = C.c_void_p()
+    st = lib().hs_create(C.byref(desc), C.byref(weights), C.byref(limits), C.byref(ctx))
+    if st != HS_OK:
+        raise HsError(st, "hs_create rejected the model shape, weights or limits")
+    return ctx
+
+
+def hs_destroy(ctx):
+    lib().hs_destroy(ctx)
+
+
+def hs_set_flags(ctx, flags: int):
+    _check(ctx, lib().hs_set_flags(ctx, flags))
+
+
+def hs_workspace_bytes(ctx) -> int:
+    return lib().hs_workspace_bytes(ctx)
+
+
+def hs_bind_workspace(ctx, dev_ptr: int, nbytes: int):
+    _check(ctx, lib().hs_bind_workspace(ctx, dev_ptr, nbytes))
+
+
+def hs_draft(ctx, args: hs_draft_args, seq: hs_seq_state, step: hs_step, stream=None):
+    _check(ctx, lib().hs_draft(ctx, C.byref(args), C.byref(seq), C.byref(step), stream))
+
+
+def hs_verify(ctx, cache: hs_kv_cache, seq: hs_seq_state, step: hs_step, stream=None):
+    _check(ctx, lib().hs_verify(ctx, C.byref(cache), C.byref(seq), C.byref(step), stream))
+
+
+def hs_accept(ctx, args: hs_accept_args, seq: hs_seq_state, step: hs_step, stream=None):
+    _check(ctx, lib().hs_accept(ctx, C.byref(args), C.byref(seq), C.byref(step), stream))
+
+
+def hs_kv_commit(ctx, cache: hs_kv_cache, seq: hs_seq_state, step: hs_step, policy: hs_policy, stream=None):
+    _check(ctx, lib().hs_kv_commit(ctx, C.byref(cache), C.byref(seq), C.byref(step), C.byref(policy), stream))
+
+
+def hs_poll_error(ctx, stream=None) -> int:
+    bits = C.c_uint32()
+    _check(ctx, lib().hs_poll_error(ctx, stream, C.byref(bits)))
+    return bits.value
+
+
+def hs_debug_buffer(ctx, which: int):
+    p, n = C.c_void_p(), C.c_size_t()
+    _check(ctx, lib().hs_debug_buffer(ctx, which, C.byref(p), C.byref(n)))
+    return p.value, n.value
+
+
+def hs_set_profile(ctx, enabled: bool):
+    _check(ctx, lib().hs_set_profile(ctx, int(enabled)))
+
+
+def hs_get_profile(ctx):
+    ms = (C.c_float * 5)()
+    n = (C.c_int32 * 5)()
+    _check(ctx, lib().hs_get_profile(ctx, ms, n))
+    return list(ms), list(n)

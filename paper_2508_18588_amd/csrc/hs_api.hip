@@ -1,0 +1,335 @@
+// C-ABI entry points: argument validation, workspace layout, and the launch sequence of one decode iteration.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "hs_internal.h"
+
+namespace {
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+hs_status fail(hs_ctx* ctx, hs_status code, const char* msg) {
+    if (ctx) ctx->err = msg;
+    return code;
+}
+
+void layout_workspace(hs_ctx* ctx) {
+    const hs_model_desc& d = ctx->desc;
+    const hs_limits& l = ctx->lim;
+    hs_workspace_layout& w = ctx->lay;
+    const size_t M = (size_t)l.max_rows;
+    const size_t qh = (size_t)d.n_q_heads * d.head_dim;
+    const size_t nqkv = (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    w.err = take(256);
+    w.x = take(M * d.d_model * 4);
+    w.xn = take(M * d.d_model * 2);
+    w.qkv = take(M * nqkv * 4);
+    w.q = take(M * qh * 2);
+    w.attn = take(M * qh * 2);
+    w.act = take(M * (size_t)d.d_ffn * 2);
+    w.part_o = take(M * d.n_q_heads * (size_t)ctx->max_parts * d.head_dim * 4);
+    w.part_ml = take(M * d.n_q_heads * (size_t)ctx->max_parts * 2 * 4);
+    w.logits = take(M * (size_t)d.vocab * 4);
+    w.draft_best = take((size_t)l.max_batch * l.c_max * ctx->max_segs * 8);
+    w.total = off;
+}
+
+struct Prof {
+    hs_ctx* ctx;
+    hipStream_t st;
+    void begin(int cls) {
+        if (!ctx->profile) return;
+        if (ctx->ev_used + 2 > (int)ctx->ev.size()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { ctx->profile = 0; return; }
+            ctx->ev.push_back(a);
+            ctx->ev.push_back(b);
+            ctx->ev_class.push_back(cls);
+        }
+        ctx->ev_class[ctx->ev_used / 2] = cls;
+        (void)hipEventRecord(ctx->ev[ctx->ev_used], st);
+    }
+    void end() {
+        if (!ctx->profile) return;
+        (void)hipEventRecord(ctx->ev[ctx->ev_used + 1], st);
+        ctx->ev_used += 2;
+    }
+};
+
+bool step_ok(const hs_step* s) {
+    return s && s->draft_start && s->match_len && s->draft_len && s->row_off && s->tok && s->pos && s->parent &&
+           s->anc_mask && s->row2seq && s->argmax && s->accept_len && s->n_out && s->out_tok && s->path_row;
+}
+
+bool seq_ok(const hs_ctx* ctx, const hs_seq_state* s) {
+    return s && s->batch >= 1 && s->batch <= ctx->lim.max_batch && s->seq_len && s->block_table && s->tail &&
+           s->tail_len && s->k_state && s->budget_left && s->seq_id && (!s->tokens || s->tokens_stride > 0);
+}
+
+bool policy_ok(const hs_ctx* ctx, const hs_policy* p) {
+    return p && p->window >= 1 && p->window <= ctx->lim.w_max && p->m_min >= 1 && p->m_min <= p->window &&
+           p->k_mode >= HS_K_FIXED && p->k_mode <= HS_K_AIMD && p->k_max >= 0 && p->k_max <= ctx->lim.k_max &&
+           p->k_fixed >= 0 && p->aimd_inc >= 0 && p->aimd_cap >= 0 && p->aimd_reset >= 0;
+}
+
+bool cache_ok(const hs_kv_cache* c) { return c && c->k && c->v && c->n_blocks >= 1; }
+
+}  // namespace
+
+extern "C" {
+
+hs_status hs_create(const hs_model_desc* desc, const hs_weights* w, const hs_limits* lim, hs_ctx** out) {
+    if (!desc || !w || !lim || !out) return HS_ERR_INVALID_ARG;
+    *out = nullptr;
+    const hs_model_desc& d = *desc;
+    if (d.n_layers < 1 || d.d_model < 1 || d.n_q_heads < 1 || d.n_kv_heads < 1 || d.d_ffn < 1 || d.vocab < 1 ||
+        !(d.rms_eps > 0.f))
+        return HS_ERR_INVALID_ARG;
+    if (d.kv_block != 16 || (d.head_dim != 64 && d.head_dim != 128) || d.n_q_heads % d.n_kv_heads != 0 ||
+        d.n_q_heads / d.n_kv_heads > 8 || d.d_model % 64 != 0 || d.d_ffn % 64 != 0 ||
+        (d.n_q_heads * d.head_dim) % 64 != 0)
+        return HS_ERR_UNSUPPORTED;
+    const hs_limits& l = *lim;
+    if (l.max_batch < 1 || l.k_max < 0 || l.k_max > 32 || l.c_max < 1 || l.c_max > 2 || l.max_blocks_per_seq < 1 ||
+        l.max_pos < 1 || l.w_max < 1 || l.w_max > 32 || l.max_rows < 1)
+        return HS_ERR_INVALID_ARG;
+    const int nodes = 1 + l.c_max * l.k_max;
+    if (nodes > HS_MAX_NODES || (d.n_q_heads / d.n_kv_heads) * nodes > 256) return HS_ERR_UNSUPPORTED;
+    if ((long long)l.max_rows < (long long)l.max_batch * nodes) return HS_ERR_CAPACITY;
+    if (!w->embed || !w->lm_head || !w->norm_f || !w->rope_cs || !w->wqkv || !w->wo || !w->wgate || !w->wup ||
+        !w->wdown || !w->norm1 || !w->norm2)
+        return HS_ERR_INVALID_ARG;
+    for (int i = 0; i < d.n_layers; i++)
+        if (!w->wqkv[i] || !w->wo[i] || !w->wgate[i] || !w->wup[i] || !w->wdown[i] || !w->norm1[i] || !w->norm2[i])
+            return HS_ERR_INVALID_ARG;
+    hs_ctx* ctx = new (std::nothrow) hs_ctx();
+    if (!ctx) return HS_ERR_CAPACITY;
+    ctx->desc = d;
+    ctx->lim = l;
+    ctx->embed = (const bf16_t*)w->embed;
+    ctx->lm_head = (const bf16_t*)w->lm_head;
+    ctx->norm_f = w->norm_f;
+    ctx->rope_cs = w->rope_cs;
+    for (int i = 0; i < d.n_layers; i++) {
+        ctx->wqkv.push_back((const bf16_t*)w->wqkv[i]);
+        ctx->wo.push_back((const bf16_t*)w->wo[i]);
+        ctx->wgate.push_back((const bf16_t*)w->wgate[i]);
+        ctx->wup.push_back((const bf16_t*)w->wup[i]);
+        ctx->wdown.push_back((const bf16_t*)w->wdown[i]);
+        ctx->norm1.push_back(w->norm1[i]);
+        ctx->norm2.push_back(w->norm2[i]);
+    }
+    // Split-KV partition length: a tuning knob (multiple of 32 keys); results are identical across calls for a
+    // fixed value.
+    ctx->att_part = HS_ATT_PART_DEFAULT;
+    if (const char* e = std::getenv("HS_ATT_PART")) {
+        int v = std::atoi(e);
+        if (v >= 32 && v % 32 == 0) ctx->att_part = v;
+    }
+    const long long max_keys = (long long)l.max_blocks_per_seq * 16;
+    ctx->max_parts = (int)((max_keys + ctx->att_part - 1) / ctx->att_part);
+    ctx->max_segs = (l.max_pos + 32 + HS_DRAFT_SEG - 1) / HS_DRAFT_SEG;
+    layout_workspace(ctx);
+    *out = ctx;
+    return HS_OK;
+}
+
+void hs_destroy(hs_ctx* ctx) {
+    if (!ctx) return;
+    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+    delete ctx;
+}
+
+const char* hs_last_error(const hs_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+hs_status hs_set_flags(hs_ctx* ctx, uint32_t flags) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    if (flags & ~(uint32_t)HS_FLAG_REFERENCE_KERNELS) return fail(ctx, HS_ERR_INVALID_ARG, "unknown flag");
+    ctx->flags = flags;
+    return HS_OK;
+}
+
+size_t hs_workspace_bytes(const hs_ctx* ctx) { return ctx ? ctx->lay.total : 0; }
+
+hs_status hs_bind_workspace(hs_ctx* ctx, void* dev_ptr, size_t bytes) {
+    if (!ctx || !dev_ptr) return HS_ERR_INVALID_ARG;
+    if (((uintptr_t)dev_ptr & 255u) != 0) return fail(ctx, HS_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    if (bytes < ctx->lay.total) return fail(ctx, HS_ERR_CAPACITY, "workspace smaller than hs_workspace_bytes");
+    ctx->ws = (char*)dev_ptr;
+    ctx->ws_bytes = bytes;
+    return HS_OK;
+}
+
+hs_status hs_draft(hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step, hs_stream stream) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
+    if (!args || !args->hist || !args->hist_off) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft: null history");
+    if (args->n_cand < 1 || args->n_cand > ctx->lim.c_max) return fail(ctx, HS_ERR_CAPACITY, "hs_draft: n_cand");
+    if (!policy_ok(ctx, &args->policy)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft: policy out of range");
+    if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft: sequence state");
+    if (!step_ok(step)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft: step arrays");
+    hs_launch_draft(ctx, args, seq, step, (hipStream_t)stream);
+    if (hipGetLastError() != hipSuccess) return fail(ctx, HS_ERR_HIP, "hs_draft: launch failed");
+    return HS_OK;
+}
+
+hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* seq, hs_step* step, hs_stream stream) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
+    if (!cache_ok(cache)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_verify: cache");
+    if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_verify: sequence state");
+    if (!step_ok(step)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_verify: step arrays");
+    hipStream_t st = (hipStream_t)stream;
+    const hs_model_desc& d = ctx->desc;
+    const int m_max = ctx->lim.max_rows;
+    const int32_t* m_dev = step->row_off + seq->batch;
+    float* x = (float*)(ctx->ws + ctx->lay.x);
+    bf16_t* xn = (bf16_t*)(ctx->ws + ctx->lay.xn);
+    float* qkv = (float*)(ctx->ws + ctx->lay.qkv);
+    bf16_t* q = (bf16_t*)(ctx->ws + ctx->lay.q);
+    bf16_t* attn = (bf16_t*)(ctx->ws + ctx->lay.attn);
+    bf16_t* act = (bf16_t*)(ctx->ws + ctx->lay.act);
+    float* logits = step->logits ? step->logits : (float*)(ctx->ws + ctx->lay.logits);
+    const int qh = d.n_q_heads * d.head_dim;
+    const int nqkv = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+
+    ctx->ev_used = 0;
+    Prof whole{ctx, st}, pr{ctx, st};
+    whole.begin(4);
+    int whole_slot = ctx->ev_used;
+    if (ctx->profile) ctx->ev_used += 2;  // the whole-call pair is closed at the end
+
+    pr.begin(3);
+    hs_launch_embed(ctx, step, seq->batch, x, st);
+    pr.end();
+    for (int l = 0; l < d.n_layers; l++) {
+        pr.begin(3);
+        hs_launch_rmsnorm(ctx, x, ctx->norm1[l], xn, m_dev, st);
+        pr.end();
+        pr.begin(1);
+        hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->wqkv[l], nullptr, qkv, m_dev, m_max, nqkv, d.d_model, st);
+        pr.end();
+        pr.begin(3);
+        hs_launch_rope_kv(ctx, l, cache, seq, step, qkv, q, st);
+        pr.end();
+        pr.begin(0);
+        hs_launch_attention(ctx, l, cache, seq, step, q, attn, st);
+        pr.end();
+        pr.begin(3);
+        hs_launch_attention_merge(ctx, seq, step, attn, st);
+        pr.end();
+        pr.begin(1);
+        hs_launch_gemm(ctx, HS_EPI_ADD_F32, attn, ctx->wo[l], nullptr, x, m_dev, m_max, d.d_model, qh, st);
+        pr.end();
+        pr.begin(3);
+        hs_launch_rmsnorm(ctx, x, ctx->norm2[l], xn, m_dev, st);
+        pr.end();
+        pr.begin(1);
+        hs_launch_gemm(ctx, HS_EPI_SWIGLU_BF16, xn, ctx->wgate[l], ctx->wup[l], act, m_dev, m_max, d.d_ffn, d.d_model, st);
+        pr.end();
+        pr.begin(1);
+        hs_launch_gemm(ctx, HS_EPI_ADD_F32, act, ctx->wdown[l], nullptr, x, m_dev, m_max, d.d_model, d.d_ffn, st);
+        pr.end();
+    }
+    pr.begin(3);
+    hs_launch_rmsnorm(ctx, x, ctx->norm_f, xn, m_dev, st);
+    pr.end();
+    pr.begin(2);
+    hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->lm_head, nullptr, logits, m_dev, m_max, d.vocab, d.d_model, st);
+    pr.end();
+    pr.begin(3);
+    hs_launch_argmax(ctx, logits, step->argmax, m_dev, st);
+    pr.end();
+    if (ctx->profile) {
+        (void)hipEventRecord(ctx->ev[whole_slot + 1], st);
+    }
+    if (hipGetLastError() != hipSuccess) return fail(ctx, HS_ERR_HIP, "hs_verify: launch failed");
+    return HS_OK;
+}
+
+hs_status hs_accept(hs_ctx* ctx, const hs_accept_args* args, const hs_seq_state* seq, hs_step* step, hs_stream stream) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
+    if (!args || (args->mode != HS_ACCEPT_GREEDY && args->mode != HS_ACCEPT_REJECTION))
+        return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept: mode");
+    if (args->mode == HS_ACCEPT_REJECTION && !(args->temperature > 0.f))
+        return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept: temperature must be positive");
+    if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept: sequence state");
+    if (!step_ok(step)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept: step arrays");
+    const float* logits = step->logits ? step->logits : (const float*)(ctx->ws + ctx->lay.logits);
+    hs_launch_accept(ctx, args, seq, step, logits, (hipStream_t)stream);
+    if (hipGetLastError() != hipSuccess) return fail(ctx, HS_ERR_HIP, "hs_accept: launch failed");
+    return HS_OK;
+}
+
+hs_status hs_kv_commit(hs_ctx* ctx, const hs_kv_cache* cache, hs_seq_state* seq, const hs_step* step,
+                       const hs_policy* policy, hs_stream stream) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    if (!cache_ok(cache)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: cache");
+    if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: sequence state");
+    if (!step_ok(step)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: step arrays");
+    if (!policy_ok(ctx, policy)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: policy out of range");
+    hs_launch_commit(ctx, cache, seq, step, policy, (hipStream_t)stream);
+    if (hipGetLastError() != hipSuccess) return fail(ctx, HS_ERR_HIP, "hs_kv_commit: launch failed");
+    return HS_OK;
+}
+
+hs_status hs_poll_error(hs_ctx* ctx, hs_stream stream, uint32_t* error_bits) {
+    if (!ctx || !error_bits) return HS_ERR_INVALID_ARG;
+    if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t v = 0;
+    if (hipMemcpyAsync(&v, ctx->ws + ctx->lay.err, 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return fail(ctx, HS_ERR_HIP, "hs_poll_error: copy failed");
+    if (v != 0) {
+        uint32_t zero = 0;
+        if (hipMemcpyAsync(ctx->ws + ctx->lay.err, &zero, 4, hipMemcpyHostToDevice, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess)
+            return fail(ctx, HS_ERR_HIP, "hs_poll_error: clear failed");
+    }
+    *error_bits = v;
+    return HS_OK;
+}
+
+hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size_t* bytes) {
+    if (!ctx || !dev_ptr || !bytes || !ctx->ws) return HS_ERR_INVALID_ARG;
+    const hs_model_desc& d = ctx->desc;
+    const size_t M = (size_t)ctx->lim.max_rows, qh = (size_t)d.n_q_heads * d.head_dim;
+    switch (which) {
+        case 0: *dev_ptr = ctx->ws + ctx->lay.xn; *bytes = M * d.d_model * 2; break;
+        case 1: *dev_ptr = ctx->ws + ctx->lay.q; *bytes = M * qh * 2; break;
+        case 2: *dev_ptr = ctx->ws + ctx->lay.attn; *bytes = M * qh * 2; break;
+        case 3: *dev_ptr = ctx->ws + ctx->lay.logits; *bytes = M * (size_t)d.vocab * 4; break;
+        default: return HS_ERR_INVALID_ARG;
+    }
+    return HS_OK;
+}
+
+hs_status hs_set_profile(hs_ctx* ctx, int32_t enabled) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    ctx->profile = enabled ? 1 : 0;
+    ctx->ev_used = 0;
+    return HS_OK;
+}
+
+hs_status hs_get_profile(hs_ctx* ctx, float ms[5], int32_t launches[5]) {
+    if (!ctx || !ms || !launches) return HS_ERR_INVALID_ARG;
+    for (int i = 0; i < 5; i++) { ms[i] = 0.f; launches[i] = 0; }
+    if (!ctx->profile || ctx->ev_used < 2) return fail(ctx, HS_ERR_INVALID_ARG, "no profiled hs_verify to report");
+    if (hipEventSynchronize(ctx->ev[1]) != hipSuccess) return fail(ctx, HS_ERR_HIP, "hs_get_profile: sync failed");
+    for (int p = 0; p < ctx->ev_used / 2; p++) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, ctx->ev[2 * p], ctx->ev[2 * p + 1]) != hipSuccess)
+            return fail(ctx, HS_ERR_HIP, "hs_get_profile: elapsed time failed");
+        int c = ctx->ev_class[p];
+        ms[c] += t;
+        launches[c] += 1;
+    }
+    return HS_OK;
+}
+
+}  // extern "C"

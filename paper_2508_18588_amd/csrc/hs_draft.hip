@@ -1,0 +1,214 @@
+// History-drafted speculation, draft side (Sec. 5.2 and 5.4 of the paper): every in-flight response looks for
+// the longest suffix of its committed tokens (at most `window`, at least `m_min` tokens) inside its previous-epoch
+// response and takes the tokens that follow as its draft.
+//
+// Kernel 1 (scan): one workgroup per (history segment, candidate).  The segment plus a `window`-token halo is
+// staged in LDS with coalesced loads; every thread then tests end positions p against the pattern held in
+// registers/LDS, and the best (match length, leftmost p) is reduced with wavefront shuffles as one packed 64-bit
+// key.  Kernel 2 (build): one thread per sequence reduces the segment winners, applies the draft-length policy,
+// merges the candidates' chains into a token tree, and a workgroup-wide prefix sum over node counts yields the
+// ragged row offsets the verify step consumes.
+#include "hs_internal.h"
+
+namespace {
+
+__device__ inline unsigned long long shfl_xor_u64(unsigned long long v, int o) {
+    unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+    lo = __shfl_xor(lo, o);
+    hi = __shfl_xor(hi, o);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// key = (match length << 32) | ~p : larger is better, ties -> smaller p
+__global__ __launch_bounds__(256) void draft_scan_kernel(const int32_t* __restrict__ hist,
+                                                          const int32_t* __restrict__ hist_off, int n_cand,
+                                                          const int32_t* __restrict__ tail,
+                                                          const int32_t* __restrict__ tail_len,
+                                                          const int32_t* __restrict__ budget_left, int w_max,
+                                                          int window, int m_min, int max_segs,
+                                                          unsigned long long* __restrict__ best) {
+    __shared__ int32_t sh[HS_DRAFT_SEG + 32];
+    __shared__ int32_t pat[32];
+    __shared__ unsigned long long red[4];
+    const int seg = blockIdx.x, bc = blockIdx.y, b = bc / n_cand;
+    const int tid = threadIdx.x;
+    unsigned long long* dst = best + (size_t)bc * max_segs + seg;
+    const int off = hist_off[bc];
+    const int lh = hist_off[bc + 1] - off;
+    const int p_lo = seg * HS_DRAFT_SEG + 1;                   // end positions handled here: [p_lo, p_hi]
+    const int p_hi = min((seg + 1) * HS_DRAFT_SEG, lh - 1);
+    int n_pat = min(min(tail_len[b], window), w_max);
+    if (budget_left[b] <= 0 || p_lo > p_hi || n_pat < m_min || n_pat <= 0) {
+        if (tid == 0) *dst = 0ull;
+        return;
+    }
+    // pattern, newest token first: pat[i] = i-th token from the end
+    if (tid < n_pat) pat[tid] = tail[(size_t)b * w_max + (w_max - 1 - tid)];
+    // tokens hist[base .. p_hi) are needed: base = p_lo - window (clamped)
+    const int base = max(0, p_lo - window);
+    const int count = p_hi - base;
+    for (int i = tid; i < count; i += 256) sh[i] = hist[off + base + i];
+    __syncthreads();
+    unsigned long long k = 0ull;
+    for (int p = p_lo + tid; p <= p_hi; p += 256) {
+        int lim = min(n_pat, p);
+        int m = 0;
+        while (m < lim && sh[p - 1 - m - base] == pat[m]) m++;
+        if (m >= m_min) {
+            unsigned long long cand = ((unsigned long long)m << 32) | (0xFFFFFFFFu - (unsigned)p);
+            if (cand > k) k = cand;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        unsigned long long other = shfl_xor_u64(k, o);
+        if (other > k) k = other;
+    }
+    if ((tid & 63) == 0) red[tid >> 6] = k;
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; w++) if (red[w] > k) k = red[w];
+        *dst = k;
+    }
+}
+
+__device__ inline int block_excl_scan_256(int v, int* total, int* sw) {
+    // wavefront inclusive scan by shuffles, then the 4 wavefront totals
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();
+    if (lane == 63) sw[wave] = inc;
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; w++) before += sw[w];
+    *total = sw[0] + sw[1] + sw[2] + sw[3];
+    return before + inc - v;
+}
+
+__global__ __launch_bounds__(256) void draft_build_kernel(
+    const int32_t* __restrict__ hist, const int32_t* __restrict__ hist_off, int n_cand, int batch,
+    const unsigned long long* __restrict__ best, int max_segs, const int32_t* __restrict__ seq_len,
+    const int32_t* __restrict__ tail, int w_max, const int32_t* __restrict__ k_state,
+    const int32_t* __restrict__ budget_left, hs_policy pol, int max_blocks, int max_pos, int max_rows,
+    int32_t* __restrict__ draft_start, int32_t* __restrict__ match_len, int32_t* __restrict__ draft_len,
+    int32_t* __restrict__ row_off, int32_t* __restrict__ tok, int32_t* __restrict__ pos,
+    int32_t* __restrict__ parent, uint64_t* __restrict__ anc_mask, int32_t* __restrict__ row2seq,
+    uint32_t* __restrict__ err) {
+    __shared__ int sw[4];
+    __shared__ int carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int b0 = 0; b0 < batch; b0 += 256) {
+        const int b = b0 + threadIdx.x;
+        int nn = 0, L = 0;
+        int pstart[2] = {-1, -1}, klen[2] = {0, 0}, hoff[2] = {0, 0};
+        int shared = 0;
+        if (b < batch && budget_left[b] > 0) {
+            L = seq_len[b] - 1;
+            for (int c = 0; c < n_cand; c++) {
+                const int bc = b * n_cand + c;
+                const int off = hist_off[bc], lh = hist_off[bc + 1] - off;
+                unsigned long long k = 0ull;
+                const int nseg = (lh - 1 + HS_DRAFT_SEG - 1) / HS_DRAFT_SEG;
+                for (int s = 0; s < nseg && s < max_segs; s++) {
+                    unsigned long long v = best[(size_t)bc * max_segs + s];
+                    if (v > k) k = v;
+                }
+                int m = (int)(k >> 32);
+                int p = m > 0 ? (int)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull)) : -1;
+                int kk = 0;
+                if (m > 0) {
+                    if (pol.k_mode == HS_K_FIXED) kk = pol.k_fixed;
+                    else if (pol.k_mode == HS_K_MATCHLEN) kk = m < 1 ? 1 : m;
+                    else kk = k_state[b];
+                    kk = min(kk, pol.k_max);
+                    kk = min(kk, lh - p);
+                    kk = min(kk, budget_left[b] - 1);
+                    kk = max(kk, 0);
+                }
+                pstart[c] = p; klen[c] = kk; hoff[c] = off + (p < 0 ? 0 : p);
+                draft_start[bc] = p;
+                match_len[bc] = m;
+            }
+            if (n_cand == 2) {
+                int lim = min(klen[0], klen[1]);
+                while (shared < lim && hist[hoff[0] + shared] == hist[hoff[1] + shared]) shared++;
+            }
+            nn = 1 + klen[0] + (n_cand == 2 ? klen[1] - shared : 0);
+            // capacity: every node needs a cache slot L + i and a rotary position below max_pos
+            int cap_tokens = max_blocks * 16;
+            if (L < 0 || L + 1 > cap_tokens || L + 1 > max_pos) {
+                atomicOr(err, L + 1 > max_pos ? HS_DEV_POSITION_OVERFLOW : HS_DEV_BLOCK_TABLE_OVERFLOW);
+                nn = 0; klen[0] = klen[1] = 0; shared = 0;
+            } else if (L + nn > cap_tokens || L + 1 + max(klen[0], klen[1]) > max_pos) {
+                atomicOr(err, L + nn > cap_tokens ? HS_DEV_BLOCK_TABLE_OVERFLOW : HS_DEV_POSITION_OVERFLOW);
+                nn = 1; klen[0] = klen[1] = 0; shared = 0;
+            }
+            for (int c = 0; c < n_cand; c++) draft_len[b * n_cand + c] = klen[c];
+        } else if (b < batch) {
+            for (int c = 0; c < n_cand; c++) {
+                draft_start[b * n_cand + c] = -1;
+                match_len[b * n_cand + c] = 0;
+                draft_len[b * n_cand + c] = 0;
+            }
+        }
+        int total;
+        int excl = block_excl_scan_256(nn, &total, sw);
+        int carry = carry_s;
+        int r0 = carry + excl;
+        if (b < batch) {
+            if (r0 + nn > max_rows) { atomicOr(err, HS_DEV_ROW_OVERFLOW); nn = 0; }
+            row_off[b] = r0;
+            if (nn > 0) {
+                tok[r0] = tail[(size_t)b * w_max + (w_max - 1)];
+                pos[r0] = L; parent[r0] = -1; anc_mask[r0] = 1ull; row2seq[r0] = b;
+                // candidate 0: nodes 1..k0, a chain
+                for (int i = 1; i <= klen[0]; i++) {
+                    tok[r0 + i] = hist[hoff[0] + i - 1];
+                    pos[r0 + i] = L + i; parent[r0 + i] = i - 1;
+                    anc_mask[r0 + i] = (2ull << i) - 1ull; row2seq[r0 + i] = b;
+                }
+                // candidate 1: nodes after the shared prefix, hanging off node `shared`
+                if (n_cand == 2) {
+                    uint64_t m = (2ull << shared) - 1ull;
+                    int par = shared;
+                    for (int i = shared + 1; i <= klen[1]; i++) {
+                        int node = klen[0] + (i - shared);
+                        m |= 1ull << node;
+                        tok[r0 + node] = hist[hoff[1] + i - 1];
+                        pos[r0 + node] = L + i; parent[r0 + node] = par;
+                        anc_mask[r0 + node] = m; row2seq[r0 + node] = b;
+                        par = node;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) carry_s = carry + total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) row_off[batch] = min(carry_s, max_rows);
+}
+
+}  // namespace
+
+void hs_launch_draft(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
+                     hipStream_t st) {
+    unsigned long long* best = reinterpret_cast<unsigned long long*>(ctx->ws + ctx->lay.draft_best);
+    uint32_t* err = reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.err);
+    const hs_policy& p = args->policy;
+    dim3 grid(ctx->max_segs, seq->batch * args->n_cand);
+    hipLaunchKernelGGL(draft_scan_kernel, grid, dim3(256), 0, st, args->hist, args->hist_off, args->n_cand,
+                       seq->tail, seq->tail_len, seq->budget_left, ctx->lim.w_max, p.window, p.m_min,
+                       ctx->max_segs, best);
+    hipLaunchKernelGGL(draft_build_kernel, dim3(1), dim3(256), 0, st, args->hist, args->hist_off, args->n_cand,
+                       seq->batch, best, ctx->max_segs, seq->seq_len, seq->tail, ctx->lim.w_max, seq->k_state,
+                       seq->budget_left, p, ctx->lim.max_blocks_per_seq, ctx->lim.max_pos, ctx->lim.max_rows,
+                       step->draft_start, step->match_len, step->draft_len, step->row_off, step->tok, step->pos,
+                       step->parent, step->anc_mask, step->row2seq, err);
+}

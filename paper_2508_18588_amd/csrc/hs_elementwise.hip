@@ -1,0 +1,149 @@
+// Row-wise kernels of the verify forward pass: embedding gather, RMSNorm, rotary embedding + KV-cache write,
+// and the per-row argmax over the vocabulary.  All are bandwidth-trivial next to attention and the GEMMs; each
+// row is processed independently with a reduction order that depends only on the row's own length.
+#include "hs_internal.h"
+
+namespace {
+
+__device__ inline float block_sum_256(float v, float* red) {
+    // fixed tree: xor-shuffle inside each wavefront, then the 4 wavefront sums in order
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ embed, const int32_t* __restrict__ tok,
+                                                     const int32_t* __restrict__ m_dev, float* __restrict__ x, int d,
+                                                     int vocab) {
+    int row = blockIdx.x;
+    if (row >= *m_dev) return;
+    int t = tok[row];
+    if (t < 0 || t >= vocab) t = 0;
+    const bf16_t* e = embed + (size_t)t * d;
+    for (int i = threadIdx.x; i < d; i += 256) x[(size_t)row * d + i] = bf16_to_f32(e[i]);
+}
+
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                       bf16_t* __restrict__ out, const int32_t* __restrict__ m_dev,
+                                                       int d, float eps) {
+    __shared__ float red[4];
+    int row = blockIdx.x;
+    if (row >= *m_dev) return;
+    const float* xr = x + (size_t)row * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) { float v = xr[i]; ss += v * v; }
+    ss = block_sum_256(ss, red);
+    float r = rsqrtf(ss / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256) out[(size_t)row * d + i] = f32_to_bf16(xr[i] * r * w[i]);
+}
+
+// One workgroup per row.  Rotates q and k heads at the row's position (pairs i, i + h/2), writes q as bf16,
+// K into its page row-major and V into its page with the token index fastest.
+__global__ __launch_bounds__(256) void rope_kv_kernel(const float* __restrict__ qkv, const float* __restrict__ rope_cs,
+                                                       const int32_t* __restrict__ pos, const int32_t* __restrict__ row2seq,
+                                                       const int32_t* __restrict__ row_off,
+                                                       const int32_t* __restrict__ seq_len,
+                                                       const int32_t* __restrict__ block_table, int max_blocks,
+                                                       int batch, bf16_t* __restrict__ q_out, bf16_t* __restrict__ kc,
+                                                       bf16_t* __restrict__ vc, size_t layer_off, int hq, int hkv,
+                                                       int h, int max_pos, int n_blocks) {
+    int row = blockIdx.x;
+    if (row >= row_off[batch]) return;
+    int b = row2seq[row];
+    int node = row - row_off[b];
+    int p = pos[row];
+    if (p < 0 || p >= max_pos) return;  // flagged by the draft step; nothing is written for such a row
+    int slot = seq_len[b] - 1 + node;
+    if (slot < 0 || (slot >> 4) >= max_blocks) return;
+    int page = block_table[(size_t)b * max_blocks + (slot >> 4)];
+    if (page < 0 || page >= n_blocks) return;
+    int in_page = slot & 15;
+    int half = h >> 1;
+    const float* cs = rope_cs + (size_t)p * half * 2;
+    const float* src = qkv + (size_t)row * (hq + 2 * hkv) * h;
+    // q heads
+    for (int i = threadIdx.x; i < hq * half; i += 256) {
+        int head = i / half, j = i % half;
+        float c = cs[2 * j], s = cs[2 * j + 1];
+        float a = src[head * h + j], bb = src[head * h + j + half];
+        bf16_t* dst = q_out + (size_t)row * hq * h + head * h;
+        dst[j] = f32_to_bf16(a * c - bb * s);
+        dst[j + half] = f32_to_bf16(bb * c + a * s);
+    }
+    // k heads -> cache [page][kv head][16][h]
+    const float* ksrc = src + (size_t)hq * h;
+    for (int i = threadIdx.x; i < hkv * half; i += 256) {
+        int head = i / half, j = i % half;
+        float c = cs[2 * j], s = cs[2 * j + 1];
+        float a = ksrc[head * h + j], bb = ksrc[head * h + j + half];
+        bf16_t* dst = kc + layer_off + (((size_t)page * hkv + head) * 16 + in_page) * h;
+        dst[j] = f32_to_bf16(a * c - bb * s);
+        dst[j + half] = f32_to_bf16(bb * c + a * s);
+    }
+    // v heads -> cache [page][kv head][h][16]
+    const float* vsrc = ksrc + (size_t)hkv * h;
+    for (int i = threadIdx.x; i < hkv * h; i += 256) {
+        int head = i / h, j = i % h;
+        vc[layer_off + (((size_t)page * hkv + head) * h + j) * 16 + in_page] = f32_to_bf16(vsrc[head * h + j]);
+    }
+}
+
+__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int32_t* __restrict__ out,
+                                                      const int32_t* __restrict__ m_dev, int vocab) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    int row = blockIdx.x;
+    if (row >= *m_dev) return;
+    const float* l = logits + (size_t)row * vocab;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < vocab; i += 256) {
+        float v = l[i];
+        if (v > bv) { bv = v; bi = i; }  // ascending i per thread: first maximum kept
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        float ov = __shfl_xor(bv, o);
+        int oi = __shfl_xor(bi, o);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; w++)
+            if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+        out[row] = bi;
+    }
+}
+
+}  // namespace
+
+void hs_launch_embed(const hs_ctx* ctx, const hs_step* step, int batch, float* x, hipStream_t st) {
+    hipLaunchKernelGGL(embed_kernel, dim3(ctx->lim.max_rows), dim3(256), 0, st, ctx->embed, step->tok,
+                       step->row_off + batch, x, ctx->desc.d_model, ctx->desc.vocab);
+}
+
+void hs_launch_rmsnorm(const hs_ctx* ctx, const float* x, const float* w, bf16_t* out, const int32_t* m_dev,
+                       hipStream_t st) {
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(ctx->lim.max_rows), dim3(256), 0, st, x, w, out, m_dev,
+                       ctx->desc.d_model, ctx->desc.rms_eps);
+}
+
+void hs_launch_rope_kv(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
+                       const hs_step* step, const float* qkv, bf16_t* q, hipStream_t st) {
+    const hs_model_desc& d = ctx->desc;
+    size_t layer_off = (size_t)layer * cache->n_blocks * d.n_kv_heads * 16 * d.head_dim;
+    hipLaunchKernelGGL(rope_kv_kernel, dim3(ctx->lim.max_rows), dim3(256), 0, st, qkv, ctx->rope_cs, step->pos,
+                       step->row2seq, step->row_off, seq->seq_len, seq->block_table, ctx->lim.max_blocks_per_seq,
+                       seq->batch, q, (bf16_t*)cache->k, (bf16_t*)cache->v, layer_off, d.n_q_heads, d.n_kv_heads,
+                       d.head_dim, ctx->lim.max_pos, cache->n_blocks);
+}
+
+void hs_launch_argmax(const hs_ctx* ctx, const float* logits, int32_t* argmax, const int32_t* m_dev,
+                      hipStream_t st) {
+    hipLaunchKernelGGL(argmax_kernel, dim3(ctx->lim.max_rows), dim3(256), 0, st, logits, argmax, m_dev,
+                       ctx->desc.vocab);
+}

@@ -1,0 +1,84 @@
+// Internal declarations shared by the HIP translation units of libhistospec.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "histospec.h"
+
+typedef uint16_t bf16_t;  // storage type: upper half of an fp32
+
+// Keys per split-KV partition of the verify attention.  Partitions are keyed to absolute position, so a row's
+// reduction order does not depend on how many draft rows share its sequence.
+constexpr int HS_ATT_PART_DEFAULT = 2048;
+// History segment scanned by one workgroup of the draft kernel.
+constexpr int HS_DRAFT_SEG = 4096;
+constexpr int HS_MAX_NODES = 64;  // ancestor masks are 64-bit
+
+struct hs_workspace_layout {
+    size_t x, xn, qkv, q, attn, act, part_o, part_ml, logits, draft_best, err, total;
+};
+
+struct hs_ctx {
+    hs_model_desc desc;
+    hs_limits lim;
+    const bf16_t *embed, *lm_head;
+    const float *norm_f, *rope_cs;
+    std::vector<const bf16_t*> wqkv, wo, wgate, wup, wdown;
+    std::vector<const float*> norm1, norm2;
+    uint32_t flags = 0;
+    char* ws = nullptr;
+    size_t ws_bytes = 0;
+    hs_workspace_layout lay;
+    int att_part = HS_ATT_PART_DEFAULT;
+    int max_parts = 0;
+    int max_segs = 0;
+    std::string err;
+    // profiling
+    int profile = 0;
+    std::vector<hipEvent_t> ev;  // pairs
+    std::vector<int> ev_class;
+    int ev_used = 0;
+};
+
+static inline __host__ __device__ float bf16_to_f32(bf16_t b) {
+    union { uint32_t u; float f; } c;
+    c.u = (uint32_t)b << 16;
+    return c.f;
+}
+
+// Round to nearest even (inputs here are never NaN).
+static inline __host__ __device__ bf16_t f32_to_bf16(float f) {
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    uint32_t u = c.u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// ---- launchers (each enqueues on `st`; shapes have been validated by the caller) ----
+
+// GEMM family: C[M,N] (+)= A[M,K] . W[N,K]^T, A and W bf16, fp32 accumulation in a fixed k order.
+// m_dev points at the row count M on the device; the grid covers m_max rows and tiles beyond M exit.
+enum { HS_EPI_STORE_F32 = 0, HS_EPI_ADD_F32 = 1, HS_EPI_SWIGLU_BF16 = 2 };
+void hs_launch_gemm(const hs_ctx* ctx, int epi, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c,
+                    const int32_t* m_dev, int m_max, int n, int k, hipStream_t st);
+
+void hs_launch_embed(const hs_ctx* ctx, const hs_step* step, int batch, float* x, hipStream_t st);
+void hs_launch_rmsnorm(const hs_ctx* ctx, const float* x, const float* w, bf16_t* out, const int32_t* m_dev,
+                       hipStream_t st);
+void hs_launch_rope_kv(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
+                       const hs_step* step, const float* qkv, bf16_t* q, hipStream_t st);
+void hs_launch_attention(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
+                         const hs_step* step, const bf16_t* q, bf16_t* out, hipStream_t st);
+void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, bf16_t* out,
+                               hipStream_t st);
+void hs_launch_argmax(const hs_ctx* ctx, const float* logits, int32_t* argmax, const int32_t* m_dev,
+                      hipStream_t st);
+void hs_launch_draft(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
+                     hipStream_t st);
+void hs_launch_accept(const hs_ctx* ctx, const hs_accept_args* args, const hs_seq_state* seq, hs_step* step,
+                      const float* logits, hipStream_t st);
+void hs_launch_commit(const hs_ctx* ctx, const hs_kv_cache* cache, hs_seq_state* seq, const hs_step* step,
+                      const hs_policy* policy, hipStream_t st);

@@ -1,0 +1,67 @@
+"""Shared pieces of the GPU parity tests: oracle-side state that advances in lock-step with the HIP path."""
+import numpy as np
+
+import oracle
+from hs_inputs import history_with_context, mutate
+
+LOGIT_TOL = 2e-2  # absolute, bf16 path (the tolerance the benchmark spec fixes)
+
+
+def np_of(t):
+    return t.detach().cpu().numpy()
+
+
+class OracleBatch:
+    """Per-sequence oracle state: committed tokens and a K/V cache holding all but the newest token."""
+
+    def __init__(self, model, token_lists, budgets, cap):
+        self.model = model
+        self.x = [list(map(int, t)) for t in token_lists]
+        self.budget = list(budgets)
+        self.seqs = []
+        for t in self.x:
+            s = oracle.Seq(model, cap)
+            s.extend(t[:-1])
+            self.seqs.append(s)
+        self.k_state = [2] * len(self.x)
+
+    def draft(self, b, cands, pol):
+        """Oracle draft for sequence b -> (per-candidate (p, m, K), tree dict or None if finished)."""
+        if self.budget[b] <= 0:
+            return [(-1, 0, 0)] * len(cands), None
+        x = np.asarray(self.x[b], np.int32)
+        info, chains = [], []
+        for h in cands:
+            p, m = oracle.suffix_match(h, x, pol.window, pol.m_min)
+            k = oracle.draft_len(oracle.k_policy(pol.k_mode, pol.k_fixed, self.k_state[b], m, pol.k_max), len(h), p,
+                                 self.budget[b])
+            info.append((p, m, k))
+            chains.append(np.asarray(h[p:p + k], np.int32) if k > 0 else np.zeros(0, np.int32))
+        tree = oracle.build_tree(chains, x[-1], len(x) - 1)
+        return info, tree
+
+    def logits(self, b, tree):
+        return self.seqs[b].tree_logits(tree["tok"], tree["parent"])
+
+    def commit(self, b, tree, a, out, path, pol):
+        """Advance by the emitted tokens `out` (a accepted + 1)."""
+        n_nodes = len(tree["tok"])
+        if pol.k_mode == oracle.K_AIMD:
+            last = int(path[a])
+            leaf = not any(int(tree["parent"][i]) == last for i in range(1, n_nodes))
+            self.k_state[b] = oracle.aimd(self.k_state[b], n_nodes > 1, leaf and a > 0, pol.aimd_inc, pol.aimd_cap,
+                                          pol.aimd_reset)
+        self.seqs[b].extend([self.x[b][-1]] + [int(t) for t in out[:a]])
+        self.x[b].extend(int(t) for t in out)
+        self.budget[b] -= len(out)
+
+
+def top2_margin(row):
+    part = np.partition(row, -2)
+    return float(part[-1] - part[-2])
+
+
+def make_histories(prompts, rollouts, window, p_iid, p_span, vocab, seed):
+    rng = np.random.default_rng(seed)
+    return [[history_with_context(prompts[b], mutate(np.asarray(rollouts[b], np.int32), p_iid, p_span, vocab, rng),
+                                  window)] for b in range(len(prompts))]

@@ -1,0 +1,127 @@
+"""Host-only checks of the C-ABI boundary: the library loads, exports every function the header declares, and
+rejects bad arguments with a status code before anything is launched (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2508_18588_amd as hs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(hs.LIB_PATH):
+        hs.build()
+    return hs.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "histospec.h")).read()
+    declared = set(re.findall(r"^\s*(?:hs_status|void|size_t|const char\*)\s+(hs_[a-z_]+)\(", header, re.M))
+    assert declared == set(hs.EXPORTS), declared ^ set(hs.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_sizes_match_the_header_layout():
+    assert C.sizeof(hs.hs_model_desc) == 36
+    assert C.sizeof(hs.hs_limits) == 28
+    assert C.sizeof(hs.hs_policy) == 32
+    assert C.sizeof(hs.hs_weights) == 11 * 8
+    assert C.sizeof(hs.hs_step) == 15 * 8
+    assert C.sizeof(hs.hs_accept_args) == 16
+    assert C.sizeof(hs.hs_kv_cache) == 24
+
+
+def _good():
+    desc = hs.hs_model_desc(2, 256, 4, 4, 64, 1024, 4096, 16, 1e-6)
+    L = 2
+    fake = 0x1000  # never dereferenced on the host
+    arr = (C.c_void_p * L)(fake, fake)
+    p = C.cast(arr, C.POINTER(C.c_void_p))
+    w = hs.hs_weights(fake, fake, fake, p, p, p, p, p, p, p, fake)
+    lim = hs.hs_limits(4, 4, 1, 20, 32, 512, 8)
+    return desc, w, lim, arr
+
+
+def test_create_validates_shape_and_limits(lib):
+    desc, w, lim, keep = _good()
+    ctx = hs.hs_create(desc, w, lim)
+    assert hs.hs_workspace_bytes(ctx) > 0
+    hs.hs_destroy(ctx)
+
+    def status(d=None, ww=None, ll=None):
+        out = C.c_void_p()
+        return lib.hs_create(C.byref(d or desc), C.byref(ww or w), C.byref(ll or lim), C.byref(out))
+
+    bad = hs.hs_model_desc(2, 256, 4, 4, 96, 1024, 4096, 16, 1e-6)       # head_dim 96
+    assert status(d=bad) == hs.HS_ERR_UNSUPPORTED
+    bad = hs.hs_model_desc(2, 256, 4, 4, 64, 1024, 4096, 32, 1e-6)       # page size 32
+    assert status(d=bad) == hs.HS_ERR_UNSUPPORTED
+    bad = hs.hs_model_desc(2, 256, 4, 3, 64, 1024, 4096, 16, 1e-6)       # heads not divisible
+    assert status(d=bad) == hs.HS_ERR_UNSUPPORTED
+    bad = hs.hs_model_desc(0, 256, 4, 4, 64, 1024, 4096, 16, 1e-6)
+    assert status(d=bad) == hs.HS_ERR_INVALID_ARG
+    assert status(ll=hs.hs_limits(4, 33, 1, 200, 32, 512, 8)) == hs.HS_ERR_INVALID_ARG      # k_max > 32
+    assert status(ll=hs.hs_limits(4, 32, 2, 400, 32, 512, 8)) == hs.HS_ERR_UNSUPPORTED      # 65 nodes
+    assert status(ll=hs.hs_limits(4, 4, 1, 19, 32, 512, 8)) == hs.HS_ERR_CAPACITY           # too few rows
+    w2 = hs.hs_weights(None, 0x1000, 0x1000, w.wqkv, w.wo, w.wgate, w.wup, w.wdown, w.norm1, w.norm2, 0x1000)
+    assert status(ww=w2) == hs.HS_ERR_INVALID_ARG
+    assert lib.hs_create(None, None, None, None) == hs.HS_ERR_INVALID_ARG
+
+
+def test_calls_reject_bad_arguments_without_launching(lib):
+    desc, w, lim, keep = _good()
+    ctx = hs.hs_create(desc, w, lim)
+    seq, step, cache = hs.hs_seq_state(), hs.hs_step(), hs.hs_kv_cache()
+    # no workspace bound yet
+    with pytest.raises(hs.HsError) as e:
+        hs.hs_verify(ctx, cache, seq, step)
+    assert e.value.status == hs.HS_ERR_CAPACITY and "workspace" in str(e.value)
+    with pytest.raises(hs.HsError) as e:
+        hs.hs_bind_workspace(ctx, 0x1001, 1 << 40)   # misaligned
+    assert e.value.status == hs.HS_ERR_INVALID_ARG
+    with pytest.raises(hs.HsError) as e:
+        hs.hs_bind_workspace(ctx, 0x1000, 16)        # too small
+    assert e.value.status == hs.HS_ERR_CAPACITY
+    hs.hs_bind_workspace(ctx, 0x100000, 1 << 40)     # address only recorded, never touched by these checks
+    pol = hs.hs_policy(8, 3, hs.HS_K_FIXED, 4, 4, 2, 32, 2)
+    args = hs.hs_draft_args(1, 0x1000, 0x1000, pol)
+    for call in (lambda: hs.hs_draft(ctx, args, seq, step), lambda: hs.hs_verify(ctx, cache, seq, step),
+                 lambda: hs.hs_accept(ctx, hs.hs_accept_args(0, 1.0, 0), seq, step),
+                 lambda: hs.hs_kv_commit(ctx, cache, seq, step, pol)):
+        with pytest.raises(hs.HsError) as e:
+            call()
+        assert e.value.status == hs.HS_ERR_INVALID_ARG   # null state / step arrays
+    full = hs.hs_seq_state(5, *([0x1000] * 7), None, 0, None)   # batch 5 > max_batch 4
+    with pytest.raises(hs.HsError):
+        hs.hs_draft(ctx, args, full, step)
+    ok_seq = hs.hs_seq_state(4, *([0x1000] * 7), None, 0, None)
+    ok_step = hs.hs_step(*([0x1000] * 15))
+    for bad_pol in (hs.hs_policy(9, 3, 0, 4, 4, 2, 32, 2),     # window > w_max
+                    hs.hs_policy(8, 9, 0, 4, 4, 2, 32, 2),     # m_min > window
+                    hs.hs_policy(8, 3, 7, 4, 4, 2, 32, 2),     # unknown k_mode
+                    hs.hs_policy(8, 3, 0, 4, 5, 2, 32, 2)):    # k_max beyond the limit
+        with pytest.raises(hs.HsError) as e:
+            hs.hs_draft(ctx, hs.hs_draft_args(1, 0x1000, 0x1000, bad_pol), ok_seq, ok_step)
+        assert e.value.status == hs.HS_ERR_INVALID_ARG
+    with pytest.raises(hs.HsError) as e:
+        hs.hs_draft(ctx, hs.hs_draft_args(2, 0x1000, 0x1000, pol), ok_seq, ok_step)   # n_cand > c_max
+    assert e.value.status == hs.HS_ERR_CAPACITY
+    with pytest.raises(hs.HsError):
+        hs.hs_accept(ctx, hs.hs_accept_args(hs.HS_ACCEPT_REJECTION, 0.0, 0), ok_seq, ok_step)  # temperature 0
+    with pytest.raises(hs.HsError):
+        hs.hs_accept(ctx, hs.hs_accept_args(5, 1.0, 0), ok_seq, ok_step)
+    with pytest.raises(hs.HsError):
+        hs.hs_set_flags(ctx, 0x80)
+    hs.hs_destroy(ctx)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(hs, "_lib", None)
+    monkeypatch.setattr(hs, "LIB_PATH", "/nonexistent/libhistospec.so")
+    with pytest.raises(RuntimeError, match="only implementation"):
+        hs.lib()

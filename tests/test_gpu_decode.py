@@ -1,0 +1,265 @@
+"""GPU parity of the whole decode iteration (hs_draft -> hs_verify -> hs_accept -> hs_kv_commit) against the
+oracle, in lock-step: both sides hold the same committed tokens; each iteration the oracle recomputes the logits
+of exactly the rows the GPU verified.  Bars: integer outputs (draft, accept length, state) bit-exact; logits
+within 2e-2 absolute; emitted tokens identical wherever the oracle's top-2 logit margin exceeds that tolerance
+(positions below it are counted and the oracle follows the GPU's token there so the comparison can go on)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from hs_inputs import CONFIG_SHAPES, ModelShape, make_weights, rope_table, make_prompts, config_seed
+from gpu_common import LOGIT_TOL, OracleBatch, make_histories, np_of, top2_margin
+
+pytestmark = pytest.mark.gpu
+
+
+def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=()):
+    """Run until every budget is spent.  Returns statistics."""
+    B = len(ob.x)
+    stats = dict(steps=0, accepted=0, emitted=0, flagged=0, max_logit_err=0.0, rows=0)
+    for _ in range(max_steps):
+        if all(b <= 0 for b in ob.budget):
+            break
+        eng.step(pol)
+        torch.cuda.synchronize()
+        assert eng.poll_error() == 0
+        st = {k: np_of(v) for k, v in eng.st.items()}
+        lg = np_of(eng.logits)
+        ro = st["row_off"]
+        for b in range(B):
+            info, tree = ob.draft(b, cands[b], pol)
+            C = len(cands[b])
+            for c in range(C):
+                got = (st["draft_start"][b * C + c], st["match_len"][b * C + c], st["draft_len"][b * C + c])
+                assert got == info[c], (b, c, got, info[c])
+            if tree is None:
+                assert ro[b + 1] == ro[b] and st["n_out"][b] == 0
+                continue
+            sl = slice(ro[b], ro[b + 1])
+            assert st["tok"][sl].tolist() == tree["tok"].tolist()
+            assert st["parent"][sl].tolist() == tree["parent"].tolist()
+            want = ob.logits(b, tree)
+            err = float(np.abs(lg[sl] - want).max())
+            stats["max_logit_err"] = max(stats["max_logit_err"], err)
+            assert err <= LOGIT_TOL, (b, err)
+            # the GPU's argmax must be the argmax of its own logits (lowest id on ties)
+            assert st["argmax"][sl].tolist() == [int(np.argmax(r)) for r in lg[sl]]
+            # oracle decision on oracle logits vs GPU decision; the GPU's walk must also be the greedy walk of
+            # its own argmax
+            arg_o = [oracle.argmax(r) for r in want]
+            a_o, out_o, path_o = oracle.accept_greedy(tree["tok"], tree["parent"], arg_o)
+            a_g, out_g, path_g = oracle.accept_greedy(tree["tok"], tree["parent"], st["argmax"][sl])
+            n = st["n_out"][b]
+            assert st["accept_len"][b] == a_g and n == a_g + 1
+            assert st["out_tok"][b, :n].tolist() == out_g.tolist()
+            assert st["path_row"][b, :n].tolist() == path_g.tolist()
+            if out_g.tolist() != out_o.tolist():
+                # allowed only where a visited row's top-2 margin is within the logit tolerance
+                visited = set(path_o.tolist()) | set(path_g.tolist())
+                assert min(top2_margin(want[r]) for r in visited) <= LOGIT_TOL, (b, out_g, out_o)
+                stats["flagged"] += 1
+            ob.commit(b, tree, a_g, out_g, path_g, pol)   # the oracle follows the GPU's tokens
+            stats["accepted"] += a_g
+            stats["emitted"] += int(n)
+            stats["rows"] += len(tree["tok"])
+        # state after commit
+        assert np_of(eng.seq_len)[:B].tolist() == [len(x) for x in ob.x]
+        assert np_of(eng.budget_left)[:B].tolist() == ob.budget
+        tail, tl = np_of(eng.tail), np_of(eng.tail_len)
+        for b in range(B):
+            m = min(len(ob.x[b]), eng.w_max)
+            assert tl[b] == m and tail[b, eng.w_max - m:].tolist() == ob.x[b][-m:]
+        if pol.k_mode == oracle.K_AIMD:
+            assert np_of(eng.k_state)[:B].tolist() == ob.k_state
+        stats["steps"] += 1
+    toks = np_of(eng.tokens)
+    for b in range(B):
+        assert toks[b, :len(ob.x[b])].tolist() == ob.x[b]
+    for layer in check_kv_layers:
+        check_cache(eng, ob, layer)
+    return stats
+
+
+def check_cache(eng, ob, layer):
+    """Cache contents at [0, L) must equal the K/V the oracle computed for the committed tokens."""
+    shape = eng.shape
+    hkv, h = shape.n_kv_heads, shape.head_dim
+    kc = np_of(eng.kc).view(np.uint16).reshape(eng.n_layers, eng.n_blocks, hkv, 16, h)
+    vc = np_of(eng.vc).view(np.uint16).reshape(eng.n_layers, eng.n_blocks, hkv, h, 16)
+    bt = np_of(eng.block_table)
+    f = lambda bits: (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    for b, s in enumerate(ob.seqs):
+        for pos in range(0, len(s), max(1, len(s) // 40)):
+            k, v = s.kv(layer, pos)
+            page, ip = bt[b, pos // 16], pos % 16
+            gk = f(kc[layer, page, :, ip, :]).reshape(-1)
+            gv = f(vc[layer, page, :, :, ip]).reshape(-1)
+            np.testing.assert_allclose(gk, k, atol=2e-2, rtol=2e-2)
+            np.testing.assert_allclose(gv, v, atol=2e-2, rtol=2e-2)
+
+
+def setup_rollout(shape, w, rope, B, prompt_len, n_new, seed):
+    model = oracle.Model(shape, w, rope)
+    prompts = make_prompts(B, prompt_len, shape.vocab, seed)
+    rollouts = []
+    for b in range(B):
+        s = oracle.Seq(model, prompt_len + n_new + 8)
+        s.extend(prompts[b][:-1])
+        rollouts.append(oracle.ar_greedy(s, prompts[b][-1], n_new))
+    return model, prompts, rollouts
+
+
+def gpu_ar_rollout(shape, w, rope, toks, n_new):
+    """The HIP path's own plain autoregressive greedy rollout (no drafts): the text a previous epoch would have
+    produced with unchanged weights."""
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    B = len(toks)
+    pol = Policy(window=8, m_min=3, k_fixed=0, k_max=0)
+    eng = Engine(shape, w, rope, max_batch=B, k_max=0, c_max=1, max_len=max(len(t) for t in toks) + n_new)
+    eng.load_sequences(toks, budgets=[n_new] * B)
+    eng.set_history([[np.zeros(0, np.int32)] for _ in range(B)])
+    eng.prefill(toks)
+    for _ in range(n_new):
+        eng.step(pol)
+    out = np_of(eng.tokens)
+    eng.close()
+    return [out[b, len(toks[b]):len(toks[b]) + n_new].copy() for b in range(B)]
+
+
+@pytest.fixture(scope="module")
+def config1():
+    shape = CONFIG_SHAPES[1]
+    seed = config_seed(1)
+    w = make_weights(shape, seed)
+    rope = rope_table(512, shape.head_dim)
+    model, prompts, rollouts = setup_rollout(shape, w, rope, 4, 64, 256, seed)
+    return shape, w, rope, model, prompts, rollouts
+
+
+@pytest.mark.parametrize("reference_kernels", [True, False])
+def test_config1_full_rollout_lockstep(config1, reference_kernels):
+    """Configuration 1 in full: B=4, prompt 64, 256-token greedy rollout, history = the oracle's rollout with 10 %
+    of positions replaced, window 8, K=4, greedy, pages of 16."""
+    from paper_2508_18588_amd import HS_FLAG_REFERENCE_KERNELS
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    shape, w, rope, model, prompts, rollouts = config1
+    pol = Policy(window=8, m_min=3, k_fixed=4, k_max=4)
+    cands = make_histories(prompts, rollouts, 8, 0.10, 0.0, shape.vocab, seed=77)
+    eng = Engine(shape, w, rope, max_batch=4, k_max=4, c_max=1, max_len=64 + 256, shuffle_pages_seed=5)
+    if reference_kernels:
+        eng.set_flags(HS_FLAG_REFERENCE_KERNELS)
+    eng.load_sequences(list(prompts), budgets=[256] * 4)
+    eng.set_history(cands)
+    eng.prefill(list(prompts))
+    ob = OracleBatch(model, list(prompts), [256] * 4, 64 + 256 + 8)
+    stats = lockstep(eng, ob, cands, pol, max_steps=300, check_kv_layers=(0, 1))
+    eng.close()
+    print("config1", "plain" if reference_kernels else "mfma", stats)
+    assert stats["emitted"] == 4 * 256
+    assert stats["accepted"] > 40             # speculation really happened (until a near-tie leaves the history)
+    assert stats["flagged"] <= 24
+    # where nothing was flagged the output is the oracle's own autoregressive greedy rollout
+    if stats["flagged"] == 0:
+        for b in range(4):
+            assert ob.x[b][64:] == rollouts[b]
+
+
+@pytest.mark.parametrize("mode", ["matchlen", "aimd"])
+def test_adaptive_draft_lengths_lockstep(config1, mode):
+    """Variable K per sequence (match-length policy, and the AIMD window 2,+2,cap,reset), ragged prompts and
+    budgets, one sequence finishing early."""
+    from paper_2508_18588_amd import HS_K_AIMD, HS_K_MATCHLEN
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    shape, w, rope, model, prompts, rollouts = config1
+    if mode == "matchlen":
+        pol = Policy(window=16, m_min=3, k_mode=HS_K_MATCHLEN, k_max=16)
+    else:
+        pol = Policy(window=7, m_min=3, k_mode=HS_K_AIMD, k_max=32)
+    lens = [64, 37, 50, 21]
+    toks = [prompts[b][64 - lens[b]:] for b in range(4)]
+    rolls = gpu_ar_rollout(shape, w, rope, toks, 120)
+    cands = make_histories(toks, rolls, pol.window, 0.05, 0.03, shape.vocab, seed=78)
+    budgets = [120, 60, 120, 9]
+    eng = Engine(shape, w, rope, max_batch=4, k_max=pol.k_max, c_max=1, max_len=64 + 130, shuffle_pages_seed=6)
+    eng.load_sequences(toks, budgets)
+    eng.set_history(cands)
+    eng.prefill(toks)
+    ob = OracleBatch(model, toks, budgets, 64 + 140 + 40)
+    stats = lockstep(eng, ob, cands, pol, max_steps=200, check_kv_layers=(1,))
+    eng.close()
+    print(mode, stats)
+    assert stats["emitted"] == sum(budgets)
+    assert stats["rows"] > 2 * stats["steps"]   # drafts longer than a token were verified
+    assert stats["flagged"] <= 6
+
+
+def test_speculative_equals_autoregressive_bitwise_on_gpu(config1):
+    """Sec. 2.2: speculation must not change the output.  The GPU path keeps every reduction order independent of
+    how many rows share a launch, so the greedy token streams with and without drafts are identical."""
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    shape, w, rope, model, prompts, rollouts = config1
+    rolls = gpu_ar_rollout(shape, w, rope, list(prompts), 256)
+    cands = make_histories(prompts, rolls, 8, 0.10, 0.02, shape.vocab, seed=79)
+    outs = []
+    for k in (0, 4):
+        pol = Policy(window=8, m_min=3, k_fixed=k, k_max=4)
+        eng = Engine(shape, w, rope, max_batch=4, k_max=4, c_max=1, max_len=64 + 256, shuffle_pages_seed=7 + k)
+        eng.load_sequences(list(prompts), budgets=[256] * 4)
+        eng.set_history(cands)
+        eng.prefill(list(prompts))
+        steps = 0
+        while int(eng.budget_left.max()) > 0:
+            eng.step(pol)
+            steps += 1
+        outs.append((np_of(eng.tokens)[:, :64 + 256].copy(), steps, np_of(eng.counters).copy()))
+        eng.close()
+    assert (outs[0][0] == outs[1][0]).all()
+    for b in range(4):
+        assert outs[0][0][b, 64:].tolist() == rolls[b].tolist()
+    assert outs[0][1] == 256 and outs[1][1] < 200
+    assert outs[0][2][2] == 0 and outs[1][2][2] > 300   # accepted-token counters
+
+
+def test_tree_drafts_two_candidates_lockstep(config1):
+    """Two history candidates per sequence (two prior epochs) merged into a draft tree of depth 8, verified with
+    the ancestor mask, greedy acceptance, accepted nodes of the second branch relocated by the commit."""
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    shape, w, rope, model, prompts, rollouts = config1
+    pol = Policy(window=8, m_min=3, k_fixed=8, k_max=8)
+    rolls = gpu_ar_rollout(shape, w, rope, list(prompts), 128)
+    h0 = make_histories(prompts, rolls, 8, 0.40, 0.0, shape.vocab, seed=80)
+    h1 = make_histories(prompts, rolls, 8, 0.25, 0.0, shape.vocab, seed=81)
+    cands = [[h0[b][0], h1[b][0]] for b in range(4)]
+    eng = Engine(shape, w, rope, max_batch=4, k_max=8, c_max=2, max_len=64 + 128, shuffle_pages_seed=9)
+    eng.load_sequences(list(prompts), budgets=[128] * 4)
+    eng.set_history(cands)
+    eng.prefill(list(prompts))
+    ob = OracleBatch(model, list(prompts), [128] * 4, 64 + 128 + 24)
+    stats = lockstep(eng, ob, cands, pol, max_steps=200, check_kv_layers=(0, 1))
+    eng.close()
+    print("tree", stats)
+    assert stats["emitted"] == 4 * 128 and stats["flagged"] <= 6
+    assert stats["rows"] > 9 * stats["steps"]   # forks occurred: more than one chain's worth of rows
+
+
+def test_gqa_head_dim_128_small_model():
+    """A small decoder with the large configurations' attention geometry (grouped queries 6:1... head_dim 128)."""
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    shape = ModelShape(n_layers=2, d_model=384, n_q_heads=6, n_kv_heads=1, head_dim=128, d_ffn=640, vocab=1024)
+    w = make_weights(shape, 31, norm_jitter=0.1, std=0.05)
+    rope = rope_table(4096, shape.head_dim)
+    model = oracle.Model(shape, w, rope)
+    prompts = make_prompts(3, 40, shape.vocab, 32)
+    rollouts = gpu_ar_rollout(shape, w, rope, list(prompts), 80)
+    pol = Policy(window=8, m_min=3, k_fixed=8, k_max=8)
+    cands = make_histories(prompts, rollouts, 8, 0.1, 0.0, shape.vocab, seed=82)
+    eng = Engine(shape, w, rope, max_batch=3, k_max=8, c_max=1, max_len=40 + 80, shuffle_pages_seed=10)
+    eng.load_sequences(list(prompts), budgets=[80] * 3)
+    eng.set_history(cands)
+    eng.prefill(list(prompts))
+    ob = OracleBatch(model, list(prompts), [80] * 3, 40 + 80 + 16)
+    stats = lockstep(eng, ob, cands, pol, max_steps=100, check_kv_layers=(1,))
+    eng.close()
+    print("gqa128", stats)
+    assert stats["emitted"] == 240 and stats["accepted"] > 60 and stats["flagged"] <= 6
