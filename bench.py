@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the history-drafted speculative decoding hot path on one MI355X.
+
+A "step" is one pass of the whole path -- hs_draft, hs_verify, hs_accept, hs_kv_commit -- over the whole
+in-flight batch.  The default workload is benchmark configuration 3 (7B-shaped decoder, batch 128, contexts
+uniform 2k..16k, 70 % history similarity, draft length set by the match length, greedy acceptance); all inputs
+are synthetic and seeded (see the design doc for the recipe) and resident in HBM before the timed region starts.
+
+Prints ONE JSON line: accepted tokens/s over the timed steps, the roofline of the dominant kernel (verify
+attention, HBM-bound) measured with HIP events on the launching stream, and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def workload_params(config: int):
+    from paper_2508_18588_amd import HS_K_FIXED, HS_K_MATCHLEN
+    if config == 3:
+        return dict(name="config3: 7B shape (28L d3584 28q/4kv x128 ffn18944 V152064), B=128, context U[2048,16384], "
+                         "history = GPU greedy 256-token window mutated 26.3% iid + 5% spans (70% copied), "
+                         "K = match length 1..16 (window 16, min 3), greedy, KV page 16",
+                    batch=128, ctx=("uniform", 2048, 16384), window_tokens=256, p_iid=0.263, p_span=0.05,
+                    policy=dict(window=16, m_min=3, k_mode=HS_K_MATCHLEN, k_max=16), k_max=16)
+    if config == 2:
+        return dict(name="config2: 1.5B shape (28L d1536 12q/2kv x128 ffn8960 V151936), B=64, prompt 512 + response "
+                         "offset 2048, history = GPU greedy 256-token window mutated 20% iid + 5% spans, K=8 fixed, "
+                         "greedy, KV page 16",
+                    batch=64, ctx=("fixed", 512 + 2048), window_tokens=256, p_iid=0.20, p_span=0.05,
+                    policy=dict(window=8, m_min=3, k_mode=HS_K_FIXED, k_fixed=8, k_max=8), k_max=8)
+    raise SystemExit(f"bench.py: no benchmark workload for config {config} (2 and 3 are available)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is then NOT the benchmark)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events (roofline null)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_2508_18588_amd as hs
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    from hs_inputs import CONFIG_SHAPES, config_seed, mutate, lengths_uniform
+    from hs_inputs.device import make_weights_device, fill_kv_random, rope_device, weights_to_host
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    hs.lib()
+    cfg = args.config
+    wp = workload_params(cfg)
+    shape = CONFIG_SHAPES[cfg]
+    seed = config_seed(cfg)
+    n_layers = args.layers or shape.n_layers
+    B, T = wp["batch"], wp["window_tokens"]
+    pol = Policy(**wp["policy"])
+    W = pol.window
+    if wp["ctx"][0] == "uniform":
+        ctx = lengths_uniform(B, wp["ctx"][1], wp["ctx"][2], seed)
+    else:
+        ctx = np.full(B, wp["ctx"][1], np.int32)
+    rng = np.random.default_rng(seed)
+
+    t0 = time.time()
+    w = make_weights_device(shape, seed, n_layers)
+    max_len = int(ctx.max()) + 1 + T
+    rope = rope_device(max_len + 64, shape.head_dim)
+    eng = Engine(shape, w, rope, max_batch=B, k_max=wp["k_max"], c_max=1, max_len=max_len,
+                 seq_caps=[int(c) + 1 + T for c in ctx], shuffle_pages_seed=seed & 0xFFFF, keep_logits=False)
+    # context: L_b cached positions (synthetic K/V of the scale a real prefill writes) + one committed root token
+    kv_std = 0.02 * float(np.sqrt(shape.d_model))
+    fill_kv_random(eng.kc, eng.vc, seed + 1, kv_std)
+    toks = [rng.integers(0, shape.vocab, int(c) + 1).astype(np.int32) for c in ctx]
+    torch.cuda.synchronize()
+    log(f"setup: weights+cache in {time.time() - t0:.1f}s; KV resident {eng.kc.numel() * 4 / 1e9:.1f} GB, "
+        f"weights {shape.dense_params * n_layers / shape.n_layers * 2 / 1e9:.1f} GB")
+
+    # ---- previous-epoch text: the path's own greedy continuation (K=0), then mutated
+    ar_pol = Policy(window=W, m_min=pol.m_min, k_fixed=0, k_max=wp["k_max"])
+    eng.load_sequences(toks, budgets=[T] * B)
+    eng.set_history([[np.zeros(0, np.int32)] for _ in range(B)])
+    for _ in range(3):
+        eng.step(ar_pol)
+    torch.cuda.synchronize()
+    t1 = time.time()
+    for _ in range(T - 3):
+        eng.step(ar_pol)
+    torch.cuda.synchronize()
+    ar_ms = (time.time() - t1) / (T - 3) * 1e3
+    out = eng.tokens.cpu().numpy()
+    rolls = [out[b, len(toks[b]):len(toks[b]) + T].copy() for b in range(B)]
+    log(f"autoregressive rollout (K=0): {ar_ms:.2f} ms/step, {B / ar_ms * 1e3:.0f} tokens/s")
+    hists = []
+    for b in range(B):
+        filler = rng.integers(0, shape.vocab, max(0, len(toks[b]) - (W - 1))).astype(np.int32)
+        hists.append([np.concatenate([filler, toks[b][-(W - 1):], mutate(rolls[b], wp["p_iid"], wp["p_span"],
+                                                                          shape.vocab, rng)])])
+    eng.load_sequences(toks, budgets=[T] * B)
+    eng.set_history(hists)
+
+    # ---- warm-up, then the timed region
+    first = None
+    for i in range(args.warmup):
+        eng.step(pol)
+        if i == 0:
+            torch.cuda.synchronize()
+            first = {k: v.cpu().numpy().copy() for k, v in eng.st.items()}
+    torch.cuda.synchronize()
+    c0 = eng.counters.cpu().numpy().copy()
+    len0 = eng.seq_len.cpu().numpy()[:B].astype(np.int64).copy()
+    if not args.no_profile:
+        eng.set_profile(True)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        eng.step(pol)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t2
+    prof = None if args.no_profile else eng.get_profile()
+    eng.set_profile(False)
+    c1 = eng.counters.cpu().numpy().copy()
+    len1 = eng.seq_len.cpu().numpy()[:B].astype(np.int64).copy()
+    assert eng.poll_error() == 0, "device error word set"
+    seq_steps, drafted, accepted, emitted = (c1 - c0).tolist()
+    ms_per_step = elapsed / args.steps * 1e3
+    rows_per_step = (drafted + seq_steps) / args.steps
+
+    # ---- roofline of the dominant kernel: verify attention, one launch per layer and step.
+    # Algorithmic bytes per launch: every cached K and V element of every sequence once (positions [0, L_b + nodes)),
+    # the bf16 queries in and the bf16 attention output out.
+    roofline = None
+    kv_tok_bytes = 2 * shape.n_kv_heads * shape.head_dim * 2          # K+V bytes per token and layer
+    mean_keys = float((len0 + len1).sum()) / 2 - B + rows_per_step     # sum_b (L_b + nodes_b), mid-region
+    att_bytes = mean_keys * kv_tok_bytes + rows_per_step * shape.n_q_heads * shape.head_dim * 2 * 2
+    extras = {}
+    if prof is not None:
+        ms, n = prof
+        att_ms = ms[0] / max(1, n[0])
+        achieved = att_bytes / (att_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "attn_verify_mfma", "achieved": round(achieved, 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": None, "algorithmic_bytes_per_launch": int(att_bytes),
+                    "avg_launch_ms": round(att_ms, 4), "launches": n[0]}
+        gemm_flops = 2.0 * rows_per_step * (shape.dense_params - shape.d_model * shape.vocab) * n_layers / shape.n_layers
+        gemm_ms = ms[1] / args.steps
+        lm_flops = 2.0 * rows_per_step * shape.d_model * shape.vocab
+        lm_ms = ms[2] / args.steps
+        extras = {"gemm_tflops": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 1),
+                  "gemm_frac_of_bf16_mfma_peak": round(gemm_flops / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                  "lm_head_tflops": round(lm_flops / (lm_ms * 1e-3) / 1e12, 1),
+                  "ms_per_step_by_class": {"attention": round(ms[0] / args.steps, 3), "proj_gemm": round(gemm_ms, 3),
+                                           "lm_head": round(lm_ms, 3), "other": round(ms[3] / args.steps, 3),
+                                           "verify_total": round(ms[4] / args.steps, 3)}}
+
+    # ---- CPU oracle on a bounded sample: one sequence, its first speculative step at full model size
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(eng, shape, w, rope, toks, hists, pol, first, B, n_layers, weights_to_host)
+
+    result = {
+        "metric": "accepted tokens/sec on 1 MI355X (verify step)", "value": round(accepted / elapsed, 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wp["name"] + ("" if n_layers == shape.n_layers else f" [DEBUG: {n_layers} layers]"),
+                   "rows_per_step": round(rows_per_step, 1),
+                   "committed_tokens_per_s": round(emitted / elapsed, 1),
+                   "accepted_per_seq_step": round(accepted / max(1, seq_steps), 3),
+                   "acceptance_rate": round(accepted / max(1, drafted), 3),
+                   "autoregressive_tokens_per_s": round(B / ar_ms * 1e3, 1),
+                   "speedup_vs_autoregressive": round((emitted / elapsed) / (B / ar_ms * 1e3), 3),
+                   "kv_resident_gb": round(float(len0.sum()) * kv_tok_bytes * n_layers / 1e9, 1), **extras},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    eng.close()
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(eng, shape, w, rope, toks, hists, pol, first, B, n_layers, weights_to_host):
+    """Time the oracle on the first speculative step of one sequence (the shortest context that drafted)."""
+    import numpy as np
+    import torch
+
+    import oracle
+    if first is None:
+        return None
+    ro = first["row_off"]
+    drafted = [b for b in range(B) if ro[b + 1] - ro[b] > 1]
+    if not drafted:
+        return None
+    b = min(drafted, key=lambda i: len(toks[i]))
+    L = len(toks[b]) - 1
+    t0 = time.time()
+    wh = weights_to_host(w)
+    model = oracle.Model(shape, wh, rope.cpu().numpy())
+    hkv, h = shape.n_kv_heads, shape.head_dim
+    pages = eng.block_table[b, :(L + 15) // 16].long()
+    kc = eng.kc.view(n_layers, eng.n_blocks, hkv, 16, h)[:, pages].view(torch.bfloat16)
+    vc = eng.vc.view(n_layers, eng.n_blocks, hkv, h, 16)[:, pages].view(torch.bfloat16)
+    k = kc.permute(0, 1, 3, 2, 4).reshape(n_layers, -1, hkv * h)[:, :L].double().cpu().numpy()
+    v = vc.permute(0, 1, 4, 2, 3).reshape(n_layers, -1, hkv * h)[:, :L].double().cpu().numpy()
+    seq = oracle.Seq(model, L + 64)
+    seq.load_kv(k, v)
+    log(f"cpu_baseline: sequence {b} (context {L}), host copy of weights and its K/V in {time.time() - t0:.1f}s")
+    x = toks[b]
+    t1 = time.time()
+    p, m = oracle.suffix_match(hists[b][0], x, pol.window, pol.m_min)
+    kk = oracle.draft_len(oracle.k_policy(pol.k_mode, pol.k_fixed, 2, m, pol.k_max), len(hists[b][0]), p, 256)
+    tree = oracle.build_tree([hists[b][0][p:p + kk]], x[-1], L)
+    lg = seq.tree_logits(tree["tok"], tree["parent"])
+    a, out, path = oracle.accept_greedy(tree["tok"], tree["parent"], [oracle.argmax(r) for r in lg])
+    dt = time.time() - t1
+    gpu_out = first["out_tok"][b, :first["n_out"][b]].tolist()
+    log(f"cpu_baseline: {len(tree['tok'])} rows in {dt:.1f}s; oracle emitted {out.tolist()}, GPU emitted {gpu_out}")
+    return {"value": round(a / dt, 4), "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"1 of {B} sequences (context {L} tokens), 1 speculative step of {len(tree['tok'])} rows "
+                      f"through all {n_layers} layers; accepted {a}, committed {a + 1} tokens in {dt:.1f} s",
+            "committed_tokens_per_s": round((a + 1) / dt, 4),
+            "same_tokens_as_gpu": out.tolist() == gpu_out}
+
+
+if __name__ == "__main__":
+    main()

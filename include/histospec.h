@@ -209,10 +209,11 @@ hs_status hs_poll_error(hs_ctx* ctx, hs_stream stream, uint32_t* error_bits);
  * 2 last layer's attention output bf16 (same shape), 3 logits f32 [max_rows][vocab]. */
 hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size_t* bytes);
 
-/* Timing of the most recent hs_verify: with hs_set_profile(ctx, 1) every kernel launch is bracketed by HIP events
- * on the call's stream; hs_get_profile waits for the call and returns total milliseconds and launch counts per
- * class: 0 attention kernel, 1 projection GEMMs (QKV, O, gate/up, down), 2 LM-head GEMM, 3 everything else
- * (norms, rotary/KV write, split-KV merge, argmax), 4 the whole call. */
+/* Kernel timing.  After hs_set_profile(ctx, 1) every kernel launch of hs_verify is bracketed by HIP events on the
+ * call's stream; hs_get_profile waits for the last profiled call and returns, summed over all hs_verify calls
+ * since the previous hs_get_profile / hs_set_profile, total milliseconds and launch counts per class:
+ * 0 attention kernel, 1 projection GEMMs (QKV, O, gate/up, down), 2 LM-head GEMM, 3 everything else (norms,
+ * rotary/KV write, split-KV merge, argmax), 4 whole calls.  Events are host objects; no device memory is used. */
 hs_status hs_set_profile(hs_ctx* ctx, int32_t enabled);
 hs_status hs_get_profile(hs_ctx* ctx, float ms[5], int32_t launches[5]);
 

@@ -68,6 +68,7 @@ def lib():
         L.orc_seq_len.argtypes = [C.c_void_p]
         L.orc_seq_truncate.argtypes = [C.c_void_p, C.c_int]
         L.orc_seq_kv.argtypes = [C.c_void_p, C.c_int, C.c_int, f64p, f64p]
+        L.orc_seq_load_kv.argtypes = [C.c_void_p, C.c_int, f64p, f64p]
         L.orc_seq_push.argtypes = [C.c_void_p, C.c_int32, f64p]
         L.orc_argmax.argtypes = [f64p, C.c_int]
         L.orc_tree_logits.argtypes = [C.c_void_p, C.c_int, i32p, i32p, f64p]
@@ -226,6 +227,15 @@ class Seq:
             raise IndexError("kv")
         return k, v
 
+    def load_kv(self, k, v):
+        """Install a given cache: k, v are [n_layers, n, n_kv_heads*head_dim]; afterwards len(self) == n."""
+        k = np.ascontiguousarray(k, np.float64)
+        v = np.ascontiguousarray(v, np.float64)
+        assert k.shape == v.shape and k.shape[0] == self.model.n_layers
+        f64p = C.POINTER(C.c_double)
+        if lib().orc_seq_load_kv(self.h, k.shape[1], k.ctypes.data_as(f64p), v.ctypes.data_as(f64p)) != 0:
+            raise IndexError("load_kv")
+
     def tree_logits(self, tok, parent) -> np.ndarray:
         t, tp = _i32(tok)
         p, pp = _i32(parent)
@@ -233,6 +243,10 @@ class Seq:
         if lib().orc_tree_logits(self.h, len(t), tp, pp, out.ctypes.data_as(C.POINTER(C.c_double))) != 0:
             raise ValueError("orc_tree_logits")
         return out
+
+
+def threads() -> int:
+    return lib().orc_threads()
 
 
 def argmax(x) -> int:

@@ -308,6 +308,20 @@ int orc_seq_kv(const orc_seq* s, int layer, int pos, double* k_out, double* v_ou
     return 0;
 }
 
+/* Install an externally supplied cache: k_in, v_in are [n_layers][n][n_kv_heads*head_dim]; afterwards positions
+ * [0, n) count as cached. */
+int orc_seq_load_kv(orc_seq* s, int n, const double* k_in, const double* v_in) {
+    const orc_model* m = s->m;
+    size_t kvw = (size_t)m->n_kv_heads * m->head_dim;
+    if (n < 0 || n > s->cap) return -1;
+    for (int l = 0; l < m->n_layers; l++) {
+        memcpy(s->k + (size_t)l * s->cap * kvw, k_in + (size_t)l * n * kvw, (size_t)n * kvw * sizeof(double));
+        memcpy(s->v + (size_t)l * s->cap * kvw, v_in + (size_t)l * n * kvw, (size_t)n * kvw * sizeof(double));
+    }
+    s->len = n;
+    return 0;
+}
+
 /*
  * Feed one token at position s->len: standard pre-norm decoder,
  *   h0 = E[token]
@@ -382,26 +396,45 @@ int orc_argmax(const double* x, int n) {
 /*
  * Logits of every node of a draft tree.  The cache must hold exactly the
  * l_cached positions before the root token.  Node r's logits are those of the
- * plain causal model fed cached-prefix + the tokens on the path root..r: the
- * tree is walked depth-first by truncating the sequence back to the parent
- * and pushing the node's token.  On return the cache is back at l_cached.
- * logits is [n_nodes][vocab].
+ * plain causal model fed cached-prefix + the tokens on the path root..r.
+ * Nodes are visited in index order; the K/V of the part of the path that the
+ * previously visited node shares stay in the cache, the rest is truncated
+ * away and the remaining path tokens are pushed one by one.  On return the
+ * cache is back at l_cached.  logits is [n_nodes][vocab].
  */
 int orc_tree_logits(orc_seq* s, int n_nodes, const int32_t* tok, const int32_t* parent, double* logits) {
     int base = s->len;
     int V = s->m->vocab;
+    int cur[80], ncur = 0; /* nodes whose K/V sit in the cache above base, root first */
     for (int r = 0; r < n_nodes; r++) {
-        /* path root..r */
         int path[80], np_ = 0;
         for (int c = r; c >= 0; c = parent[c]) { if (np_ >= 80) return -1; path[np_++] = c; }
-        if (orc_seq_truncate(s, base) != 0) return -1;
-        for (int j = np_ - 1; j >= 0; j--) {
-            double* out = (j == 0) ? logits + (size_t)r * V : NULL;
-            if (orc_seq_push(s, tok[path[j]], out) != 0) return -1;
+        /* path[] is leaf-first; compare root-first with cur[] */
+        int common = 0;
+        while (common < ncur && common < np_ && cur[common] == path[np_ - 1 - common]) common++;
+        if (orc_seq_truncate(s, base + common) != 0) return -1;
+        ncur = common;
+        for (int j = common; j < np_; j++) {
+            int node = path[np_ - 1 - j];
+            double* out = (j == np_ - 1) ? logits + (size_t)r * V : NULL;
+            if (orc_seq_push(s, tok[node], out) != 0) return -1;
+            cur[ncur++] = node;
+        }
+        if (common == np_) {
+            /* r itself was already cached (cannot happen for distinct nodes, kept for safety) */
+            return -1;
         }
     }
     return orc_seq_truncate(s, base);
 }
+
+/* Threads the matrix-vector products use. */
+#ifdef _OPENMP
+#include <omp.h>
+int orc_threads(void) { return omp_get_max_threads(); }
+#else
+int orc_threads(void) { return 1; }
+#endif
 
 /* ----------------------------------------------------------------- accept */
 

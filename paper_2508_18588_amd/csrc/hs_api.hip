@@ -196,7 +196,6 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
     const int qh = d.n_q_heads * d.head_dim;
     const int nqkv = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
 
-    ctx->ev_used = 0;
     Prof whole{ctx, st}, pr{ctx, st};
     whole.begin(4);
     int whole_slot = ctx->ev_used;
@@ -245,6 +244,7 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
     pr.end();
     if (ctx->profile) {
         (void)hipEventRecord(ctx->ev[whole_slot + 1], st);
+        ctx->ev_last = whole_slot + 1;
     }
     if (hipGetLastError() != hipSuccess) return fail(ctx, HS_ERR_HIP, "hs_verify: launch failed");
     return HS_OK;
@@ -320,7 +320,8 @@ hs_status hs_get_profile(hs_ctx* ctx, float ms[5], int32_t launches[5]) {
     if (!ctx || !ms || !launches) return HS_ERR_INVALID_ARG;
     for (int i = 0; i < 5; i++) { ms[i] = 0.f; launches[i] = 0; }
     if (!ctx->profile || ctx->ev_used < 2) return fail(ctx, HS_ERR_INVALID_ARG, "no profiled hs_verify to report");
-    if (hipEventSynchronize(ctx->ev[1]) != hipSuccess) return fail(ctx, HS_ERR_HIP, "hs_get_profile: sync failed");
+    if (hipEventSynchronize(ctx->ev[ctx->ev_last]) != hipSuccess)
+        return fail(ctx, HS_ERR_HIP, "hs_get_profile: sync failed");
     for (int p = 0; p < ctx->ev_used / 2; p++) {
         float t = 0.f;
         if (hipEventElapsedTime(&t, ctx->ev[2 * p], ctx->ev[2 * p + 1]) != hipSuccess)
@@ -329,6 +330,7 @@ hs_status hs_get_profile(hs_ctx* ctx, float ms[5], int32_t launches[5]) {
         ms[c] += t;
         launches[c] += 1;
     }
+    ctx->ev_used = 0;
     return HS_OK;
 }
 

@@ -40,6 +40,7 @@ struct hs_ctx {
     std::vector<hipEvent_t> ev;  // pairs
     std::vector<int> ev_class;
     int ev_used = 0;
+    int ev_last = 0;
 };
 
 static inline __host__ __device__ float bf16_to_f32(bf16_t b) {

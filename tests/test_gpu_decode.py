@@ -247,7 +247,7 @@ def test_gqa_head_dim_128_small_model():
     """A small decoder with the large configurations' attention geometry (grouped queries 6:1... head_dim 128)."""
     from paper_2508_18588_amd.runtime import Engine, Policy
     shape = ModelShape(n_layers=2, d_model=384, n_q_heads=6, n_kv_heads=1, head_dim=128, d_ffn=640, vocab=1024)
-    w = make_weights(shape, 31, norm_jitter=0.1, std=0.05)
+    w = make_weights(shape, 31, norm_jitter=0.1)
     rope = rope_table(4096, shape.head_dim)
     model = oracle.Model(shape, w, rope)
     prompts = make_prompts(3, 40, shape.vocab, 32)

@@ -165,6 +165,21 @@ def test_tree_logits_equal_plain_sequences(small):
         np.testing.assert_array_equal(lg[r], want)
 
 
+def test_loaded_cache_reproduces_computed_cache(small):
+    _, _, model = small
+    a = [9, 8, 7, 6, 5, 4]
+    s1 = oracle.Seq(model, 16)
+    for t in a[:4]:
+        s1.push(t, want_logits=False)
+    k = np.stack([[s1.kv(l, p)[0] for p in range(4)] for l in range(SHAPE.n_layers)])
+    v = np.stack([[s1.kv(l, p)[1] for p in range(4)] for l in range(SHAPE.n_layers)])
+    s2 = oracle.Seq(model, 16)
+    s2.load_kv(k, v)
+    assert len(s2) == 4
+    np.testing.assert_array_equal(s2.push(a[4]), s1.push(a[4]))
+    np.testing.assert_array_equal(s2.push(a[5]), s1.push(a[5]))
+
+
 def test_argmax_lowest_id_on_ties():
     assert oracle.argmax(np.array([1.0, 3.0, 3.0, 2.0])) == 1
     assert oracle.argmax(np.array([5.0])) == 0
