@@ -104,6 +104,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: run __graft_entry__.build() (hipcc, gfx950) first; "
                                "the HIP library is the only implementation of this path")
+        # The library must bind to the HIP runtime PyTorch has loaded: stream handles and device pointers passed
+        # across the C ABI belong to that runtime.  Importing torch first makes its libamdhip64 the one in use.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp = C.c_void_p
         L.hs_create.argtypes = [C.POINTER(hs_model_desc), C.POINTER(hs_weights), C.POINTER(hs_limits), C.POINTER(vp)]

@@ -14,6 +14,11 @@ hs_status fail(hs_ctx* ctx, hs_status code, const char* msg) {
     return code;
 }
 
+hs_status fail_hip(hs_ctx* ctx, const char* where, hipError_t e) {
+    ctx->err = std::string(where) + ": kernel launch failed: " + hipGetErrorString(e);
+    return HS_ERR_HIP;
+}
+
 void layout_workspace(hs_ctx* ctx) {
     const hs_model_desc& d = ctx->desc;
     const hs_limits& l = ctx->lim;
@@ -171,8 +176,9 @@ hs_status hs_draft(hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* s
     if (!policy_ok(ctx, &args->policy)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft: policy out of range");
     if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft: sequence state");
     if (!step_ok(step)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft: step arrays");
+    (void)hipGetLastError();  // drop stale errors of earlier, unrelated runtime calls
     hs_launch_draft(ctx, args, seq, step, (hipStream_t)stream);
-    if (hipGetLastError() != hipSuccess) return fail(ctx, HS_ERR_HIP, "hs_draft: launch failed");
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_draft", e);
     return HS_OK;
 }
 
@@ -196,6 +202,7 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
     const int qh = d.n_q_heads * d.head_dim;
     const int nqkv = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
 
+    (void)hipGetLastError();
     Prof whole{ctx, st}, pr{ctx, st};
     whole.begin(4);
     int whole_slot = ctx->ev_used;
@@ -246,7 +253,7 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
         (void)hipEventRecord(ctx->ev[whole_slot + 1], st);
         ctx->ev_last = whole_slot + 1;
     }
-    if (hipGetLastError() != hipSuccess) return fail(ctx, HS_ERR_HIP, "hs_verify: launch failed");
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_verify", e);
     return HS_OK;
 }
 
@@ -260,8 +267,9 @@ hs_status hs_accept(hs_ctx* ctx, const hs_accept_args* args, const hs_seq_state*
     if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept: sequence state");
     if (!step_ok(step)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept: step arrays");
     const float* logits = step->logits ? step->logits : (const float*)(ctx->ws + ctx->lay.logits);
+    (void)hipGetLastError();
     hs_launch_accept(ctx, args, seq, step, logits, (hipStream_t)stream);
-    if (hipGetLastError() != hipSuccess) return fail(ctx, HS_ERR_HIP, "hs_accept: launch failed");
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_accept", e);
     return HS_OK;
 }
 
@@ -272,8 +280,9 @@ hs_status hs_kv_commit(hs_ctx* ctx, const hs_kv_cache* cache, hs_seq_state* seq,
     if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: sequence state");
     if (!step_ok(step)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: step arrays");
     if (!policy_ok(ctx, policy)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: policy out of range");
+    (void)hipGetLastError();
     hs_launch_commit(ctx, cache, seq, step, policy, (hipStream_t)stream);
-    if (hipGetLastError() != hipSuccess) return fail(ctx, HS_ERR_HIP, "hs_kv_commit: launch failed");
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_kv_commit", e);
     return HS_OK;
 }
 
