@@ -100,6 +100,7 @@ def main():
     ar_pol = Policy(window=W, m_min=pol.m_min, k_fixed=0, k_max=wp["k_max"])
     eng.load_sequences(toks, budgets=[T] * B)
     eng.set_history([[np.zeros(0, np.int32)] for _ in range(B)])
+    eng.set_rows_hint(B)   # launch-shape hint only: one row per sequence without drafts
     for _ in range(3):
         eng.step(ar_pol)
     torch.cuda.synchronize()
@@ -127,6 +128,9 @@ def main():
             torch.cuda.synchronize()
             first = {k: v.cpu().numpy().copy() for k, v in eng.st.items()}
     torch.cuda.synchronize()
+    if args.warmup > 0:
+        eng.set_rows_hint(int(eng.st["row_off"][B].item()))   # rows of the last warm-up step
+        log(f"rows hint for the timed steps: {eng.c_step.rows_hint}")
     c0 = eng.counters.cpu().numpy().copy()
     len0 = eng.seq_len.cpu().numpy()[:B].astype(np.int64).copy()
     if not args.no_profile:

@@ -159,6 +159,8 @@ typedef struct hs_step {
     int32_t* n_out;        /* [batch] emitted tokens (a_b + 1; 0 for a finished sequence) */
     int32_t* out_tok;      /* [batch][k_max+1] emitted tokens */
     int32_t* path_row;     /* [batch][k_max+1] node index of the root and of each accepted node */
+    int32_t rows_hint;     /* HOST: rows M the caller expects this step (e.g. last step's row_off[batch]), 0 =
+                              unknown.  Only steers how kernels are launched; results do not depend on it. */
 } hs_step;
 
 typedef struct hs_accept_args {

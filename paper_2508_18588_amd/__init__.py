@@ -83,7 +83,7 @@ class hs_draft_args(C.Structure):
 class hs_step(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("draft_start", "match_len", "draft_len", "row_off", "tok", "pos", "parent",
                                           "anc_mask", "row2seq", "logits", "argmax", "accept_len", "n_out",
-                                          "out_tok", "path_row")]
+                                          "out_tok", "path_row")] + [("rows_hint", C.c_int32)]
 
 
 class hs_accept_args(C.Structure):

@@ -1,4 +1,5 @@
 // C-ABI entry points: argument validation, workspace layout, and the launch sequence of one decode iteration.
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -39,6 +40,10 @@ void layout_workspace(hs_ctx* ctx) {
     w.part_ml = take(M * d.n_q_heads * (size_t)ctx->max_parts * 2 * 4);
     w.logits = take(M * (size_t)d.vocab * 4);
     w.draft_best = take((size_t)l.max_batch * l.c_max * ctx->max_segs * 8);
+    size_t part_cols = std::max({(size_t)hs_gemm_chunks((int)nqkv, d.d_model) * nqkv,
+                                 (size_t)hs_gemm_chunks(d.d_model, (int)qh) * d.d_model,
+                                 (size_t)hs_gemm_chunks(d.d_model, d.d_ffn) * d.d_model});
+    w.gemm_part = take(M * part_cols * 4);
     w.total = off;
 }
 
@@ -201,6 +206,9 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
     float* logits = step->logits ? step->logits : (float*)(ctx->ws + ctx->lay.logits);
     const int qh = d.n_q_heads * d.head_dim;
     const int nqkv = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+    // Few rows expected: run the narrow projections split over K (same arithmetic, more workgroups).
+    const int hint = step->rows_hint > 0 ? step->rows_hint : m_max;
+    const bool few = hint <= 512;
 
     (void)hipGetLastError();
     Prof whole{ctx, st}, pr{ctx, st};
@@ -216,7 +224,7 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
         hs_launch_rmsnorm(ctx, x, ctx->norm1[l], xn, m_dev, st);
         pr.end();
         pr.begin(1);
-        hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->wqkv[l], nullptr, qkv, m_dev, m_max, nqkv, d.d_model, st);
+        hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->wqkv[l], nullptr, qkv, m_dev, m_max, nqkv, d.d_model, few, st);
         pr.end();
         pr.begin(3);
         hs_launch_rope_kv(ctx, l, cache, seq, step, qkv, q, st);
@@ -228,23 +236,23 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
         hs_launch_attention_merge(ctx, seq, step, attn, st);
         pr.end();
         pr.begin(1);
-        hs_launch_gemm(ctx, HS_EPI_ADD_F32, attn, ctx->wo[l], nullptr, x, m_dev, m_max, d.d_model, qh, st);
+        hs_launch_gemm(ctx, HS_EPI_ADD_F32, attn, ctx->wo[l], nullptr, x, m_dev, m_max, d.d_model, qh, few, st);
         pr.end();
         pr.begin(3);
         hs_launch_rmsnorm(ctx, x, ctx->norm2[l], xn, m_dev, st);
         pr.end();
         pr.begin(1);
-        hs_launch_gemm(ctx, HS_EPI_SWIGLU_BF16, xn, ctx->wgate[l], ctx->wup[l], act, m_dev, m_max, d.d_ffn, d.d_model, st);
+        hs_launch_gemm(ctx, HS_EPI_SWIGLU_BF16, xn, ctx->wgate[l], ctx->wup[l], act, m_dev, m_max, d.d_ffn, d.d_model, few, st);
         pr.end();
         pr.begin(1);
-        hs_launch_gemm(ctx, HS_EPI_ADD_F32, act, ctx->wdown[l], nullptr, x, m_dev, m_max, d.d_model, d.d_ffn, st);
+        hs_launch_gemm(ctx, HS_EPI_ADD_F32, act, ctx->wdown[l], nullptr, x, m_dev, m_max, d.d_model, d.d_ffn, few, st);
         pr.end();
     }
     pr.begin(3);
     hs_launch_rmsnorm(ctx, x, ctx->norm_f, xn, m_dev, st);
     pr.end();
     pr.begin(2);
-    hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->lm_head, nullptr, logits, m_dev, m_max, d.vocab, d.d_model, st);
+    hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->lm_head, nullptr, logits, m_dev, m_max, d.vocab, d.d_model, few, st);
     pr.end();
     pr.begin(3);
     hs_launch_argmax(ctx, logits, step->argmax, m_dev, st);

@@ -3,9 +3,16 @@
 //
 // Layout on gfx950: a workgroup of 4 wavefronts owns a 128x128 output tile; each wavefront a 64x64 quadrant as
 // 2x2 v_mfma_f32_32x32x16_bf16 tiles.  A and W tiles (128 x 64 bf16) are staged through LDS with a padded row
-// stride; the next k-tile is prefetched into registers while the current one feeds the matrix cores.  The
-// accumulation order over K is the same for every row, whatever M is: a row's result does not depend on which
-// other rows share the launch (this is what makes speculative and one-token decoding agree bit for bit).
+// stride; two k-tiles are kept in flight in registers while the current one feeds the matrix cores.
+//
+// Reduction order.  K is cut into a fixed number of chunks that depends only on the GEMM's shape (N, K).  Each
+// chunk is accumulated by the matrix cores on its own, and the chunk sums are added left to right in fp32.  This
+// one definition is executed in two ways that give bit-identical results: "serial" (one workgroup walks all
+// chunks, folding each finished chunk into a running total) for many rows, and "split" (one workgroup per chunk
+// writes its partial sum, a second kernel adds the partials in the same order) for few rows, where a 128-row tile
+// grid alone cannot fill 256 compute units and the weight stream would be latency-bound.  Which one runs is a pure
+// performance hint; a row's result never depends on how many other rows share the launch (this is what makes
+// speculative and one-token decoding agree bit for bit).
 //
 // The row count M lives on the device (number of draft-tree rows of this step); the grid covers m_max rows and
 // workgroups whose rows start beyond M exit at once.  Workgroup ids are spread so that all M-tiles that read the
@@ -14,19 +21,21 @@
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // plain vector: stays in registers
 
 namespace {
 
 constexpr int BM = 128, BN = 128, BK = 64;
 constexpr int LDS_STRIDE = BK + 8;  // bf16 elements; 144-byte rows keep 16-byte reads conflict-free
 
-struct Chunk { uint4 v; };
+enum { MODE_PLAIN = 0, MODE_SERIAL = 1, MODE_SPLIT = 2 };
 
-template <int EPI>
+template <int EPI, int MODE>
 __global__ __launch_bounds__(256) void gemm_bf16_mfma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                        const bf16_t* __restrict__ W2, void* __restrict__ Cout,
-                                                       const int32_t* __restrict__ m_dev, int N, int K, int m_tiles,
-                                                       int n_tiles) {
+                                                       float* __restrict__ part, const int32_t* __restrict__ m_dev,
+                                                       int m_max, int N, int K, int m_tiles, int n_tiles,
+                                                       int tiles_per_chunk) {
     __shared__ __attribute__((aligned(16))) bf16_t sA[BM * LDS_STRIDE];
     __shared__ __attribute__((aligned(16))) bf16_t sB[BN * LDS_STRIDE];
 
@@ -46,20 +55,27 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma(const bf16_t* __restrict__
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // global -> register staging: 4 x 16-byte chunks of A and of W per thread and k-tile
-    Chunk ra[4], rb[4];
+    const int nk = K / BK;
+    int kt0 = 0, kt1 = nk;
+    if (MODE == MODE_SPLIT) {
+        kt0 = blockIdx.y * tiles_per_chunk;
+        kt1 = min(nk, kt0 + tiles_per_chunk);
+    }
+
+    // global -> register staging: 4 x 16-byte chunks of A and of W per thread and k-tile, two k-tiles in flight.
+    // Rows beyond M (or N) are clamped to the last valid row: their products are computed and never stored, so
+    // every load is unconditional and the prefetch stays in registers.
+    u32x4 ra0[4], rb0[4], ra1[4], rb1[4];
     const bf16_t* a_ptr[4];
     const bf16_t* b_ptr[4];
-    bool a_ok[4], b_ok[4];
     int s_off[4];
 #pragma unroll
     for (int i = 0; i < 4; i++) {
         int c = tid + 256 * i;
         int r = c >> 3, c8 = (c & 7) * 8;
         s_off[i] = r * LDS_STRIDE + c8;
-        int gm = m0 + r;
-        a_ok[i] = gm < M;
-        a_ptr[i] = A + (size_t)(a_ok[i] ? gm : 0) * K + c8;
+        int gm = min(m0 + r, M - 1);
+        a_ptr[i] = A + (size_t)gm * K + c8;
         int gn;
         const bf16_t* wsrc = W;
         if (EPI == HS_EPI_SWIGLU_BF16) {
@@ -68,58 +84,78 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma(const bf16_t* __restrict__
         } else {
             gn = n0 + r;
         }
-        b_ok[i] = gn < N;
-        b_ptr[i] = wsrc + (size_t)(b_ok[i] ? gn : 0) * K + c8;
+        gn = min(gn, N - 1);
+        b_ptr[i] = wsrc + (size_t)gn * K + c8;
     }
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+#define HS_FETCH(RA, RB, KT)                                                              \
+    _Pragma("unroll") for (int i = 0; i < 4; i++) {                                       \
+        RA[i] = *reinterpret_cast<const u32x4*>(a_ptr[i] + (size_t)(KT) * BK);            \
+        RB[i] = *reinterpret_cast<const u32x4*>(b_ptr[i] + (size_t)(KT) * BK);            \
+    }
+#define HS_STAGE(RA, RB)                                                                  \
+    _Pragma("unroll") for (int i = 0; i < 4; i++) {                                       \
+        *reinterpret_cast<u32x4*>(&sA[s_off[i]]) = RA[i];                                 \
+        *reinterpret_cast<u32x4*>(&sB[s_off[i]]) = RB[i];                                 \
+    }
 
-    f32x16 acc[2][2];
+    f32x16 acc[2][2], total[2][2];
 #pragma unroll
     for (int i = 0; i < 2; i++)
 #pragma unroll
         for (int j = 0; j < 2; j++)
 #pragma unroll
-            for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
-
-    const int nk = K / BK;
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        ra[i].v = a_ok[i] ? *reinterpret_cast<const uint4*>(a_ptr[i]) : zero4;
-        rb[i].v = b_ok[i] ? *reinterpret_cast<const uint4*>(b_ptr[i]) : zero4;
-    }
+            for (int e = 0; e < 16; e++) {
+                acc[i][j][e] = 0.f;
+                if (MODE == MODE_SERIAL) total[i][j][e] = 0.f;
+            }
 
     const int arow = wm * 64 + (lane & 31);
     const int brow0 = (EPI == HS_EPI_SWIGLU_BF16) ? (wn * 32 + (lane & 31)) : (wn * 64 + (lane & 31));
     const int brow1 = (EPI == HS_EPI_SWIGLU_BF16) ? (64 + wn * 32 + (lane & 31)) : (wn * 64 + 32 + (lane & 31));
     const int koff = (lane >> 5) * 8;
 
-    for (int kt = 0; kt < nk; kt++) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            *reinterpret_cast<uint4*>(&sA[s_off[i]]) = ra[i].v;
-            *reinterpret_cast<uint4*>(&sB[s_off[i]]) = rb[i].v;
-        }
-        __syncthreads();
-        if (kt + 1 < nk) {
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                ra[i].v = a_ok[i] ? *reinterpret_cast<const uint4*>(a_ptr[i] + (size_t)(kt + 1) * BK) : zero4;
-                rb[i].v = b_ok[i] ? *reinterpret_cast<const uint4*>(b_ptr[i] + (size_t)(kt + 1) * BK) : zero4;
-            }
-        }
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ks++) {
-            bf16x8 fa0 = *reinterpret_cast<const bf16x8*>(&sA[arow * LDS_STRIDE + ks * 16 + koff]);
-            bf16x8 fa1 = *reinterpret_cast<const bf16x8*>(&sA[(arow + 32) * LDS_STRIDE + ks * 16 + koff]);
-            bf16x8 fb0 = *reinterpret_cast<const bf16x8*>(&sB[brow0 * LDS_STRIDE + ks * 16 + koff]);
-            bf16x8 fb1 = *reinterpret_cast<const bf16x8*>(&sB[brow1 * LDS_STRIDE + ks * 16 + koff]);
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb1, acc[1][1], 0, 0, 0);
-        }
-        __syncthreads();
+#define HS_COMPUTE(KT)                                                                                      \
+    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ks++) {                                                \
+        bf16x8 fa0 = *reinterpret_cast<const bf16x8*>(&sA[arow * LDS_STRIDE + ks * 16 + koff]);             \
+        bf16x8 fa1 = *reinterpret_cast<const bf16x8*>(&sA[(arow + 32) * LDS_STRIDE + ks * 16 + koff]);      \
+        bf16x8 fb0 = *reinterpret_cast<const bf16x8*>(&sB[brow0 * LDS_STRIDE + ks * 16 + koff]);            \
+        bf16x8 fb1 = *reinterpret_cast<const bf16x8*>(&sB[brow1 * LDS_STRIDE + ks * 16 + koff]);            \
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb0, acc[0][0], 0, 0, 0);                  \
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb1, acc[0][1], 0, 0, 0);                  \
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb0, acc[1][0], 0, 0, 0);                  \
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb1, acc[1][1], 0, 0, 0);                  \
+    }                                                                                                       \
+    if (MODE == MODE_SERIAL) {                                                                              \
+        /* end of a chunk: fold its sum into the running total (left-to-right chunk order) */               \
+        if (((KT) + 1) % tiles_per_chunk == 0 || (KT) + 1 == nk) {                                          \
+            _Pragma("unroll") for (int i = 0; i < 2; i++)                                                   \
+            _Pragma("unroll") for (int j = 0; j < 2; j++)                                                   \
+            _Pragma("unroll") for (int e = 0; e < 16; e++) {                                                \
+                total[i][j][e] += acc[i][j][e];                                                             \
+                acc[i][j][e] = 0.f;                                                                         \
+            }                                                                                               \
+        }                                                                                                   \
     }
+
+    if (kt0 < kt1) { HS_FETCH(ra0, rb0, kt0) }
+    if (kt0 + 1 < kt1) { HS_FETCH(ra1, rb1, kt0 + 1) }
+    for (int kt = kt0; kt < kt1; kt += 2) {
+        HS_STAGE(ra0, rb0)
+        __syncthreads();
+        if (kt + 2 < kt1) { HS_FETCH(ra0, rb0, kt + 2) }
+        HS_COMPUTE(kt)
+        __syncthreads();
+        if (kt + 1 < kt1) {
+            HS_STAGE(ra1, rb1)
+            __syncthreads();
+            if (kt + 3 < kt1) { HS_FETCH(ra1, rb1, kt + 3) }
+            HS_COMPUTE(kt + 1)
+            __syncthreads();
+        }
+    }
+#undef HS_FETCH
+#undef HS_STAGE
+#undef HS_COMPUTE
 
     // Epilogue.  Accumulator element e of a 32x32 tile: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
     const int lr = 4 * (lane >> 5), lc = lane & 31;
@@ -140,7 +176,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma(const bf16_t* __restrict__
                 }
         }
     } else {
-        float* C = reinterpret_cast<float*>(Cout);
+        float* C = (MODE == MODE_SPLIT) ? part + (size_t)blockIdx.y * m_max * N : reinterpret_cast<float*>(Cout);
 #pragma unroll
         for (int mi = 0; mi < 2; mi++)
 #pragma unroll
@@ -151,12 +187,38 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma(const bf16_t* __restrict__
                 for (int e = 0; e < 16; e++) {
                     int row = m0 + wm * 64 + mi * 32 + 8 * (e >> 2) + lr + (e & 3);
                     if (row < M) {
+                        float v = (MODE == MODE_SERIAL) ? total[mi][ni][e] : acc[mi][ni][e];
                         float* p = &C[(size_t)row * N + col];
-                        if (EPI == HS_EPI_ADD_F32) *p += acc[mi][ni][e];
-                        else *p = acc[mi][ni][e];
+                        if (MODE != MODE_SPLIT && EPI == HS_EPI_ADD_F32) *p += v;
+                        else *p = v;
                     }
                 }
             }
+    }
+}
+
+// Second pass of the split execution: add the chunk partials left to right, then store or add to the residual.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_split_reduce(const float* __restrict__ part, float* __restrict__ C,
+                                                          const int32_t* __restrict__ m_dev, int m_max, int N,
+                                                          int chunks) {
+    const int row = blockIdx.y;
+    if (row >= *m_dev) return;
+    const int c4 = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (c4 >= N) return;
+    const size_t off = (size_t)row * N + c4, stride = (size_t)m_max * N;
+    float4 t = *reinterpret_cast<const float4*>(part + off);
+    for (int s = 1; s < chunks; s++) {
+        float4 p = *reinterpret_cast<const float4*>(part + s * stride + off);
+        t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+    }
+    float4* dst = reinterpret_cast<float4*>(C + off);
+    if (EPI == HS_EPI_ADD_F32) {
+        float4 o = *dst;
+        o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
+        *dst = o;
+    } else {
+        *dst = t;
     }
 }
 
@@ -188,28 +250,57 @@ __global__ void gemm_bf16_plain(const bf16_t* __restrict__ A, const bf16_t* __re
 
 template <int EPI>
 void launch(const hs_ctx* ctx, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, const int32_t* m_dev,
-            int m_max, int n, int k, hipStream_t st) {
+            int m_max, int n, int k, bool few_rows, hipStream_t st) {
     if (ctx->flags & HS_FLAG_REFERENCE_KERNELS) {
         dim3 grid((n + 255) / 256, m_max);
         hipLaunchKernelGGL(gemm_bf16_plain<EPI>, grid, dim3(256), 0, st, a, w, w2, c, m_dev, n, k);
         return;
     }
     constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? 64 : 128;
-    int m_tiles = (m_max + BM - 1) / BM;
-    int n_tiles = (n + NCOLS - 1) / NCOLS;
-    int n_per_xcd = (n_tiles + 7) / 8;
-    int blocks = n_per_xcd * m_tiles * 8;
-    hipLaunchKernelGGL(gemm_bf16_mfma<EPI>, dim3(blocks), dim3(256), 0, st, a, w, w2, c, m_dev, n, k, m_tiles,
-                       n_tiles);
+    const int m_tiles = (m_max + BM - 1) / BM;
+    const int n_tiles = (n + NCOLS - 1) / NCOLS;
+    const int blocks = ((n_tiles + 7) / 8) * m_tiles * 8;
+    const int nk = k / BK;
+    int chunks = (EPI == HS_EPI_SWIGLU_BF16) ? 1 : hs_gemm_chunks(n, k);
+    const int tpc = (nk + chunks - 1) / chunks;
+    chunks = (nk + tpc - 1) / tpc;  // no empty chunk
+    float* part = reinterpret_cast<float*>(ctx->ws + ctx->lay.gemm_part);
+    if (chunks == 1) {
+        hipLaunchKernelGGL((gemm_bf16_mfma<EPI, MODE_PLAIN>), dim3(blocks), dim3(256), 0, st, a, w, w2, c, part, m_dev,
+                           m_max, n, k, m_tiles, n_tiles, tpc);
+    } else if (!few_rows) {
+        hipLaunchKernelGGL((gemm_bf16_mfma<EPI, MODE_SERIAL>), dim3(blocks), dim3(256), 0, st, a, w, w2, c, part,
+                           m_dev, m_max, n, k, m_tiles, n_tiles, tpc);
+    } else {
+        // only the first row tiles can be live when few rows are expected; the grid still covers them all
+        hipLaunchKernelGGL((gemm_bf16_mfma<EPI, MODE_SPLIT>), dim3(blocks, chunks), dim3(256), 0, st, a, w, w2, c,
+                           part, m_dev, m_max, n, k, m_tiles, n_tiles, tpc);
+        if (EPI != HS_EPI_SWIGLU_BF16)
+            hipLaunchKernelGGL((gemm_split_reduce<EPI>), dim3((n / 4 + 255) / 256, m_max), dim3(256), 0, st, part,
+                               reinterpret_cast<float*>(c), m_dev, m_max, n, chunks);
+    }
 }
 
 }  // namespace
 
+// Number of K chunks of a projection: a function of the shape alone.  Narrow outputs (few column tiles) get up
+// to 8 chunks so that the split execution can put several hundred workgroups on the chip; every chunk keeps at
+// least 4 k-tiles.
+int hs_gemm_chunks(int n, int k) {
+    const int n_tiles = (n + BN - 1) / BN;
+    int chunks = (512 + n_tiles - 1) / n_tiles;
+    if (chunks > 8) chunks = 8;
+    const int nk = k / BK;
+    if (chunks > nk / 4) chunks = nk / 4;
+    if (chunks < 1) chunks = 1;
+    return chunks;
+}
+
 void hs_launch_gemm(const hs_ctx* ctx, int epi, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c,
-                    const int32_t* m_dev, int m_max, int n, int k, hipStream_t st) {
+                    const int32_t* m_dev, int m_max, int n, int k, bool few_rows, hipStream_t st) {
     switch (epi) {
-        case HS_EPI_STORE_F32: launch<HS_EPI_STORE_F32>(ctx, a, w, w2, c, m_dev, m_max, n, k, st); break;
-        case HS_EPI_ADD_F32: launch<HS_EPI_ADD_F32>(ctx, a, w, w2, c, m_dev, m_max, n, k, st); break;
-        default: launch<HS_EPI_SWIGLU_BF16>(ctx, a, w, w2, c, m_dev, m_max, n, k, st); break;
+        case HS_EPI_STORE_F32: launch<HS_EPI_STORE_F32>(ctx, a, w, w2, c, m_dev, m_max, n, k, few_rows, st); break;
+        case HS_EPI_ADD_F32: launch<HS_EPI_ADD_F32>(ctx, a, w, w2, c, m_dev, m_max, n, k, few_rows, st); break;
+        default: launch<HS_EPI_SWIGLU_BF16>(ctx, a, w, w2, c, m_dev, m_max, n, k, few_rows, st); break;
     }
 }

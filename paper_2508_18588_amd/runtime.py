@@ -137,7 +137,7 @@ class Engine:
                               s["parent"].data_ptr(), s["anc_mask"].data_ptr(), s["row2seq"].data_ptr(),
                               self.logits.data_ptr() if self.logits is not None else None, s["argmax"].data_ptr(),
                               s["accept_len"].data_ptr(), s["n_out"].data_ptr(), s["out_tok"].data_ptr(),
-                              s["path_row"].data_ptr())
+                              s["path_row"].data_ptr(), getattr(self, "rows_hint", 0))
 
     def close(self):
         if self.ctx:
@@ -196,6 +196,11 @@ class Engine:
     def draft(self, policy: Policy):
         args = hs_draft_args(self.n_cand, self.hist.data_ptr(), self.hist_off.data_ptr(), policy.c())
         hs_draft(self.ctx, args, self.c_seq, self.c_step, self.stream())
+
+    def set_rows_hint(self, rows: int):
+        """Tell the library how many rows to expect (a launch-shape hint; results do not depend on it)."""
+        self.rows_hint = int(rows)
+        self.c_step.rows_hint = self.rows_hint
 
     def verify(self):
         hs_verify(self.ctx, self.c_cache, self.c_seq, self.c_step, self.stream())

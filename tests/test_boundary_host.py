@@ -31,7 +31,7 @@ def test_struct_sizes_match_the_header_layout():
     assert C.sizeof(hs.hs_limits) == 28
     assert C.sizeof(hs.hs_policy) == 32
     assert C.sizeof(hs.hs_weights) == 11 * 8
-    assert C.sizeof(hs.hs_step) == 15 * 8
+    assert C.sizeof(hs.hs_step) == 16 * 8
     assert C.sizeof(hs.hs_accept_args) == 16
     assert C.sizeof(hs.hs_kv_cache) == 24
 
@@ -100,7 +100,7 @@ def test_calls_reject_bad_arguments_without_launching(lib):
     with pytest.raises(hs.HsError):
         hs.hs_draft(ctx, args, full, step)
     ok_seq = hs.hs_seq_state(4, *([0x1000] * 7), None, 0, None)
-    ok_step = hs.hs_step(*([0x1000] * 15))
+    ok_step = hs.hs_step(*([0x1000] * 15), 0)
     for bad_pol in (hs.hs_policy(9, 3, 0, 4, 4, 2, 32, 2),     # window > w_max
                     hs.hs_policy(8, 9, 0, 4, 4, 2, 32, 2),     # m_min > window
                     hs.hs_policy(8, 3, 7, 4, 4, 2, 32, 2),     # unknown k_mode

@@ -263,3 +263,38 @@ def test_gqa_head_dim_128_small_model():
     eng.close()
     print("gqa128", stats)
     assert stats["emitted"] == 240 and stats["accepted"] > 60 and stats["flagged"] <= 6
+
+
+def test_split_and_serial_gemm_execution_agree_bitwise():
+    """The narrow projections cut K into a fixed number of chunks; with few rows each chunk runs in its own
+    workgroup and an ordered reduce adds them, with many rows one workgroup folds the chunks itself.  Both must
+    give the same bits (the row hint is a launch-shape hint only), and both must match the oracle."""
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    shape = ModelShape(n_layers=2, d_model=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ffn=2048, vocab=2048)
+    w = make_weights(shape, 41)
+    rope = rope_table(1024, shape.head_dim)
+    model = oracle.Model(shape, w, rope)
+    prompts = make_prompts(4, 33, shape.vocab, 42)
+    rollouts = gpu_ar_rollout(shape, w, rope, list(prompts), 40)
+    pol = Policy(window=8, m_min=3, k_fixed=6, k_max=6)
+    cands = make_histories(prompts, rollouts, 8, 0.1, 0.0, shape.vocab, seed=83)
+    results = []
+    for hint in (1, 100000):
+        eng = Engine(shape, w, rope, max_batch=4, k_max=6, c_max=1, max_len=33 + 40, shuffle_pages_seed=11)
+        eng.set_rows_hint(hint)
+        eng.load_sequences(list(prompts), budgets=[40] * 4)
+        eng.set_history(cands)
+        eng.prefill(list(prompts))
+        if hint == 1:
+            ob = OracleBatch(model, list(prompts), [40] * 4, 33 + 40 + 16)
+            stats = lockstep(eng, ob, cands, pol, max_steps=60, check_kv_layers=(0, 1))
+            print("split-gemm", stats)
+            assert stats["emitted"] == 160 and stats["accepted"] > 40
+        else:
+            while int(eng.budget_left.max()) > 0:
+                eng.step(pol)
+        torch.cuda.synchronize()
+        results.append((np_of(eng.tokens).copy(), np_of(eng.logits).copy(), np_of(eng.kc).copy(), np_of(eng.vc).copy()))
+        eng.close()
+    for a, b in zip(*results):
+        assert (a == b).all()
