@@ -127,6 +127,14 @@ def main():
         if i == 0:
             torch.cuda.synchronize()
             first = {k: v.cpu().numpy().copy() for k, v in eng.st.items()}
+            # logits of the sequence the oracle will re-compute (shortest context among those that drafted)
+            ro = first["row_off"]
+            cand = [b for b in range(B) if ro[b + 1] - ro[b] > 1]
+            if cand:
+                bs = min(cand, key=lambda i: len(toks[i]))
+                lg = eng.debug_tensor(3).view(torch.float32).view(-1, shape.vocab)
+                first["sample_seq"] = bs
+                first["sample_logits"] = lg[ro[bs]:ro[bs + 1]].cpu().numpy().copy()
     torch.cuda.synchronize()
     if args.warmup > 0:
         eng.set_rows_hint(int(eng.st["row_off"][B].item()))   # rows of the last warm-up step
@@ -209,11 +217,9 @@ def cpu_baseline(eng, shape, w, rope, toks, hists, pol, first, B, n_layers, weig
     import oracle
     if first is None:
         return None
-    ro = first["row_off"]
-    drafted = [b for b in range(B) if ro[b + 1] - ro[b] > 1]
-    if not drafted:
+    if "sample_seq" not in first:
         return None
-    b = min(drafted, key=lambda i: len(toks[i]))
+    b = first["sample_seq"]
     L = len(toks[b]) - 1
     t0 = time.time()
     wh = weights_to_host(w)
@@ -236,12 +242,23 @@ def cpu_baseline(eng, shape, w, rope, toks, hists, pol, first, B, n_layers, weig
     a, out, path = oracle.accept_greedy(tree["tok"], tree["parent"], [oracle.argmax(r) for r in lg])
     dt = time.time() - t1
     gpu_out = first["out_tok"][b, :first["n_out"][b]].tolist()
+    # parity of this sample: logits within the bf16 tolerance; tokens equal unless a visited row's top-2 margin in
+    # the oracle's logits is below that tolerance (a near-tie, decided by rounding)
+    err = float(np.abs(first["sample_logits"] - lg).max())
+    same = out.tolist() == gpu_out
+    margin = None
+    if not same:
+        n = min(len(gpu_out), len(out))
+        j = next((i for i in range(n) if gpu_out[i] != int(out[i])), n - 1)
+        row = np.sort(lg[int(path[j])])
+        margin = float(row[-1] - row[-2])
     log(f"cpu_baseline: {len(tree['tok'])} rows in {dt:.1f}s; oracle emitted {out.tolist()}, GPU emitted {gpu_out}")
     return {"value": round(a / dt, 4), "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"1 of {B} sequences (context {L} tokens), 1 speculative step of {len(tree['tok'])} rows "
                       f"through all {n_layers} layers; accepted {a}, committed {a + 1} tokens in {dt:.1f} s",
             "committed_tokens_per_s": round((a + 1) / dt, 4),
-            "same_tokens_as_gpu": out.tolist() == gpu_out}
+            "parity_sample": {"max_abs_logit_err_vs_gpu": round(err, 5), "same_tokens_as_gpu": same,
+                              "oracle_top2_margin_at_first_difference": margin}}
 
 
 if __name__ == "__main__":
