@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is then NOT the benchmark)")
+    ap.add_argument("--window", type=int, default=0,
+                    help="debug: tokens of previous-epoch text generated at set-up (default: the workload's 256)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events (roofline null)")
     args = ap.parse_args()
@@ -73,7 +75,7 @@ def main():
     shape = CONFIG_SHAPES[cfg]
     seed = config_seed(cfg)
     n_layers = args.layers or shape.n_layers
-    B, T = wp["batch"], wp["window_tokens"]
+    B, T = wp["batch"], (args.window or wp["window_tokens"])
     pol = Policy(**wp["policy"])
     W = pol.window
     if wp["ctx"][0] == "uniform":
@@ -87,7 +89,7 @@ def main():
     max_len = int(ctx.max()) + 1 + T
     rope = rope_device(max_len + 64, shape.head_dim)
     eng = Engine(shape, w, rope, max_batch=B, k_max=wp["k_max"], c_max=1, max_len=max_len,
-                 seq_caps=[int(c) + 1 + T for c in ctx], shuffle_pages_seed=seed & 0xFFFF, keep_logits=False)
+                 seq_caps=[int(c) + 1 + T for c in ctx], shuffle_pages_seed=(None if os.environ.get("HS_BENCH_PAGES") == "bump" else seed & 0xFFFF), keep_logits=False)
     # context: L_b cached positions (synthetic K/V of the scale a real prefill writes) + one committed root token
     kv_std = 0.02 * float(np.sqrt(shape.d_model))
     fill_kv_random(eng.kc, eng.vc, seed + 1, kv_std)
@@ -195,7 +197,8 @@ def main():
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wp["name"] + ("" if n_layers == shape.n_layers else f" [DEBUG: {n_layers} layers]"),
+        "config": {"workload": wp["name"] + ("" if n_layers == shape.n_layers else f" [DEBUG: {n_layers} layers]")
+                   + ("" if T == wp["window_tokens"] else f" [DEBUG: window {T}]"),
                    "rows_per_step": round(rows_per_step, 1),
                    "committed_tokens_per_s": round(emitted / elapsed, 1),
                    "accepted_per_seq_step": round(accepted / max(1, seq_steps), 3),

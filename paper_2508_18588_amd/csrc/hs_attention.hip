@@ -5,50 +5,166 @@
 // ancestors or itself.  The KV cache is read once per (sequence, KV head) and step, shared by all G * nn query
 // rows -- which is why verifying a whole draft costs about one KV traversal (Sec. 2.2 of the paper).
 //
-// Work decomposition: one workgroup per (partition of `part_keys` absolute positions, KV head, sequence).  K and
-// V pages are staged through LDS in tiles of 32 keys (two 16-token pages); the next tile is prefetched into
-// registers while the matrix cores work on the current one.  Query rows are split over the 4 wavefronts in tiles
-// of 32.  Scores are computed transposed, S^T = K . Q^T (v_mfma_f32_32x32x16_bf16, A = K tile from LDS, B = Q^T
-// held in registers), so that each lane owns one query row: the online-softmax statistics are per-lane scalars,
-// and the exponentiated scores are already in the register layout the second product O^T = V^T . P^T needs as
-// its B operand.  V is stored in the cache with the token index fastest so V^T tiles are plain 8-byte LDS reads.
+// Work decomposition.  Keys are cut into partitions of `part_keys` absolute positions; every (partition, KV head,
+// sequence) yields one partial result (unnormalised O, running max, running sum) per query row, and a second
+// kernel merges a row's partitions in index order.  Inside a partition, keys are visited in 32-key sub-tiles (two
+// 16-token pages), each through the same routine: scores transposed, S^T = K . Q^T (v_mfma_f32_32x32x16_bf16,
+// A = K tile from LDS, B = Q^T held in registers), so that each lane owns one query row -- the online-softmax
+// statistics are per-lane scalars and the exponentiated scores are already in the register layout the second
+// product O^T = V^T . P^T needs as its B operand.  V is stored in the cache with the token index fastest so V^T
+// tiles are plain 8-byte LDS reads.
 //
-// Partitions are keyed to absolute positions and merged in index order, masked keys contribute exact zeros, so a
-// row's result is bit-identical whether it is verified next to other draft rows or decoded alone.
+// Two ways to run a partition, chosen per sequence by its number of query rows R = G * nn:
+//   R <= 32 (one-token decoding and short drafts): one WAVEFRONT per partition.  The 4 wavefronts of a workgroup
+//     take 4 consecutive partitions and never synchronise: each stages its own sub-tiles in a private LDS slice.
+//     With a single 32-row tile the softmax arithmetic of a partition is one instruction stream; giving every
+//     wavefront its own stream keeps all four SIMDs of a compute unit busy and the KV stream bandwidth-bound.
+//   R > 32: one WORKGROUP per partition; K/V tiles of 64 keys are staged once and shared, the row tiles are
+//     dealt to the 4 wavefronts.
+// Both run the identical per-row arithmetic on the identical partitions: masked keys contribute exact zeros and
+// partitions merge in index order, so a row's result is bit-identical whether it is verified next to other draft
+// rows or decoded alone.
 #include "hs_internal.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// One 32-key sub-tile for one 32-row query tile: S^T = K.Q^T, online softmax per lane, O^T += V^T.P^T.
+// sK points at the sub-tile's 32 key rows, sV at its two 16-token pages.  Every query row's arithmetic is
+// independent of which other rows are in flight.
+template <int HD>
+__device__ inline void attn_subtile(const bf16_t* sK, const bf16_t* sV, const bf16x8 (&qf)[HD / 16],
+                                    f32x16 (&o)[HD / 32], float& m_run, float& l_run, uint64_t anc, int kbase, int L,
+                                    int total, float scale_log2, int half, int l32) {
+    constexpr int KS = HD + 8, VS = 20, NKS = HD / 16, NDT = HD / 32;
+    f32x16 s;
+#pragma unroll
+    for (int e = 0; e < 16; e++) s[e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ks++) {
+        bf16x8 ka = *reinterpret_cast<const bf16x8*>(&sK[l32 * KS + ks * 16 + half * 8]);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], s, 0, 0, 0);
+    }
+    // element e: key kbase + 8*(e/4) + 4*half + e%4, query row = this lane's
+    const bool need_mask = kbase + 32 > L;
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+        float v = s[e] * scale_log2;
+        if (need_mask) {
+            int kp = kbase + 8 * (e >> 2) + 4 * half + (e & 3);
+            bool vis = kp < L || (kp < total && ((anc >> (kp - L)) & 1ull));
+            v = vis ? v : -INFINITY;
+        }
+        s[e] = v;
+        tmax = fmaxf(tmax, v);
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    float m_new = fmaxf(m_run, tmax);
+    float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    float alpha = fast_exp2(m_run - m_safe);
+    float psum = 0.f;
+    bf16x8 pb[2];
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+        float p = fast_exp2(s[e] - m_safe);
+        psum += p;
+        pb[e >> 3][e & 7] = (__bf16)p;
+    }
+    psum += __shfl_xor(psum, 32);
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+    // the running maximum rarely moves after the first tiles: multiplying by exactly 1 is skipped
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int dt = 0; dt < NDT; dt++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) o[dt][e] *= alpha;
+    }
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+        for (int dt = 0; dt < NDT; dt++) {
+            const bf16_t* vrow = &sV[(kk * HD + dt * 32 + l32) * VS];
+            u32x2 lo = *reinterpret_cast<const u32x2*>(vrow + 4 * half);
+            u32x2 hi = *reinterpret_cast<const u32x2*>(vrow + 8 + 4 * half);
+            union { u32x4 u; bf16x8 v; } va;
+            va.u = u32x4{lo.x, lo.y, hi.x, hi.y};
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pb[kk], o[dt], 0, 0, 0);
+        }
+}
+
+// Query fragments (B operand of S^T) and ancestor mask of the lane's row; rows beyond R read as zero.
+template <int HD>
+__device__ inline void load_query_tile(const bf16_t* q, const uint64_t* anc_mask, int r0, int rt, int R, int G,
+                                       int hq, int j, int half, int l32, bf16x8 (&qf)[HD / 16], uint64_t& anc) {
+    int rho = rt * 32 + l32;
+    bool ok = rho < R;
+    int node = ok ? rho / G : 0;
+    int g = ok ? rho - node * G : 0;
+    anc = ok ? anc_mask[r0 + node] : 0ull;
+    const bf16_t* qp = q + ((size_t)(r0 + node) * hq + j * G + g) * HD;
+#pragma unroll
+    for (int ks = 0; ks < HD / 16; ks++) {
+        if (ok) {
+            qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + half * 8);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; e++) qf[ks][e] = (__bf16)0.f;
+        }
+    }
+}
+
+// Partial result of one partition for the lane's row: unnormalised O, running max (log2 domain) and sum.
+template <int HD>
+__device__ inline void store_partial(const f32x16 (&o)[HD / 32], float m_run, float l_run, float* part_o,
+                                     float* part_ml, int r0, int rt, int R, int G, int hq, int j, int max_parts,
+                                     int part, int half, int l32) {
+    int rho = rt * 32 + l32;
+    if (rho >= R) return;
+    int node = rho / G, g = rho - node * G;
+    size_t prow = ((size_t)(r0 + node) * hq + j * G + g) * max_parts + part;
+    float* po = part_o + prow * HD;
+#pragma unroll
+    for (int dt = 0; dt < HD / 32; dt++)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; g4++) {
+            float4 v = make_float4(o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]);
+            *reinterpret_cast<float4*>(po + dt * 32 + 8 * g4 + 4 * half) = v;
+        }
+    if (half == 0) {
+        part_ml[prow * 2] = m_run;
+        part_ml[prow * 2 + 1] = l_run;
+    }
+}
+
 template <int HD, int RTW>
-__global__ __launch_bounds__(256) void attn_verify_mfma(
+__global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc, size_t layer_off,
     const int32_t* __restrict__ seq_len, const int32_t* __restrict__ block_table, int max_blocks, int n_blocks,
     const int32_t* __restrict__ row_off, const uint64_t* __restrict__ anc_mask, float* __restrict__ part_o,
     float* __restrict__ part_ml, int max_parts, int part_keys, int hq, int hkv, float scale_log2) {
     constexpr int KS = HD + 8;        // sK row stride (bf16)
     constexpr int VS = 20;            // sV row stride (bf16): 16 tokens + pad, 40 bytes
-    constexpr int NCK = HD / 64;      // 16-byte K chunks per thread and tile
-    constexpr int NCV = HD / 64;      // 16-byte V chunks per thread and tile
     constexpr int NKS = HD / 16;      // k-steps of the score product
     constexpr int NDT = HD / 32;      // 32-wide tiles of the head dimension
-    __shared__ __attribute__((aligned(16))) bf16_t sK[32 * KS];
-    __shared__ __attribute__((aligned(16))) bf16_t sV[2 * HD * VS];
+    // 128 keys of K and 8 pages of V^T: four private 32-key slices (wavefront-per-partition path) or tiles of 64
+    // keys shared by the workgroup (workgroup-per-partition path).
+    __shared__ __attribute__((aligned(16))) bf16_t sK[128 * KS];
+    __shared__ __attribute__((aligned(16))) bf16_t sV[8 * HD * VS];
 
-    const int part = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
+    const int j = blockIdx.y, b = blockIdx.z;
     const int r0 = row_off[b];
     const int nn = row_off[b + 1] - r0;
     if (nn <= 0) return;
     const int L = seq_len[b] - 1;
     const int total = L + nn;
-    const int k_begin = part * part_keys;
-    if (k_begin >= total) return;
-    const int k_end = min(total, k_begin + part_keys);
     const int G = hq / hkv;
     const int R = nn * G;
     const int nrt = (R + 31) >> 5;
@@ -56,8 +172,97 @@ __global__ __launch_bounds__(256) void attn_verify_mfma(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int32_t* bt = block_table + (size_t)b * max_blocks;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    const bf16_t* kbase_ptr = kc + layer_off + (size_t)j * 16 * HD;   // + page * page_stride
+    const bf16_t* vbase_ptr = vc + layer_off + (size_t)j * HD * 16;   // + page * page_stride
+    const size_t page_stride = (size_t)hkv * 16 * HD;
 
-    // ---- per-row-tile state
+    if (nrt == 1) {
+        // ---------------- one wavefront per partition, no workgroup synchronisation ----------------
+        if (blockIdx.x & 3) return;
+        const int part = blockIdx.x + wave;
+        const int k_begin = part * part_keys;
+        if (k_begin >= total) return;
+        const int k_end = min(total, k_begin + part_keys);
+        bf16_t* sKw = sK + wave * 32 * KS;
+        bf16_t* sVw = sV + wave * 2 * HD * VS;
+
+        bf16x8 qf[NKS];
+        uint64_t anc;
+        load_query_tile<HD>(q, anc_mask, r0, 0, R, G, hq, j, half, l32, qf, anc);
+        f32x16 o[NDT];
+#pragma unroll
+        for (int dt = 0; dt < NDT; dt++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) o[dt][e] = 0.f;
+        float m_run = -INFINITY, l_run = 0.f;
+
+        // one 32-key sub-tile = 8 KB of K + 8 KB of V^T (HD = 128) = 2 x HD/16 16-byte chunks per lane
+        constexpr int NCW = HD / 16;
+        u32x4 rk[NCW], rv[NCW];
+#define HS_W_FETCH(KB)                                                                                            \
+        {                                                                                                         \
+            int pg[2];                                                                                            \
+            _Pragma("unroll") for (int kk = 0; kk < 2; kk++) {                                                    \
+                int p0 = (KB) + 16 * kk;                                                                          \
+                int pidx = p0 >> 4;                                                                               \
+                int page = (p0 < total && pidx < max_blocks) ? bt[pidx] : -1;                                     \
+                pg[kk] = (page >= 0 && page < n_blocks) ? page : -1;                                              \
+            }                                                                                                     \
+            _Pragma("unroll") for (int i = 0; i < NCW; i++) {                                                     \
+                int c = lane + 64 * i;                                                                            \
+                int key = c / (HD / 8), c16 = c % (HD / 8);                                                       \
+                int page = pg[key >> 4];                                                                          \
+                rk[i] = zero4;                                                                                    \
+                if (page >= 0)                                                                                    \
+                    rk[i] = *reinterpret_cast<const u32x4*>(kbase_ptr + page * page_stride + (key & 15) * HD + c16 * 8); \
+            }                                                                                                     \
+            _Pragma("unroll") for (int i = 0; i < NCW; i++) {                                                     \
+                int c = lane + 64 * i;                                                                            \
+                int kk = c / (HD * 2), rem = c % (HD * 2);                                                        \
+                int page = pg[kk];                                                                                \
+                rv[i] = zero4;                                                                                    \
+                if (page >= 0)                                                                                    \
+                    rv[i] = *reinterpret_cast<const u32x4*>(vbase_ptr + page * page_stride + rem * 8);            \
+            }                                                                                                     \
+        }
+        HS_W_FETCH(k_begin)
+        for (int kb = k_begin; kb < k_end; kb += 32) {
+            // a wavefront's LDS operations execute in order: the previous sub-tile's reads are done
+#pragma unroll
+            for (int i = 0; i < NCW; i++) {
+                int c = lane + 64 * i;
+                int key = c / (HD / 8), c16 = c % (HD / 8);
+                *reinterpret_cast<u32x4*>(&sKw[key * KS + c16 * 8]) = rk[i];
+            }
+#pragma unroll
+            for (int i = 0; i < NCW; i++) {
+                int c = lane + 64 * i;
+                int kk = c / (HD * 2), rem = c % (HD * 2);
+                int dim = rem >> 1, hf = rem & 1;
+                u32x2* dst = reinterpret_cast<u32x2*>(&sVw[(kk * HD + dim) * VS + hf * 8]);
+                dst[0] = u32x2{rv[i].x, rv[i].y};
+                dst[1] = u32x2{rv[i].z, rv[i].w};
+            }
+            if (kb + 32 < k_end) HS_W_FETCH(kb + 32)
+            attn_subtile<HD>(sKw, sVw, qf, o, m_run, l_run, anc, kb, L, total, scale_log2, half, l32);
+        }
+#undef HS_W_FETCH
+        store_partial<HD>(o, m_run, l_run, part_o, part_ml, r0, 0, R, G, hq, j, max_parts, part, half, l32);
+        return;
+    }
+
+    // ------------ one workgroup per partition: shared 64-key tiles, row tiles dealt to the wavefronts ------------
+    constexpr int TILE = 64;
+    constexpr int NCK = HD / 32;      // 16-byte K chunks per thread and tile
+    constexpr int NCV = HD / 32;      // 16-byte V chunks per thread and tile
+    const int part = blockIdx.x;
+    const int k_begin = part * part_keys;
+    if (k_begin >= total) return;
+    const int k_end = min(total, k_begin + part_keys);
+    // row tiles start at a workgroup-dependent wavefront so that two-tile sequences do not all use the same SIMDs
+    const int slot = (wave - (part + j + b)) & 3;
+
     bf16x8 qf[RTW][NKS];
     f32x16 o[RTW][NDT];
     float m_run[RTW], l_run[RTW];
@@ -65,23 +270,9 @@ __global__ __launch_bounds__(256) void attn_verify_mfma(
     bool rt_on[RTW];
 #pragma unroll
     for (int t = 0; t < RTW; t++) {
-        int rt = wave + 4 * t;
+        int rt = slot + 4 * t;
         rt_on[t] = rt < nrt;
-        int rho = rt * 32 + l32;
-        bool ok = rt_on[t] && rho < R;
-        int node = ok ? rho / G : 0;
-        int g = ok ? rho - node * G : 0;
-        anc[t] = ok ? anc_mask[r0 + node] : 0ull;
-        const bf16_t* qp = q + ((size_t)(r0 + node) * hq + j * G + g) * HD;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ks++) {
-            if (ok) {
-                qf[t][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + half * 8);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; e++) qf[t][ks][e] = (__bf16)0.f;
-            }
-        }
+        load_query_tile<HD>(q, anc_mask, r0, rt_on[t] ? rt : 0, rt_on[t] ? R : 0, G, hq, j, half, l32, qf[t], anc[t]);
 #pragma unroll
         for (int dt = 0; dt < NDT; dt++)
 #pragma unroll
@@ -90,140 +281,71 @@ __global__ __launch_bounds__(256) void attn_verify_mfma(
         l_run[t] = 0.f;
     }
 
-    // ---- global -> register prefetch of one 32-key tile
-    uint4 rk[NCK], rv[NCV];
-    auto fetch = [&](int kbase) {
-        // two pages of this tile
-        int pg[2];
-#pragma unroll
-        for (int kk = 0; kk < 2; kk++) {
-            int p0 = kbase + 16 * kk;
-            int pidx = p0 >> 4;
-            int page = (p0 < total && pidx < max_blocks) ? bt[pidx] : -1;
-            pg[kk] = (page >= 0 && page < n_blocks) ? page : -1;
-        }
-#pragma unroll
-        for (int i = 0; i < NCK; i++) {
-            int c = tid + 256 * i;
-            int key = c / (HD / 8), c16 = c % (HD / 8);
-            int page = pg[key >> 4];
-            rk[i] = make_uint4(0, 0, 0, 0);
-            if (page >= 0)
-                rk[i] = *reinterpret_cast<const uint4*>(kc + layer_off + (((size_t)page * hkv + j) * 16 + (key & 15)) * HD + c16 * 8);
-        }
-#pragma unroll
-        for (int i = 0; i < NCV; i++) {
-            int c = tid + 256 * i;
-            int kk = c / (HD * 2), rem = c % (HD * 2);
-            int page = pg[kk];
-            rv[i] = make_uint4(0, 0, 0, 0);
-            if (page >= 0)
-                rv[i] = *reinterpret_cast<const uint4*>(vc + layer_off + ((size_t)page * hkv + j) * HD * 16 + rem * 8);
-        }
-    };
-    auto stage = [&]() {
+    u32x4 rk[NCK], rv[NCV];
+#define HS_G_FETCH(KB)                                                                                            \
+    {                                                                                                             \
+        int pg[4];                                                                                                \
+        _Pragma("unroll") for (int kk = 0; kk < 4; kk++) {                                                        \
+            int p0 = (KB) + 16 * kk;                                                                              \
+            int pidx = p0 >> 4;                                                                                   \
+            int page = (p0 < total && pidx < max_blocks) ? bt[pidx] : -1;                                         \
+            pg[kk] = (page >= 0 && page < n_blocks) ? page : -1;                                                  \
+        }                                                                                                         \
+        _Pragma("unroll") for (int i = 0; i < NCK; i++) {                                                         \
+            int c = tid + 256 * i;                                                                                \
+            int key = c / (HD / 8), c16 = c % (HD / 8);                                                           \
+            int page = pg[key >> 4];                                                                              \
+            rk[i] = zero4;                                                                                        \
+            if (page >= 0)                                                                                        \
+                rk[i] = *reinterpret_cast<const u32x4*>(kbase_ptr + page * page_stride + (key & 15) * HD + c16 * 8); \
+        }                                                                                                         \
+        _Pragma("unroll") for (int i = 0; i < NCV; i++) {                                                         \
+            int c = tid + 256 * i;                                                                                \
+            int kk = c / (HD * 2), rem = c % (HD * 2);                                                            \
+            int page = pg[kk];                                                                                    \
+            rv[i] = zero4;                                                                                        \
+            if (page >= 0)                                                                                        \
+                rv[i] = *reinterpret_cast<const u32x4*>(vbase_ptr + page * page_stride + rem * 8);                \
+        }                                                                                                         \
+    }
+    HS_G_FETCH(k_begin)
+    for (int kbase = k_begin; kbase < k_end; kbase += TILE) {
+        __syncthreads();  // previous tile fully consumed
 #pragma unroll
         for (int i = 0; i < NCK; i++) {
             int c = tid + 256 * i;
             int key = c / (HD / 8), c16 = c % (HD / 8);
-            *reinterpret_cast<uint4*>(&sK[key * KS + c16 * 8]) = rk[i];
+            *reinterpret_cast<u32x4*>(&sK[key * KS + c16 * 8]) = rk[i];
         }
 #pragma unroll
         for (int i = 0; i < NCV; i++) {
             int c = tid + 256 * i;
             int kk = c / (HD * 2), rem = c % (HD * 2);
             int dim = rem >> 1, hf = rem & 1;
-            uint2* dst = reinterpret_cast<uint2*>(&sV[(kk * HD + dim) * VS + hf * 8]);
-            dst[0] = make_uint2(rv[i].x, rv[i].y);
-            dst[1] = make_uint2(rv[i].z, rv[i].w);
+            u32x2* dst = reinterpret_cast<u32x2*>(&sV[(kk * HD + dim) * VS + hf * 8]);
+            dst[0] = u32x2{rv[i].x, rv[i].y};
+            dst[1] = u32x2{rv[i].z, rv[i].w};
         }
-    };
-
-    fetch(k_begin);
-    for (int kbase = k_begin; kbase < k_end; kbase += 32) {
-        __syncthreads();  // previous tile fully consumed
-        stage();
         __syncthreads();
-        if (kbase + 32 < k_end) fetch(kbase + 32);
-
-        const bool need_mask = kbase + 32 > L;
+        if (kbase + TILE < k_end) HS_G_FETCH(kbase + TILE)
 #pragma unroll
-        for (int t = 0; t < RTW; t++) {
-            if (!rt_on[t]) continue;
-            f32x16 s;
+        for (int sub = 0; sub < 2; sub++) {
+            const int kb = kbase + 32 * sub;
+            if (kb >= k_end) break;
 #pragma unroll
-            for (int e = 0; e < 16; e++) s[e] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < NKS; ks++) {
-                bf16x8 ka = *reinterpret_cast<const bf16x8*>(&sK[l32 * KS + ks * 16 + half * 8]);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[t][ks], s, 0, 0, 0);
+            for (int t = 0; t < RTW; t++) {
+                if (!rt_on[t]) continue;
+                attn_subtile<HD>(sK + sub * 32 * KS, sV + sub * 2 * HD * VS, qf[t], o[t], m_run[t], l_run[t], anc[t],
+                                 kb, L, total, scale_log2, half, l32);
             }
-            // element e: key kbase + 8*(e/4) + 4*half + e%4, query row = this lane's
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int e = 0; e < 16; e++) {
-                float v = s[e] * scale_log2;
-                if (need_mask) {
-                    int kp = kbase + 8 * (e >> 2) + 4 * half + (e & 3);
-                    bool vis = kp < L || (kp < total && ((anc[t] >> (kp - L)) & 1ull));
-                    v = vis ? v : -INFINITY;
-                }
-                s[e] = v;
-                tmax = fmaxf(tmax, v);
-            }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            float m_new = fmaxf(m_run[t], tmax);
-            float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-            float alpha = fast_exp2(m_run[t] - m_safe);
-            float psum = 0.f;
-            bf16x8 pb[2];
-#pragma unroll
-            for (int e = 0; e < 16; e++) {
-                float p = fast_exp2(s[e] - m_safe);
-                psum += p;
-                pb[e >> 3][e & 7] = (__bf16)p;
-            }
-            psum += __shfl_xor(psum, 32);
-            l_run[t] = l_run[t] * alpha + psum;
-            m_run[t] = m_new;
-#pragma unroll
-            for (int dt = 0; dt < NDT; dt++)
-#pragma unroll
-                for (int e = 0; e < 16; e++) o[t][dt][e] *= alpha;
-#pragma unroll
-            for (int kk = 0; kk < 2; kk++)
-#pragma unroll
-                for (int dt = 0; dt < NDT; dt++) {
-                    const bf16_t* vrow = &sV[(kk * HD + dt * 32 + l32) * VS];
-                    uint2 lo = *reinterpret_cast<const uint2*>(vrow + 4 * half);
-                    uint2 hi = *reinterpret_cast<const uint2*>(vrow + 8 + 4 * half);
-                    union { uint4 u; bf16x8 v; } va;
-                    va.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
-                    o[t][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pb[kk], o[t][dt], 0, 0, 0);
-                }
         }
     }
-
-    // ---- partial results: unnormalised O, running max (log2 domain) and sum
+#undef HS_G_FETCH
 #pragma unroll
     for (int t = 0; t < RTW; t++) {
-        int rt = wave + 4 * t;
-        int rho = rt * 32 + l32;
-        if (!rt_on[t] || rho >= R) continue;
-        int node = rho / G, g = rho - node * G;
-        size_t prow = ((size_t)(r0 + node) * hq + j * G + g) * max_parts + part;
-        float* po = part_o + prow * HD;
-#pragma unroll
-        for (int dt = 0; dt < NDT; dt++)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; g4++) {
-                float4 v = make_float4(o[t][dt][4 * g4], o[t][dt][4 * g4 + 1], o[t][dt][4 * g4 + 2], o[t][dt][4 * g4 + 3]);
-                *reinterpret_cast<float4*>(po + dt * 32 + 8 * g4 + 4 * half) = v;
-            }
-        if (half == 0) {
-            part_ml[prow * 2] = m_run[t];
-            part_ml[prow * 2 + 1] = l_run[t];
-        }
+        if (!rt_on[t]) continue;
+        store_partial<HD>(o[t], m_run[t], l_run[t], part_o, part_ml, r0, slot + 4 * t, R, G, hq, j, max_parts, part,
+                          half, l32);
     }
 }
 

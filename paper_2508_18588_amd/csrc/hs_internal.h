@@ -11,7 +11,7 @@ typedef uint16_t bf16_t;  // storage type: upper half of an fp32
 
 // Keys per split-KV partition of the verify attention.  Partitions are keyed to absolute position, so a row's
 // reduction order does not depend on how many draft rows share its sequence.
-constexpr int HS_ATT_PART_DEFAULT = 2048;
+constexpr int HS_ATT_PART_DEFAULT = 512;
 // History segment scanned by one workgroup of the draft kernel.
 constexpr int HS_DRAFT_SEG = 4096;
 constexpr int HS_MAX_NODES = 64;  // ancestor masks are 64-bit
