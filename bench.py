@@ -55,6 +55,9 @@ def main():
                     help="debug: tokens of previous-epoch text generated at set-up (default: the workload's 256)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events (roofline null)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed steps run three 1 GiB device-to-device copies: a kernel of known traffic "
+                         "that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
@@ -208,6 +211,16 @@ def main():
                    "kv_resident_gb": round(float(len0.sum()) * kv_tok_bytes * n_layers / 1e9, 1), **extras},
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log(f"calibration copy: 3 x 1 GiB read + 1 GiB written in {(time.perf_counter() - t3) * 1e3:.2f} ms "
+            f"({3 * 2 * 2 ** 30 / (time.perf_counter() - t3) / 1e9:.0f} GB/s read+write)")
     eng.close()
     print(json.dumps(result), flush=True)
 

@@ -51,21 +51,20 @@ __device__ inline void attn_subtile(const bf16_t* sK, const bf16_t* sV, const bf
         bf16x8 ka = *reinterpret_cast<const bf16x8*>(&sK[l32 * KS + ks * 16 + half * 8]);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], s, 0, 0, 0);
     }
-    // element e: key kbase + 8*(e/4) + 4*half + e%4, query row = this lane's
-    const bool need_mask = kbase + 32 > L;
-    float tmax = -INFINITY;
+    // element e: key kbase + 8*(e/4) + 4*half + e%4, query row = this lane's.  Only tiles that reach past the
+    // cached prefix need the tree mask.
+    if (kbase + 32 > L) {
 #pragma unroll
-    for (int e = 0; e < 16; e++) {
-        float v = s[e] * scale_log2;
-        if (need_mask) {
+        for (int e = 0; e < 16; e++) {
             int kp = kbase + 8 * (e >> 2) + 4 * half + (e & 3);
             bool vis = kp < L || (kp < total && ((anc >> (kp - L)) & 1ull));
-            v = vis ? v : -INFINITY;
+            s[e] = vis ? s[e] : -INFINITY;
         }
-        s[e] = v;
-        tmax = fmaxf(tmax, v);
     }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    float tmax = s[0];
+#pragma unroll
+    for (int e = 1; e < 16; e++) tmax = fmaxf(tmax, s[e]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * scale_log2;   // scale > 0: the maximum commutes with it
     float m_new = fmaxf(m_run, tmax);
     float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
     float alpha = fast_exp2(m_run - m_safe);
@@ -73,7 +72,7 @@ __device__ inline void attn_subtile(const bf16_t* sK, const bf16_t* sV, const bf
     bf16x8 pb[2];
 #pragma unroll
     for (int e = 0; e < 16; e++) {
-        float p = fast_exp2(s[e] - m_safe);
+        float p = fast_exp2(__builtin_fmaf(s[e], scale_log2, -m_safe));
         psum += p;
         pb[e >> 3][e & 7] = (__bf16)p;
     }
@@ -98,6 +97,16 @@ __device__ inline void attn_subtile(const bf16_t* sK, const bf16_t* sV, const bf
             va.u = u32x4{lo.x, lo.y, hi.x, hi.y};
             o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pb[kk], o[dt], 0, 0, 0);
         }
+}
+
+// Page holding position p0, as a wavefront-uniform value.  Positions at or beyond `total` (nothing written yet) and
+// malformed table entries resolve to the sequence's first page: its keys are masked and its finite values are
+// multiplied by exact zeros, so every load can be unconditional.
+__device__ inline int safe_page(const int32_t* bt, int p0, int total, int max_blocks, int n_blocks) {
+    int pidx = p0 >> 4;
+    int page = (p0 < total && pidx < max_blocks) ? bt[pidx] : bt[0];
+    page = (page >= 0 && page < n_blocks) ? page : 0;
+    return __builtin_amdgcn_readfirstlane(page);
 }
 
 // Query fragments (B operand of S^T) and ancestor mask of the lane's row; rows beyond R read as zero.
@@ -172,7 +181,6 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int32_t* bt = block_table + (size_t)b * max_blocks;
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
     const bf16_t* kbase_ptr = kc + layer_off + (size_t)j * 16 * HD;   // + page * page_stride
     const bf16_t* vbase_ptr = vc + layer_off + (size_t)j * HD * 16;   // + page * page_stride
     const size_t page_stride = (size_t)hkv * 16 * HD;
@@ -197,53 +205,37 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
             for (int e = 0; e < 16; e++) o[dt][e] = 0.f;
         float m_run = -INFINITY, l_run = 0.f;
 
-        // one 32-key sub-tile = 8 KB of K + 8 KB of V^T (HD = 128) = 2 x HD/16 16-byte chunks per lane
-        constexpr int NCW = HD / 16;
-        u32x4 rk[NCW], rv[NCW];
+        // one 32-key sub-tile = two pages; a page's K block and V^T block are each 16*HD contiguous elements,
+        // copied as NCP 16-byte chunks per lane (chunk c = lane + 64*ii covers elements [8c, 8c+8))
+        constexpr int NCP = HD / 32;
+        u32x4 rk[2 * NCP], rv[2 * NCP];
 #define HS_W_FETCH(KB)                                                                                            \
         {                                                                                                         \
-            int pg[2];                                                                                            \
-            _Pragma("unroll") for (int kk = 0; kk < 2; kk++) {                                                    \
-                int p0 = (KB) + 16 * kk;                                                                          \
-                int pidx = p0 >> 4;                                                                               \
-                int page = (p0 < total && pidx < max_blocks) ? bt[pidx] : -1;                                     \
-                pg[kk] = (page >= 0 && page < n_blocks) ? page : -1;                                              \
-            }                                                                                                     \
-            _Pragma("unroll") for (int i = 0; i < NCW; i++) {                                                     \
-                int c = lane + 64 * i;                                                                            \
-                int key = c / (HD / 8), c16 = c % (HD / 8);                                                       \
-                int page = pg[key >> 4];                                                                          \
-                rk[i] = zero4;                                                                                    \
-                if (page >= 0)                                                                                    \
-                    rk[i] = *reinterpret_cast<const u32x4*>(kbase_ptr + page * page_stride + (key & 15) * HD + c16 * 8); \
-            }                                                                                                     \
-            _Pragma("unroll") for (int i = 0; i < NCW; i++) {                                                     \
-                int c = lane + 64 * i;                                                                            \
-                int kk = c / (HD * 2), rem = c % (HD * 2);                                                        \
-                int page = pg[kk];                                                                                \
-                rv[i] = zero4;                                                                                    \
-                if (page >= 0)                                                                                    \
-                    rv[i] = *reinterpret_cast<const u32x4*>(vbase_ptr + page * page_stride + rem * 8);            \
+            _Pragma("unroll") for (int pp = 0; pp < 2; pp++) {                                                    \
+                const size_t pofs = (size_t)safe_page(bt, (KB) + 16 * pp, total, max_blocks, n_blocks) * page_stride; \
+                const bf16_t* kp_ = kbase_ptr + pofs + lane * 8;                                                  \
+                const bf16_t* vp_ = vbase_ptr + pofs + lane * 8;                                                  \
+                _Pragma("unroll") for (int ii = 0; ii < NCP; ii++) {                                              \
+                    rk[pp * NCP + ii] = *reinterpret_cast<const u32x4*>(kp_ + ii * 512);                          \
+                    rv[pp * NCP + ii] = *reinterpret_cast<const u32x4*>(vp_ + ii * 512);                          \
+                }                                                                                                 \
             }                                                                                                     \
         }
         HS_W_FETCH(k_begin)
         for (int kb = k_begin; kb < k_end; kb += 32) {
             // a wavefront's LDS operations execute in order: the previous sub-tile's reads are done
 #pragma unroll
-            for (int i = 0; i < NCW; i++) {
-                int c = lane + 64 * i;
-                int key = c / (HD / 8), c16 = c % (HD / 8);
-                *reinterpret_cast<u32x4*>(&sKw[key * KS + c16 * 8]) = rk[i];
-            }
+            for (int pp = 0; pp < 2; pp++)
 #pragma unroll
-            for (int i = 0; i < NCW; i++) {
-                int c = lane + 64 * i;
-                int kk = c / (HD * 2), rem = c % (HD * 2);
-                int dim = rem >> 1, hf = rem & 1;
-                u32x2* dst = reinterpret_cast<u32x2*>(&sVw[(kk * HD + dim) * VS + hf * 8]);
-                dst[0] = u32x2{rv[i].x, rv[i].y};
-                dst[1] = u32x2{rv[i].z, rv[i].w};
-            }
+                for (int ii = 0; ii < NCP; ii++) {
+                    int c = lane + 64 * ii;
+                    int key = pp * 16 + c / (HD / 8), c16 = c % (HD / 8);
+                    *reinterpret_cast<u32x4*>(&sKw[key * KS + c16 * 8]) = rk[pp * NCP + ii];
+                    int dim = c >> 1, hf = c & 1;
+                    u32x2* dst = reinterpret_cast<u32x2*>(&sVw[(pp * HD + dim) * VS + hf * 8]);
+                    dst[0] = u32x2{rv[pp * NCP + ii].x, rv[pp * NCP + ii].y};
+                    dst[1] = u32x2{rv[pp * NCP + ii].z, rv[pp * NCP + ii].w};
+                }
             if (kb + 32 < k_end) HS_W_FETCH(kb + 32)
             attn_subtile<HD>(sKw, sVw, qf, o, m_run, l_run, anc, kb, L, total, scale_log2, half, l32);
         }
@@ -255,7 +247,7 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
     // ------------ one workgroup per partition: shared 64-key tiles, row tiles dealt to the wavefronts ------------
     constexpr int TILE = 64;
     constexpr int NCK = HD / 32;      // 16-byte K chunks per thread and tile
-    constexpr int NCV = HD / 32;      // 16-byte V chunks per thread and tile
+    constexpr int NCV = NCK;
     const int part = blockIdx.x;
     const int k_begin = part * part_keys;
     if (k_begin >= total) return;
@@ -281,31 +273,18 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
         l_run[t] = 0.f;
     }
 
+    // a 64-key tile = four pages = 8*HD 16-byte chunks of K and of V^T; chunk c = tid + 256*i lies in page
+    // c / (2*HD), which is uniform within a wavefront
     u32x4 rk[NCK], rv[NCV];
+    const int wave_c0 = tid & ~63;
 #define HS_G_FETCH(KB)                                                                                            \
     {                                                                                                             \
-        int pg[4];                                                                                                \
-        _Pragma("unroll") for (int kk = 0; kk < 4; kk++) {                                                        \
-            int p0 = (KB) + 16 * kk;                                                                              \
-            int pidx = p0 >> 4;                                                                                   \
-            int page = (p0 < total && pidx < max_blocks) ? bt[pidx] : -1;                                         \
-            pg[kk] = (page >= 0 && page < n_blocks) ? page : -1;                                                  \
-        }                                                                                                         \
         _Pragma("unroll") for (int i = 0; i < NCK; i++) {                                                         \
-            int c = tid + 256 * i;                                                                                \
-            int key = c / (HD / 8), c16 = c % (HD / 8);                                                           \
-            int page = pg[key >> 4];                                                                              \
-            rk[i] = zero4;                                                                                        \
-            if (page >= 0)                                                                                        \
-                rk[i] = *reinterpret_cast<const u32x4*>(kbase_ptr + page * page_stride + (key & 15) * HD + c16 * 8); \
-        }                                                                                                         \
-        _Pragma("unroll") for (int i = 0; i < NCV; i++) {                                                         \
-            int c = tid + 256 * i;                                                                                \
-            int kk = c / (HD * 2), rem = c % (HD * 2);                                                            \
-            int page = pg[kk];                                                                                    \
-            rv[i] = zero4;                                                                                        \
-            if (page >= 0)                                                                                        \
-                rv[i] = *reinterpret_cast<const u32x4*>(vbase_ptr + page * page_stride + rem * 8);                \
+            const int kk = (wave_c0 + 256 * i) / (2 * HD);                                                        \
+            const int within = (tid + 256 * i) % (2 * HD);                                                        \
+            const size_t pofs = (size_t)safe_page(bt, (KB) + 16 * kk, total, max_blocks, n_blocks) * page_stride; \
+            rk[i] = *reinterpret_cast<const u32x4*>(kbase_ptr + pofs + within * 8);                               \
+            rv[i] = *reinterpret_cast<const u32x4*>(vbase_ptr + pofs + within * 8);                               \
         }                                                                                                         \
     }
     HS_G_FETCH(k_begin)
@@ -313,15 +292,11 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
         __syncthreads();  // previous tile fully consumed
 #pragma unroll
         for (int i = 0; i < NCK; i++) {
-            int c = tid + 256 * i;
-            int key = c / (HD / 8), c16 = c % (HD / 8);
+            const int kk = (wave_c0 + 256 * i) / (2 * HD);
+            const int within = (tid + 256 * i) % (2 * HD);
+            int key = kk * 16 + within / (HD / 8), c16 = within % (HD / 8);
             *reinterpret_cast<u32x4*>(&sK[key * KS + c16 * 8]) = rk[i];
-        }
-#pragma unroll
-        for (int i = 0; i < NCV; i++) {
-            int c = tid + 256 * i;
-            int kk = c / (HD * 2), rem = c % (HD * 2);
-            int dim = rem >> 1, hf = rem & 1;
+            int dim = within >> 1, hf = within & 1;
             u32x2* dst = reinterpret_cast<u32x2*>(&sV[(kk * HD + dim) * VS + hf * 8]);
             dst[0] = u32x2{rv[i].x, rv[i].y};
             dst[1] = u32x2{rv[i].z, rv[i].w};
