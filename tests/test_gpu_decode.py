@@ -82,7 +82,8 @@ def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=()):
 
 
 def check_cache(eng, ob, layer):
-    """Cache contents at [0, L) must equal the K/V the oracle computed for the committed tokens."""
+    """Cache contents at [0, L) must equal the K/V the oracle computed for the committed tokens (K and V have the
+    logits' scale 0.02 sqrt(d_model), so the logit tolerance applies)."""
     shape = eng.shape
     hkv, h = shape.n_kv_heads, shape.head_dim
     kc = np_of(eng.kc).view(np.uint16).reshape(eng.n_layers, eng.n_blocks, hkv, 16, h)
@@ -95,8 +96,8 @@ def check_cache(eng, ob, layer):
             page, ip = bt[b, pos // 16], pos % 16
             gk = f(kc[layer, page, :, ip, :]).reshape(-1)
             gv = f(vc[layer, page, :, :, ip]).reshape(-1)
-            np.testing.assert_allclose(gk, k, atol=2e-2, rtol=2e-2)
-            np.testing.assert_allclose(gv, v, atol=2e-2, rtol=2e-2)
+            np.testing.assert_allclose(gk, k, atol=LOGIT_TOL, rtol=2e-2)
+            np.testing.assert_allclose(gv, v, atol=LOGIT_TOL, rtol=2e-2)
 
 
 def setup_rollout(shape, w, rope, B, prompt_len, n_new, seed):
