@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is then NOT the benchmark)")
     ap.add_argument("--window", type=int, default=0,
                     help="debug: tokens of previous-epoch text generated at set-up (default: the workload's 256)")
+    ap.add_argument("--reuse-all", action="store_true",
+                    help="debug: history = the rollout itself (every draft accepted, rows per step at their maximum)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events (roofline null)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -81,6 +83,8 @@ def main():
     B, T = wp["batch"], (args.window or wp["window_tokens"])
     pol = Policy(**wp["policy"])
     W = pol.window
+    if args.reuse_all:
+        wp["p_iid"], wp["p_span"] = 0.0, 0.0
     if wp["ctx"][0] == "uniform":
         ctx = lengths_uniform(B, wp["ctx"][1], wp["ctx"][2], seed)
     else:
@@ -201,7 +205,8 @@ def main():
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wp["name"] + ("" if n_layers == shape.n_layers else f" [DEBUG: {n_layers} layers]")
-                   + ("" if T == wp["window_tokens"] else f" [DEBUG: window {T}]"),
+                   + ("" if T == wp["window_tokens"] else f" [DEBUG: window {T}]")
+                   + (" [DEBUG: history == rollout]" if args.reuse_all else ""),
                    "rows_per_step": round(rows_per_step, 1),
                    "committed_tokens_per_s": round(emitted / elapsed, 1),
                    "accepted_per_seq_step": round(accepted / max(1, seq_steps), 3),

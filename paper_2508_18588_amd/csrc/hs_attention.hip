@@ -324,28 +324,46 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
     }
 }
 
-// Combine the partitions of one (row, query head) in partition order.
+// Combine the partitions of one (row, query head) in partition order: one wavefront per (row, head), four per
+// workgroup.  Lane p holds partition p's (max, sum); weights are broadcast from there.
 template <int HD>
-__global__ __launch_bounds__(64) void attn_merge(const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                                                  const int32_t* __restrict__ row2seq, const int32_t* __restrict__ row_off,
-                                                  const int32_t* __restrict__ seq_len, int batch, int max_parts,
-                                                  int part_keys, int hq, bf16_t* __restrict__ out) {
-    int row = blockIdx.x, head = blockIdx.y;
-    if (row >= row_off[batch]) return;
-    int b = row2seq[row];
-    int total = seq_len[b] - 1 + (row_off[b + 1] - row_off[b]);
-    int nparts = min(max_parts, (total + part_keys - 1) / part_keys);
-    size_t prow = ((size_t)row * hq + head) * max_parts;
+__global__ __launch_bounds__(256) void attn_merge(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                   const int32_t* __restrict__ row2seq, const int32_t* __restrict__ row_off,
+                                                   const int32_t* __restrict__ seq_len, int batch, int max_parts,
+                                                   int part_keys, int hq, bf16_t* __restrict__ out) {
+    const int row = blockIdx.x, head = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= row_off[batch] || head >= hq) return;
+    const int b = row2seq[row];
+    const int total = seq_len[b] - 1 + (row_off[b + 1] - row_off[b]);
+    const int nparts = min(max_parts, (total + part_keys - 1) / part_keys);
+    const size_t prow = ((size_t)row * hq + head) * max_parts;
     float mg = -INFINITY;
-    for (int p = 0; p < nparts; p++) mg = fmaxf(mg, part_ml[(prow + p) * 2]);
-    float den = 0.f;
-    for (int p = 0; p < nparts; p++) den += fast_exp2(part_ml[(prow + p) * 2] - mg) * part_ml[(prow + p) * 2 + 1];
-    for (int d = threadIdx.x; d < HD; d += 64) {
-        float acc = 0.f;
-        for (int p = 0; p < nparts; p++)
-            acc += fast_exp2(part_ml[(prow + p) * 2] - mg) * part_o[(prow + p) * HD + d];
-        out[((size_t)row * hq + head) * HD + d] = f32_to_bf16(acc / den);
+    for (int p0 = 0; p0 < nparts; p0 += 64) {
+        float m = (p0 + lane < nparts) ? part_ml[(prow + p0 + lane) * 2] : -INFINITY;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+        mg = fmaxf(mg, m);
     }
+    float den = 0.f, acc[HD / 64];
+#pragma unroll
+    for (int i = 0; i < HD / 64; i++) acc[i] = 0.f;
+    for (int p0 = 0; p0 < nparts; p0 += 64) {
+        float wl = 0.f, ll = 0.f;
+        if (p0 + lane < nparts) {
+            wl = fast_exp2(part_ml[(prow + p0 + lane) * 2] - mg);
+            ll = part_ml[(prow + p0 + lane) * 2 + 1];
+        }
+        const int n = min(64, nparts - p0);
+        for (int p = 0; p < n; p++) {     // partition order
+            float w = __shfl(wl, p);
+            den += w * __shfl(ll, p);
+            const float* po = part_o + (prow + p0 + p) * HD;
+#pragma unroll
+            for (int i = 0; i < HD / 64; i++) acc[i] += w * po[lane + 64 * i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < HD / 64; i++) out[((size_t)row * hq + head) * HD + lane + 64 * i] = f32_to_bf16(acc[i] / den);
 }
 
 // Plain kernel for debugging: one wavefront per (row, query head), keys visited one by one.
@@ -439,11 +457,11 @@ void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const
     const hs_model_desc& d = ctx->desc;
     float* part_o = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_o);
     float* part_ml = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_ml);
-    dim3 grid(ctx->lim.max_rows, d.n_q_heads);
+    dim3 grid(ctx->lim.max_rows, (d.n_q_heads + 3) / 4);
     if (d.head_dim == 128)
-        hipLaunchKernelGGL((attn_merge<128>), grid, dim3(64), 0, st, part_o, part_ml, step->row2seq, step->row_off,
+        hipLaunchKernelGGL((attn_merge<128>), grid, dim3(256), 0, st, part_o, part_ml, step->row2seq, step->row_off,
                            seq->seq_len, seq->batch, ctx->max_parts, ctx->att_part, d.n_q_heads, out);
     else
-        hipLaunchKernelGGL((attn_merge<64>), grid, dim3(64), 0, st, part_o, part_ml, step->row2seq, step->row_off,
+        hipLaunchKernelGGL((attn_merge<64>), grid, dim3(256), 0, st, part_o, part_ml, step->row2seq, step->row_off,
                            seq->seq_len, seq->batch, ctx->max_parts, ctx->att_part, d.n_q_heads, out);
 }

@@ -91,30 +91,37 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float* __restrict__ 
     }
 }
 
-__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int32_t* __restrict__ out,
-                                                      const int32_t* __restrict__ m_dev, int vocab) {
-    __shared__ float sv[4];
-    __shared__ int si[4];
+// One workgroup of 16 wavefronts per row; 16-byte loads where the row is aligned.  Ties resolve to the lowest id
+// at every level, so the result is the first maximum whatever the reduction shape.
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int32_t* __restrict__ out,
+                                                       const int32_t* __restrict__ m_dev, int vocab) {
+    __shared__ float sv[16];
+    __shared__ int si[16];
     int row = blockIdx.x;
     if (row >= *m_dev) return;
     const float* l = logits + (size_t)row * vocab;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int i = threadIdx.x; i < vocab; i += 256) {
-        float v = l[i];
-        if (v > bv) { bv = v; bi = i; }  // ascending i per thread: first maximum kept
+    auto take = [&](float v, int i) { if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; } };
+    if ((vocab & 3) == 0) {
+        const float4* l4 = reinterpret_cast<const float4*>(l);
+        for (int i = threadIdx.x; i < vocab / 4; i += 1024) {
+            float4 v = l4[i];
+            take(v.x, 4 * i); take(v.y, 4 * i + 1); take(v.z, 4 * i + 2); take(v.w, 4 * i + 3);
+        }
+    } else {
+        for (int i = threadIdx.x; i < vocab; i += 1024) take(l[i], i);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         float ov = __shfl_xor(bv, o);
         int oi = __shfl_xor(bi, o);
-        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        take(ov, oi);
     }
     if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        for (int w = 1; w < 4; w++)
-            if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+        for (int w = 1; w < 16; w++) take(sv[w], si[w]);
         out[row] = bi;
     }
 }
@@ -144,6 +151,6 @@ void hs_launch_rope_kv(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, c
 
 void hs_launch_argmax(const hs_ctx* ctx, const float* logits, int32_t* argmax, const int32_t* m_dev,
                       hipStream_t st) {
-    hipLaunchKernelGGL(argmax_kernel, dim3(ctx->lim.max_rows), dim3(256), 0, st, logits, argmax, m_dev,
+    hipLaunchKernelGGL(argmax_kernel, dim3(ctx->lim.max_rows), dim3(1024), 0, st, logits, argmax, m_dev,
                        ctx->desc.vocab);
 }
