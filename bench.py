@@ -131,8 +131,10 @@ def main():
 
     # ---- warm-up, then the timed region
     first = None
+    warm_rows = []
     for i in range(args.warmup):
         eng.step(pol)
+        warm_rows.append(int(eng.st["row_off"][B].item()))
         if i == 0:
             torch.cuda.synchronize()
             first = {k: v.cpu().numpy().copy() for k, v in eng.st.items()}
@@ -146,7 +148,10 @@ def main():
                 first["sample_logits"] = lg[ro[bs]:ro[bs + 1]].cpu().numpy().copy()
     torch.cuda.synchronize()
     if args.warmup > 0:
-        eng.set_rows_hint(int(eng.st["row_off"][B].item()))   # rows of the last warm-up step
+        # launch-shape hint: mean rows of the warm-up steps after the first (in which every sequence drafts a full
+        # window because all of them start in sync with their history)
+        tail = warm_rows[1:] or warm_rows
+        eng.set_rows_hint(-(-sum(tail) // len(tail)))
         log(f"rows hint for the timed steps: {eng.c_step.rows_hint}")
     c0 = eng.counters.cpu().numpy().copy()
     len0 = eng.seq_len.cpu().numpy()[:B].astype(np.int64).copy()

@@ -208,7 +208,6 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
     const int nqkv = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
     // Few rows expected: run the narrow projections split over K (same arithmetic, more workgroups).
     const int hint = step->rows_hint > 0 ? step->rows_hint : m_max;
-    const bool few = hint <= 512;
 
     (void)hipGetLastError();
     Prof whole{ctx, st}, pr{ctx, st};
@@ -224,7 +223,7 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
         hs_launch_rmsnorm(ctx, x, ctx->norm1[l], xn, m_dev, st);
         pr.end();
         pr.begin(1);
-        hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->wqkv[l], nullptr, qkv, m_dev, m_max, nqkv, d.d_model, few, st);
+        hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->wqkv[l], nullptr, qkv, m_dev, m_max, nqkv, d.d_model, hint, st);
         pr.end();
         pr.begin(3);
         hs_launch_rope_kv(ctx, l, cache, seq, step, qkv, q, st);
@@ -236,23 +235,23 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
         hs_launch_attention_merge(ctx, seq, step, attn, st);
         pr.end();
         pr.begin(1);
-        hs_launch_gemm(ctx, HS_EPI_ADD_F32, attn, ctx->wo[l], nullptr, x, m_dev, m_max, d.d_model, qh, few, st);
+        hs_launch_gemm(ctx, HS_EPI_ADD_F32, attn, ctx->wo[l], nullptr, x, m_dev, m_max, d.d_model, qh, hint, st);
         pr.end();
         pr.begin(3);
         hs_launch_rmsnorm(ctx, x, ctx->norm2[l], xn, m_dev, st);
         pr.end();
         pr.begin(1);
-        hs_launch_gemm(ctx, HS_EPI_SWIGLU_BF16, xn, ctx->wgate[l], ctx->wup[l], act, m_dev, m_max, d.d_ffn, d.d_model, few, st);
+        hs_launch_gemm(ctx, HS_EPI_SWIGLU_BF16, xn, ctx->wgate[l], ctx->wup[l], act, m_dev, m_max, d.d_ffn, d.d_model, hint, st);
         pr.end();
         pr.begin(1);
-        hs_launch_gemm(ctx, HS_EPI_ADD_F32, act, ctx->wdown[l], nullptr, x, m_dev, m_max, d.d_model, d.d_ffn, few, st);
+        hs_launch_gemm(ctx, HS_EPI_ADD_F32, act, ctx->wdown[l], nullptr, x, m_dev, m_max, d.d_model, d.d_ffn, hint, st);
         pr.end();
     }
     pr.begin(3);
     hs_launch_rmsnorm(ctx, x, ctx->norm_f, xn, m_dev, st);
     pr.end();
     pr.begin(2);
-    hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->lm_head, nullptr, logits, m_dev, m_max, d.vocab, d.d_model, few, st);
+    hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->lm_head, nullptr, logits, m_dev, m_max, d.vocab, d.d_model, hint, st);
     pr.end();
     pr.begin(3);
     hs_launch_argmax(ctx, logits, step->argmax, m_dev, st);

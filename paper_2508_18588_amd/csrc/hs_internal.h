@@ -63,9 +63,10 @@ static inline __host__ __device__ bf16_t f32_to_bf16(float f) {
 // GEMM family: C[M,N] (+)= A[M,K] . W[N,K]^T, A and W bf16, fp32 accumulation in a fixed k order.
 // m_dev points at the row count M on the device; the grid covers m_max rows and tiles beyond M exit.
 enum { HS_EPI_STORE_F32 = 0, HS_EPI_ADD_F32 = 1, HS_EPI_SWIGLU_BF16 = 2 };
-// few_rows selects the split execution (one workgroup per K chunk + an ordered reduce); results are identical.
+// rows_hint (host-side estimate of the live row count) selects the tile height and the split execution
+// (one workgroup per K chunk + an ordered reduce); results are identical whatever it is.
 void hs_launch_gemm(const hs_ctx* ctx, int epi, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c,
-                    const int32_t* m_dev, int m_max, int n, int k, bool few_rows, hipStream_t st);
+                    const int32_t* m_dev, int m_max, int n, int k, int rows_hint, hipStream_t st);
 int hs_gemm_chunks(int n, int k);
 
 void hs_launch_embed(const hs_ctx* ctx, const hs_step* step, int batch, float* x, hipStream_t st);
