@@ -1,12 +1,16 @@
 // bf16 MFMA GEMMs for the dense projections of the verify forward pass (QKV, O, gate/up with SwiGLU epilogue,
 // down, LM head):  C[M,N] (+)= A[M,K] . W[N,K]^T,  both operands K-contiguous, fp32 accumulation.
 //
-// Layout on gfx950: a workgroup of 4 wavefronts owns a BM x 128 output tile, BM = 128 or 256; each wavefront a
-// (BM/2) x 64 quadrant as (BM/64) x 2 v_mfma_f32_32x32x16_bf16 tiles.  A and W tiles (64 deep in K) are staged
-// through LDS with a padded row stride.  The weight stream comes from HBM and is kept two k-tiles ahead in
-// registers; the activations come from L2 and are kept one k-tile ahead.  The 256-row tile reads every weight once
-// for up to 256 rows -- the shape of a verify step with a few draft tokens per sequence, which is weight-streaming
-// bound -- the 128-row tile serves one-token decoding (rows = sequences).
+// Layout on gfx950: a workgroup of 4 wavefronts owns a BM x 128 output tile (BM = 64 * MI; 128 is what runs);
+// each wavefront a (BM/2) x 64 quadrant as (BM/64) x 2 v_mfma_f32_32x32x16_bf16 tiles.  The operand tiles, 64
+// deep in K, travel from global memory straight into LDS (global_load_lds_dwordx4: no staging registers) through
+// two rings: activations, which come from L2 with a short latency, are double-buffered; weights, which stream from
+// HBM exactly once, get SW stages, so that SW-1 weight tiles per workgroup are in flight while one is being
+// multiplied.  At a few hundred rows these GEMMs live on weight bytes in flight and on every workgroup of the grid
+// being resident at once (80 KB of LDS per workgroup: two per compute unit), not on matrix-core rate.  The
+// load writes lane i's 16 bytes at LDS offset 16*i of a wavefront-uniform base, so a tile row is 128 unpadded
+// bytes; bank conflicts of the fragment reads are avoided by an XOR swizzle of the 16-byte chunk index with bits of
+// the row index, applied on the global side (which chunk a lane fetches).
 //
 // Reduction order.  K is cut into a fixed number of chunks that depends only on the GEMM's shape (N, K).  Each
 // chunk is accumulated by the matrix cores on its own, and the chunk sums are added left to right in fp32.  This
@@ -17,48 +21,75 @@
 // by the caller's row hint; a row's result never depends on how many other rows share the launch (this is what
 // makes speculative and one-token decoding agree bit for bit).
 //
-// The row count M lives on the device (number of draft-tree rows of this step); the grid covers m_max rows and
-// workgroups whose rows start beyond M exit at once.  Workgroup ids are spread so that all M-tiles that read the
-// same W-tile run on the same XCD (ids are dealt round-robin to the 8 XCDs, each with its own L2).
+// The row count M lives on the device (number of draft-tree rows of this step).  The grid holds as many row tiles
+// as the host-side row hint suggests; a workgroup walks row tiles with that stride until it passes M, so any M up
+// to m_max is covered whatever the hint was.  Workgroup ids are spread so that all row tiles that read the same
+// W tile run on the same XCD (ids are dealt round-robin to the 8 XCDs, each with its own L2).
 #include "hs_internal.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // plain vector: stays in registers
 
 namespace {
 
 constexpr int BN = 128, BK = 64;
-constexpr int LDS_STRIDE = BK + 8;  // bf16 elements; 144-byte rows keep 16-byte reads conflict-free
+constexpr int ROW_BYTES = BK * 2;  // one tile row in LDS: 8 chunks of 16 bytes
 
 enum { MODE_PLAIN = 0, MODE_SERIAL = 1, MODE_SPLIT = 2 };
 
-// MI = 32-row MFMA tiles per wavefront in M: the workgroup tile is BM = 64 * MI rows.
-template <int EPI, int MODE, int MI>
-__global__ __launch_bounds__(256) void gemm_bf16_mfma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+// vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
+#define HS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+// Chunk swizzle of tile row r: consecutive rows 0..15 map to the 16 distinct (row parity, chunk) bank groups, and
+// rows 0..7 to even values, so that the two k-halves of a fragment read (chunks c and c^1) never collide either.
+__device__ __forceinline__ int swz(int r) { return (((r >> 1) & 3) << 1) | ((r >> 3) & 1); }
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// 16 bytes per lane from global memory straight into LDS: lane i's data lands at LDS byte offset lds_off + 16 * i
+// (lds_off is wavefront-uniform and travels in M0).  Counted by vmcnt like any other load.  Issued as inline
+// assembly so that the compiler's wait-count bookkeeping does not see it: told about such a load it treats every
+// later LDS read as possibly returning out of order and waits for all of them at once, which serialises fragment
+// reads and matrix-core work; the kernel places the vmcnt waits for these loads itself.  Any wait the compiler
+// inserts for its own loads can only be stricter than needed, because loads complete in issue order.
+__device__ __forceinline__ void load_to_lds_16(const unsigned char* src, unsigned lds_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_off), "v"(src) : "memory", "m0");
+}
+
+}  // namespace
+
+// MI = 32-row MFMA tiles per wavefront in M: the workgroup tile is BM = 64 * MI rows.  SW = stages of the weight
+// ring (the activation ring has two).
+// (External linkage: the host takes the kernel's address to raise its dynamic LDS limit.)
+template <int EPI, int MODE, int MI, int SW>
+__global__ __launch_bounds__(256) void hs_gemm_bf16_mfma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                        const bf16_t* __restrict__ W2, void* __restrict__ Cout,
                                                        float* __restrict__ part, const int32_t* __restrict__ m_dev,
                                                        int m_max, int N, int K, int m_tiles, int n_tiles,
                                                        int tiles_per_chunk) {
     constexpr int BM = 64 * MI;
-    constexpr int NA = BM / 32;  // 16-byte A chunks per thread and k-tile
-    __shared__ __attribute__((aligned(16))) bf16_t sA[BM * LDS_STRIDE];
-    __shared__ __attribute__((aligned(16))) bf16_t sB[BN * LDS_STRIDE];
+    constexpr int NLA = BM / 32;        // 1 KB load instructions per wavefront and k-tile for the A tile
+    constexpr int NLB = BN / 32;        // ... and for the W tile
+    constexpr int SA = 2;
+    constexpr int A_BYTES = BM * ROW_BYTES, W_BYTES = BN * ROW_BYTES;
+    constexpr int W_RING = SA * A_BYTES;  // byte offset of the weight ring
+    static_assert(SW == 2 || SW == 3, "the wait counts below cover two or three weight stages");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    // LDS byte offset of the ring (what M0 carries): the 32-bit value of the pointer in the LDS address space
+    const unsigned smem_off = (unsigned)(size_t)(lds_ptr_t)smem;
 
     const int M = *m_dev;
     // XCD-aware tile assignment: id -> (xcd, local); an XCD walks its N-tiles, M fastest.
     const int id = blockIdx.x;
     const int xcd = id & 7, local = id >> 3;
     const int n_tile = (local / m_tiles) * 8 + xcd;
-    const int m_tile = local % m_tiles;
     if (n_tile >= n_tiles) return;
-    const int m0 = m_tile * BM;
-    if (m0 >= M) return;
     // SwiGLU: the tile's 128 B-rows are 64 gate rows followed by the 64 up rows of the same output columns.
     constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? 64 : 128;
     const int n0 = n_tile * NCOLS;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
 
     const int nk = K / BK;
@@ -68,24 +99,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma(const bf16_t* __restrict__
         kt1 = min(nk, kt0 + tiles_per_chunk);
     }
 
-    // Rows beyond M (or N) are clamped to the last valid row: their products are computed and never stored, so
-    // every load is unconditional and the prefetch stays in registers.
-    u32x4 ra[NA], rb0[4], rb1[4];
-    const bf16_t* a_ptr[NA];
-    const bf16_t* b_ptr[4];
-    int sa_off[NA], sb_off[4];
+    // Load geometry: instruction j of wavefront w fills the 1 KB block (4j + w) of a tile = its rows 8(4j+w)..+7;
+    // lane i lands on row i/8, chunk position i%8 and therefore fetches chunk (i%8) ^ swz(row).  Rows beyond M
+    // (or N) are clamped to the last valid row: their products are computed and never stored.
+    const int lrow = lane >> 3, lpos = lane & 7;
+    const unsigned char* b_src[NLB];
 #pragma unroll
-    for (int i = 0; i < NA; i++) {
-        int c = tid + 256 * i;
-        int r = c >> 3, c8 = (c & 7) * 8;
-        sa_off[i] = r * LDS_STRIDE + c8;
-        a_ptr[i] = A + (size_t)min(m0 + r, M - 1) * K + c8;
-    }
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        int c = tid + 256 * i;
-        int r = c >> 3, c8 = (c & 7) * 8;
-        sb_off[i] = r * LDS_STRIDE + c8;
+    for (int j = 0; j < NLB; j++) {
+        const int r = (4 * j + wave) * 8 + lrow;
         int gn;
         const bf16_t* wsrc = W;
         if (EPI == HS_EPI_SWIGLU_BF16) {
@@ -94,143 +115,182 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma(const bf16_t* __restrict__
         } else {
             gn = n0 + r;
         }
-        b_ptr[i] = wsrc + (size_t)min(gn, N - 1) * K + c8;
-    }
-#define HS_FETCH_A(KT)                                                                     \
-    _Pragma("unroll") for (int i = 0; i < NA; i++)                                         \
-        ra[i] = *reinterpret_cast<const u32x4*>(a_ptr[i] + (size_t)(KT) * BK);
-#define HS_FETCH_B(RB, KT)                                                                 \
-    _Pragma("unroll") for (int i = 0; i < 4; i++)                                          \
-        RB[i] = *reinterpret_cast<const u32x4*>(b_ptr[i] + (size_t)(KT) * BK);
-#define HS_STAGE(RB)                                                                       \
-    _Pragma("unroll") for (int i = 0; i < NA; i++)                                         \
-        *reinterpret_cast<u32x4*>(&sA[sa_off[i]]) = ra[i];                                 \
-    _Pragma("unroll") for (int i = 0; i < 4; i++)                                          \
-        *reinterpret_cast<u32x4*>(&sB[sb_off[i]]) = RB[i];
-
-    f32x16 acc[MI][2], total[MI][2];
-#pragma unroll
-    for (int i = 0; i < MI; i++)
-#pragma unroll
-        for (int j = 0; j < 2; j++)
-#pragma unroll
-            for (int e = 0; e < 16; e++) {
-                acc[i][j][e] = 0.f;
-                if (MODE == MODE_SERIAL) total[i][j][e] = 0.f;
-            }
-
-    const int arow = wm * (BM / 2) + (lane & 31);
-    const int brow0 = (EPI == HS_EPI_SWIGLU_BF16) ? (wn * 32 + (lane & 31)) : (wn * 64 + (lane & 31));
-    const int brow1 = (EPI == HS_EPI_SWIGLU_BF16) ? (64 + wn * 32 + (lane & 31)) : (wn * 64 + 32 + (lane & 31));
-    const int koff = (lane >> 5) * 8;
-
-#define HS_COMPUTE(KT)                                                                                      \
-    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ks++) {                                                \
-        bf16x8 fb0 = *reinterpret_cast<const bf16x8*>(&sB[brow0 * LDS_STRIDE + ks * 16 + koff]);            \
-        bf16x8 fb1 = *reinterpret_cast<const bf16x8*>(&sB[brow1 * LDS_STRIDE + ks * 16 + koff]);            \
-        _Pragma("unroll") for (int mi = 0; mi < MI; mi++) {                                                 \
-            bf16x8 fa = *reinterpret_cast<const bf16x8*>(&sA[(arow + 32 * mi) * LDS_STRIDE + ks * 16 + koff]); \
-            acc[mi][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb0, acc[mi][0], 0, 0, 0);             \
-            acc[mi][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb1, acc[mi][1], 0, 0, 0);             \
-        }                                                                                                   \
-    }                                                                                                       \
-    if (MODE == MODE_SERIAL) {                                                                              \
-        /* end of a chunk: fold its sum into the running total (left-to-right chunk order) */               \
-        if (((KT) + 1) % tiles_per_chunk == 0 || (KT) + 1 == nk) {                                          \
-            _Pragma("unroll") for (int i = 0; i < MI; i++)                                                  \
-            _Pragma("unroll") for (int j = 0; j < 2; j++)                                                   \
-            _Pragma("unroll") for (int e = 0; e < 16; e++) {                                                \
-                total[i][j][e] += acc[i][j][e];                                                             \
-                acc[i][j][e] = 0.f;                                                                         \
-            }                                                                                               \
-        }                                                                                                   \
+        b_src[j] = reinterpret_cast<const unsigned char*>(wsrc + (size_t)min(gn, N - 1) * K) + ((lpos ^ swz(r)) << 4);
     }
 
-    if (kt0 < kt1) { HS_FETCH_A(kt0) HS_FETCH_B(rb0, kt0) }
-    if (kt0 + 1 < kt1) { HS_FETCH_B(rb1, kt0 + 1) }
-    for (int kt = kt0; kt < kt1; kt += 2) {
-        HS_STAGE(rb0)
-        __syncthreads();
-        if (kt + 1 < kt1) { HS_FETCH_A(kt + 1) }
-        if (kt + 2 < kt1) { HS_FETCH_B(rb0, kt + 2) }
-        HS_COMPUTE(kt)
-        __syncthreads();
-        if (kt + 1 < kt1) {
-            HS_STAGE(rb1)
-            __syncthreads();
-            if (kt + 2 < kt1) { HS_FETCH_A(kt + 2) }
-            if (kt + 3 < kt1) { HS_FETCH_B(rb1, kt + 3) }
-            HS_COMPUTE(kt + 1)
-            __syncthreads();
+    // Fragment geometry: lane l reads tile row (row0 + l%32), k-chunk 2*ks + l/32, at its swizzled position.
+    const int l32 = lane & 31, g = lane >> 5, fl = swz(l32);
+    const int a_frag = (wm * (BM / 2) + l32) * ROW_BYTES;
+    const int b_frag0 = ((EPI == HS_EPI_SWIGLU_BF16) ? (wn * 32 + l32) : (wn * 64 + l32)) * ROW_BYTES;
+    const int b_frag1 = ((EPI == HS_EPI_SWIGLU_BF16) ? (64 + wn * 32 + l32) : (wn * 64 + 32 + l32)) * ROW_BYTES;
+
+    for (int m_tile = local % m_tiles; m_tile * BM < M; m_tile += m_tiles) {
+        const int m0 = m_tile * BM;
+        const unsigned char* a_src[NLA];
+#pragma unroll
+        for (int j = 0; j < NLA; j++) {
+            const int r = (4 * j + wave) * 8 + lrow;
+            a_src[j] = reinterpret_cast<const unsigned char*>(A + (size_t)min(m0 + r, M - 1) * K) +
+                       ((lpos ^ swz(r)) << 4);
         }
+#define HS_ISSUE_A(KT, SLOT)                                                                                     \
+    {                                                                                                            \
+        const unsigned dst_ = smem_off + (SLOT) * A_BYTES + wave * 1024;                                         \
+        const size_t koff_ = (size_t)(KT) * ROW_BYTES;                                                           \
+        _Pragma("unroll") for (int j = 0; j < NLA; j++) load_to_lds_16(a_src[j] + koff_, dst_ + j * 4096);       \
     }
-#undef HS_FETCH_A
-#undef HS_FETCH_B
-#undef HS_STAGE
-#undef HS_COMPUTE
+#define HS_ISSUE_W(KT, SLOT)                                                                                     \
+    {                                                                                                            \
+        const unsigned dst_ = smem_off + W_RING + (SLOT) * W_BYTES + wave * 1024;                                \
+        const size_t koff_ = (size_t)(KT) * ROW_BYTES;                                                           \
+        _Pragma("unroll") for (int j = 0; j < NLB; j++) load_to_lds_16(b_src[j] + koff_, dst_ + j * 4096);       \
+    }
 
-    // Epilogue.  Accumulator element e of a 32x32 tile: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
-    const int lr = 4 * (lane >> 5), lc = lane & 31;
-    if (EPI == HS_EPI_SWIGLU_BF16) {
-        bf16_t* C = reinterpret_cast<bf16_t*>(Cout);
-        const int col = n0 + wn * 32 + lc;
-        if (col < N) {
+        f32x16 acc[MI][2], total[MI][2];
+#pragma unroll
+        for (int i = 0; i < MI; i++)
+#pragma unroll
+            for (int j = 0; j < 2; j++)
+#pragma unroll
+                for (int e = 0; e < 16; e++) {
+                    acc[i][j][e] = 0.f;
+                    if (MODE == MODE_SERIAL) total[i][j][e] = 0.f;
+                }
+
+        // Prologue: activation tile kt0 and weight tiles kt0 .. kt0+SW-2 in flight.  Issue order matters for the
+        // wait counts below: in every iteration the activation tile goes first, then the weight tile.
+        HS_ISSUE_A(kt0, 0)
+#pragma unroll
+        for (int s = 0; s < SW - 1; s++)
+            if (kt0 + s < kt1) HS_ISSUE_W(kt0 + s, s)
+
+        int slot_a = 0, slot_w = 0;
+        for (int kt = kt0; kt < kt1; kt++) {
+            // Loads complete in issue order, and the last loads issued before this point are activation tile kt
+            // followed by weight tile kt+SW-2 (if there is one).  So tile kt of both operands has landed once at
+            // most that one weight tile is outstanding.  (The in-order rule also means that a third weight stage
+            // is the deepest that pays: waiting for the young activation tile drains every older weight tile.)
+            if (SW > 2 && kt + SW - 2 < kt1) {
+                HS_WAIT_VMCNT(NLB);
+            } else {
+                HS_WAIT_VMCNT(0);
+            }
+            // Bare barrier: a fenced one would wait for every outstanding load, the tiles in flight included.
+            // Everyone's part of tile kt is in LDS (each wavefront waited for its own loads above), and everyone
+            // is done reading tile kt-1, whose slots are refilled next.
+            __builtin_amdgcn_s_barrier();
+            if (kt + 1 < kt1) HS_ISSUE_A(kt + 1, slot_a ^ 1)
+            if (kt + SW - 1 < kt1) HS_ISSUE_W(kt + SW - 1, (slot_w == 0) ? SW - 1 : slot_w - 1)
+            const unsigned char* sta = smem + slot_a * A_BYTES;
+            const unsigned char* stw = smem + W_RING + slot_w * W_BYTES;
+            // All fragment reads of the k-tile are issued up front; the matrix cores start as the first ones arrive
+            // and the rest of the LDS latency hides behind them.
+            bf16x8 fa[BK / 16][MI], fb[BK / 16][2];
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ks++) {
+                const int pos = ((2 * ks + g) ^ fl) << 4;
+                fb[ks][0] = *reinterpret_cast<const bf16x8*>(stw + b_frag0 + pos);
+                fb[ks][1] = *reinterpret_cast<const bf16x8*>(stw + b_frag1 + pos);
+#pragma unroll
+                for (int mi = 0; mi < MI; mi++)
+                    fa[ks][mi] = *reinterpret_cast<const bf16x8*>(sta + a_frag + mi * 32 * ROW_BYTES + pos);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the matrix-core block
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ks++)
+#pragma unroll
+                for (int mi = 0; mi < MI; mi++) {
+                    acc[mi][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][mi], fb[ks][0], acc[mi][0], 0, 0, 0);
+                    acc[mi][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][mi], fb[ks][1], acc[mi][1], 0, 0, 0);
+                }
+            if (MODE == MODE_SERIAL) {
+                // end of a chunk: fold its sum into the running total (left-to-right chunk order)
+                if ((kt + 1) % tiles_per_chunk == 0 || kt + 1 == nk) {
+#pragma unroll
+                    for (int i = 0; i < MI; i++)
+#pragma unroll
+                        for (int j = 0; j < 2; j++)
+#pragma unroll
+                            for (int e = 0; e < 16; e++) {
+                                total[i][j][e] += acc[i][j][e];
+                                acc[i][j][e] = 0.f;
+                            }
+                }
+            }
+            slot_a ^= 1;
+            slot_w = (slot_w + 1 == SW) ? 0 : slot_w + 1;
+        }
+#undef HS_ISSUE_A
+#undef HS_ISSUE_W
+
+        // Epilogue.  Accumulator element e of a 32x32 tile: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
+        const int lr = 4 * (lane >> 5), lc = lane & 31;
+        if (EPI == HS_EPI_SWIGLU_BF16) {
+            bf16_t* C = reinterpret_cast<bf16_t*>(Cout);
+            const int col = n0 + wn * 32 + lc;
+            if (col < N) {
+#pragma unroll
+                for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+                    for (int e = 0; e < 16; e++) {
+                        int row = m0 + wm * (BM / 2) + mi * 32 + 8 * (e >> 2) + lr + (e & 3);
+                        if (row < M) {
+                            float gt = acc[mi][0][e], u = acc[mi][1][e];
+                            float s = gt / (1.f + __expf(-gt));
+                            C[(size_t)row * N + col] = f32_to_bf16(s * u);
+                        }
+                    }
+            }
+        } else {
+            float* C =
+                (MODE == MODE_SPLIT) ? part + (size_t)blockIdx.y * m_max * N : reinterpret_cast<float*>(Cout);
 #pragma unroll
             for (int mi = 0; mi < MI; mi++)
 #pragma unroll
-                for (int e = 0; e < 16; e++) {
-                    int row = m0 + wm * (BM / 2) + mi * 32 + 8 * (e >> 2) + lr + (e & 3);
-                    if (row < M) {
-                        float g = acc[mi][0][e], u = acc[mi][1][e];
-                        float s = g / (1.f + __expf(-g));
-                        C[(size_t)row * N + col] = f32_to_bf16(s * u);
+                for (int ni = 0; ni < 2; ni++) {
+                    const int col = n0 + wn * 64 + ni * 32 + lc;
+                    if (col >= N) continue;
+#pragma unroll
+                    for (int e = 0; e < 16; e++) {
+                        int row = m0 + wm * (BM / 2) + mi * 32 + 8 * (e >> 2) + lr + (e & 3);
+                        if (row < M) {
+                            float v = (MODE == MODE_SERIAL) ? total[mi][ni][e] : acc[mi][ni][e];
+                            float* p = &C[(size_t)row * N + col];
+                            if (MODE != MODE_SPLIT && EPI == HS_EPI_ADD_F32) *p += v;
+                            else *p = v;
+                        }
                     }
                 }
         }
-    } else {
-        float* C = (MODE == MODE_SPLIT) ? part + (size_t)blockIdx.y * m_max * N : reinterpret_cast<float*>(Cout);
-#pragma unroll
-        for (int mi = 0; mi < MI; mi++)
-#pragma unroll
-            for (int ni = 0; ni < 2; ni++) {
-                const int col = n0 + wn * 64 + ni * 32 + lc;
-                if (col >= N) continue;
-#pragma unroll
-                for (int e = 0; e < 16; e++) {
-                    int row = m0 + wm * (BM / 2) + mi * 32 + 8 * (e >> 2) + lr + (e & 3);
-                    if (row < M) {
-                        float v = (MODE == MODE_SERIAL) ? total[mi][ni][e] : acc[mi][ni][e];
-                        float* p = &C[(size_t)row * N + col];
-                        if (MODE != MODE_SPLIT && EPI == HS_EPI_ADD_F32) *p += v;
-                        else *p = v;
-                    }
-                }
-            }
+        __syncthreads();  // the ring is reused by the next row tile
     }
 }
+
+namespace {
 
 // Second pass of the split execution: add the chunk partials left to right, then store or add to the residual.
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_split_reduce(const float* __restrict__ part, float* __restrict__ C,
                                                           const int32_t* __restrict__ m_dev, int m_max, int N,
                                                           int chunks) {
-    const int row = blockIdx.y;
-    if (row >= *m_dev) return;
     const int c4 = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (c4 >= N) return;
-    const size_t off = (size_t)row * N + c4, stride = (size_t)m_max * N;
-    float4 t = *reinterpret_cast<const float4*>(part + off);
-    for (int s = 1; s < chunks; s++) {
-        float4 p = *reinterpret_cast<const float4*>(part + s * stride + off);
-        t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
-    }
-    float4* dst = reinterpret_cast<float4*>(C + off);
-    if (EPI == HS_EPI_ADD_F32) {
-        float4 o = *dst;
-        o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
-        *dst = o;
-    } else {
-        *dst = t;
+    const int M = *m_dev;
+    for (int row = blockIdx.y; row < M; row += gridDim.y) {
+        const size_t off = (size_t)row * N + c4, stride = (size_t)m_max * N;
+        float4 t = *reinterpret_cast<const float4*>(part + off);
+        for (int s = 1; s < chunks; s++) {
+            float4 p = *reinterpret_cast<const float4*>(part + s * stride + off);
+            t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+        }
+        float4* dst = reinterpret_cast<float4*>(C + off);
+        if (EPI == HS_EPI_ADD_F32) {
+            float4 o = *dst;
+            o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
+            *dst = o;
+        } else {
+            *dst = t;
+        }
     }
 }
 
@@ -260,16 +320,27 @@ __global__ void gemm_bf16_plain(const bf16_t* __restrict__ A, const bf16_t* __re
     }
 }
 
-template <int EPI, int MODE, int MI>
+template <int EPI, int MODE, int MI, int SW>
 void launch_tile(const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, float* part, const int32_t* m_dev,
-                 int m_max, int n, int k, int chunks, int tpc, hipStream_t st) {
+                 int m_max, int n, int k, int chunks, int tpc, int rows_hint, hipStream_t st) {
     constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? 64 : 128;
-    const int m_tiles = (m_max + 64 * MI - 1) / (64 * MI);
+    constexpr int BM = 64 * MI;
+    constexpr size_t lds = (size_t)(2 * BM + SW * BN) * ROW_BYTES;
+    static bool configured = false;  // more than 64 KB of dynamic LDS has to be asked for once per kernel
+    if (!configured) {
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&hs_gemm_bf16_mfma<EPI, MODE, MI, SW>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        configured = true;
+    }
+    const int m_tiles_all = (m_max + BM - 1) / BM;
+    int m_tiles = (rows_hint + BM - 1) / BM;
+    if (m_tiles < 1) m_tiles = 1;
+    if (m_tiles > m_tiles_all) m_tiles = m_tiles_all;
     const int n_tiles = (n + NCOLS - 1) / NCOLS;
     const int blocks = ((n_tiles + 7) / 8) * m_tiles * 8;
     dim3 grid(blocks, MODE == MODE_SPLIT ? chunks : 1);
-    hipLaunchKernelGGL((gemm_bf16_mfma<EPI, MODE, MI>), grid, dim3(256), 0, st, a, w, w2, c, part, m_dev, m_max, n, k,
-                       m_tiles, n_tiles, tpc);
+    hipLaunchKernelGGL((hs_gemm_bf16_mfma<EPI, MODE, MI, SW>), grid, dim3(256), lds, st, a, w, w2, c, part, m_dev, m_max,
+                       n, k, m_tiles, n_tiles, tpc);
 }
 
 template <int EPI>
@@ -286,21 +357,19 @@ void launch(const hs_ctx* ctx, const bf16_t* a, const bf16_t* w, const bf16_t* w
     chunks = (nk + tpc - 1) / tpc;  // no empty chunk
     float* part = reinterpret_cast<float*>(ctx->ws + ctx->lay.gemm_part);
     // Launch shape from the row hint: narrow outputs run split over K while the row tiles alone would leave compute
-    // units idle.  The 256-row tile measured slower than two 128-row tiles at every row count tried (one wavefront
-    // per SIMD cannot hide the staging), so it is compiled but not selected.
-    const bool tall = false;
+    // units idle.
     const bool split = chunks > 1 && rows_hint <= 512;
     if (chunks == 1) {
-        if (tall) launch_tile<EPI, MODE_PLAIN, 4>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, st);
-        else launch_tile<EPI, MODE_PLAIN, 2>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, st);
+        launch_tile<EPI, MODE_PLAIN, 2, 3>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st);
     } else if (!split) {
-        launch_tile<EPI, MODE_SERIAL, 2>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, st);
+        launch_tile<EPI, MODE_SERIAL, 2, 3>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st);
     } else {
-        if (tall) launch_tile<EPI, MODE_SPLIT, 4>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, st);
-        else launch_tile<EPI, MODE_SPLIT, 2>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, st);
-        if (EPI != HS_EPI_SWIGLU_BF16)
-            hipLaunchKernelGGL((gemm_split_reduce<EPI>), dim3((n / 4 + 255) / 256, m_max), dim3(256), 0, st, part,
+        launch_tile<EPI, MODE_SPLIT, 2, 3>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st);
+        if (EPI != HS_EPI_SWIGLU_BF16) {
+            int rows = rows_hint < 1 ? 1 : (rows_hint > m_max ? m_max : rows_hint);
+            hipLaunchKernelGGL((gemm_split_reduce<EPI>), dim3((n / 4 + 255) / 256, rows), dim3(256), 0, st, part,
                                reinterpret_cast<float*>(c), m_dev, m_max, n, chunks);
+        }
     }
 }
 
