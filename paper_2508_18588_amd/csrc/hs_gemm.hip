@@ -65,8 +65,8 @@ template <int EPI, int MODE, int MI, int SW>
 __global__ __launch_bounds__(256) void hs_gemm_bf16_mfma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                        const bf16_t* __restrict__ W2, void* __restrict__ Cout,
                                                        float* __restrict__ part, const int32_t* __restrict__ m_dev,
-                                                       int m_max, int N, int K, int m_tiles, int n_tiles,
-                                                       int tiles_per_chunk) {
+                                                       int m_max, int N, int K, int m_tiles, int m_main,
+                                                       int n_tiles, int tiles_per_chunk) {
     constexpr int BM = 64 * MI;
     constexpr int NLA = BM / 32;        // 1 KB load instructions per wavefront and k-tile for the A tile
     constexpr int NLB = BN / 32;        // ... and for the W tile
@@ -79,10 +79,23 @@ __global__ __launch_bounds__(256) void hs_gemm_bf16_mfma(const bf16_t* __restric
     const unsigned smem_off = (unsigned)(size_t)(lds_ptr_t)smem;
 
     const int M = *m_dev;
-    // XCD-aware tile assignment: id -> (xcd, local); an XCD walks its N-tiles, M fastest.
+    // XCD-aware tile assignment.  The first n8 * m_main workgroups (n8 = column tiles rounded up to 8) cover the
+    // row tiles the host expects to be live: id -> (xcd, local), an XCD walks its column tiles with the row tile
+    // running fastest, so the row tiles that share a weight tile run together on one L2.  The remaining
+    // workgroups cover spare row tiles, row tile slowest: they are dispatched last, where an unused one only
+    // costs its early exit, and keep the column-tile -> XCD mapping of the first group.
     const int id = blockIdx.x;
-    const int xcd = id & 7, local = id >> 3;
-    const int n_tile = (local / m_tiles) * 8 + xcd;
+    const int n8 = (n_tiles + 7) & ~7;
+    int n_tile, m_first;
+    if (id < n8 * m_main) {
+        const int xcd = id & 7, local = id >> 3;
+        n_tile = (local / m_main) * 8 + xcd;
+        m_first = local % m_main;
+    } else {
+        const int id2 = id - n8 * m_main;
+        n_tile = id2 % n8;
+        m_first = m_main + id2 / n8;
+    }
     if (n_tile >= n_tiles) return;
     // SwiGLU: the tile's 128 B-rows are 64 gate rows followed by the 64 up rows of the same output columns.
     constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? 64 : 128;
@@ -124,7 +137,7 @@ __global__ __launch_bounds__(256) void hs_gemm_bf16_mfma(const bf16_t* __restric
     const int b_frag0 = ((EPI == HS_EPI_SWIGLU_BF16) ? (wn * 32 + l32) : (wn * 64 + l32)) * ROW_BYTES;
     const int b_frag1 = ((EPI == HS_EPI_SWIGLU_BF16) ? (64 + wn * 32 + l32) : (wn * 64 + 32 + l32)) * ROW_BYTES;
 
-    for (int m_tile = local % m_tiles; m_tile * BM < M; m_tile += m_tiles) {
+    for (int m_tile = m_first; m_tile * BM < M; m_tile += m_tiles) {
         const int m0 = m_tile * BM;
         const unsigned char* a_src[NLA];
 #pragma unroll
@@ -332,15 +345,19 @@ void launch_tile(const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, fl
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         configured = true;
     }
+    // Row tiles in the grid: those the hint calls for, plus as many spare ones, because the row count swings from
+    // step to step and a missing row tile costs a whole second pass of some workgroups.
     const int m_tiles_all = (m_max + BM - 1) / BM;
-    int m_tiles = (rows_hint + BM - 1) / BM;
-    if (m_tiles < 1) m_tiles = 1;
+    int m_main = (rows_hint + BM - 1) / BM;
+    if (m_main < 1) m_main = 1;
+    if (m_main > m_tiles_all) m_main = m_tiles_all;
+    int m_tiles = 2 * m_main;
     if (m_tiles > m_tiles_all) m_tiles = m_tiles_all;
     const int n_tiles = (n + NCOLS - 1) / NCOLS;
     const int blocks = ((n_tiles + 7) / 8) * m_tiles * 8;
     dim3 grid(blocks, MODE == MODE_SPLIT ? chunks : 1);
     hipLaunchKernelGGL((hs_gemm_bf16_mfma<EPI, MODE, MI, SW>), grid, dim3(256), lds, st, a, w, w2, c, part, m_dev, m_max,
-                       n, k, m_tiles, n_tiles, tpc);
+                       n, k, m_tiles, m_main, n_tiles, tpc);
 }
 
 template <int EPI>
@@ -366,7 +383,7 @@ void launch(const hs_ctx* ctx, const bf16_t* a, const bf16_t* w, const bf16_t* w
     } else {
         launch_tile<EPI, MODE_SPLIT, 2, 3>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st);
         if (EPI != HS_EPI_SWIGLU_BF16) {
-            int rows = rows_hint < 1 ? 1 : (rows_hint > m_max ? m_max : rows_hint);
+            int rows = rows_hint < 1 ? 1 : (2 * rows_hint > m_max ? m_max : 2 * rows_hint);
             hipLaunchKernelGGL((gemm_split_reduce<EPI>), dim3((n / 4 + 255) / 256, rows), dim3(256), 0, st, part,
                                reinterpret_cast<float*>(c), m_dev, m_max, n, chunks);
         }
