@@ -211,9 +211,12 @@ hs_status hs_poll_error(hs_ctx* ctx, hs_stream stream, uint32_t* error_bits);
  * 2 last layer's attention output bf16 (same shape), 3 logits f32 [max_rows][vocab]. */
 hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size_t* bytes);
 
-/* Kernel timing.  After hs_set_profile(ctx, 1) every kernel launch of hs_verify is bracketed by HIP events on the
- * call's stream; hs_get_profile waits for the last profiled call and returns, summed over all hs_verify calls
- * since the previous hs_get_profile / hs_set_profile, total milliseconds and launch counts per class:
+/* Kernel timing with HIP events on the call's stream.  hs_set_profile(ctx, level): 0 off; 1 brackets the attention
+ * kernel of every layer and the whole hs_verify call (cheap enough for a timed run); 2 brackets every kernel
+ * launch of hs_verify (each pair of events costs a few microseconds of stream time: use it on steps that are not
+ * themselves being timed).  hs_get_profile waits for the last profiled call and returns, summed over all hs_verify
+ * calls since the previous hs_get_profile / hs_set_profile, total milliseconds and launch counts per class (classes
+ * that the level does not bracket report zero):
  * 0 attention kernel, 1 projection GEMMs (QKV, O, gate/up, down), 2 LM-head GEMM, 3 everything else (norms,
  * rotary/KV write, split-KV merge, argmax), 4 whole calls.  Events are host objects; no device memory is used. */
 hs_status hs_set_profile(hs_ctx* ctx, int32_t enabled);

@@ -197,8 +197,8 @@ def hs_debug_buffer(ctx, which: int):
     return p.value, n.value
 
 
-def hs_set_profile(ctx, enabled: bool):
-    _check(ctx, lib().hs_set_profile(ctx, int(enabled)))
+def hs_set_profile(ctx, level: int):
+    _check(ctx, lib().hs_set_profile(ctx, int(level)))
 
 
 def hs_get_profile(ctx):

@@ -50,8 +50,13 @@ void layout_workspace(hs_ctx* ctx) {
 struct Prof {
     hs_ctx* ctx;
     hipStream_t st;
+    bool open = false;
     void begin(int cls) {
-        if (!ctx->profile) return;
+        open = false;
+        // level 1 brackets the attention kernel (and the whole call) only: every pair of events costs a few
+        // microseconds of stream time, which a timed run should not pay around all ~15 launches per layer
+        if (!ctx->profile || (ctx->profile == 1 && cls != 0 && cls != 4)) return;
+        open = true;
         if (ctx->ev_used + 2 > (int)ctx->ev.size()) {
             hipEvent_t a, b;
             if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { ctx->profile = 0; return; }
@@ -63,7 +68,8 @@ struct Prof {
         (void)hipEventRecord(ctx->ev[ctx->ev_used], st);
     }
     void end() {
-        if (!ctx->profile) return;
+        if (!ctx->profile || !open) return;
+        open = false;
         (void)hipEventRecord(ctx->ev[ctx->ev_used + 1], st);
         ctx->ev_used += 2;
     }
@@ -327,7 +333,7 @@ hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size
 
 hs_status hs_set_profile(hs_ctx* ctx, int32_t enabled) {
     if (!ctx) return HS_ERR_INVALID_ARG;
-    ctx->profile = enabled ? 1 : 0;
+    ctx->profile = enabled <= 0 ? 0 : (enabled == 1 ? 1 : 2);
     ctx->ev_used = 0;
     return HS_OK;
 }

@@ -223,8 +223,9 @@ class Engine:
     def set_flags(self, flags: int):
         hs_set_flags(self.ctx, flags)
 
-    def set_profile(self, on: bool):
-        hs_set_profile(self.ctx, on)
+    def set_profile(self, level: int):
+        """0 off, 1 events around the attention kernel and the whole call, 2 around every launch of hs_verify."""
+        hs_set_profile(self.ctx, int(level))
 
     def get_profile(self):
         return hs_get_profile(self.ctx)
