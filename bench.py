@@ -57,6 +57,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is then NOT the benchmark)")
     ap.add_argument("--window", type=int, default=0,
                     help="debug: tokens of previous-epoch text generated at set-up (default: the workload's 256)")
+    ap.add_argument("--print-rows", action="store_true", help="diagnostic: log the row count of every timed step")
     ap.add_argument("--reuse-all", action="store_true",
                     help="debug: history = the rollout itself (every draft accepted, rows per step at their maximum)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -163,10 +164,15 @@ def main():
         eng.set_profile(1)      # events around the attention kernel only: the timed steps pay for nothing else
     torch.cuda.synchronize()
     t2 = time.perf_counter()
+    step_rows = []
     for _ in range(args.steps):
         eng.step(pol)
+        if args.print_rows:     # diagnostic: synchronises every step, the timing of such a run means nothing
+            step_rows.append(int(eng.st["row_off"][B].item()))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t2
+    if step_rows:
+        log(f"rows per timed step: {step_rows}")
     prof = None if args.no_profile else eng.get_profile()
     eng.set_profile(0)
     c1 = eng.counters.cpu().numpy().copy()

@@ -115,6 +115,16 @@ hs_status hs_create(const hs_model_desc* desc, const hs_weights* w, const hs_lim
     const int nodes = 1 + l.c_max * l.k_max;
     if (nodes > HS_MAX_NODES || (d.n_q_heads / d.n_kv_heads) * nodes > 256) return HS_ERR_UNSUPPORTED;
     if ((long long)l.max_rows < (long long)l.max_batch * nodes) return HS_ERR_CAPACITY;
+    {
+        // the GEMM kernels address an operand with 32-bit byte offsets from its base
+        const long long qh = (long long)d.n_q_heads * d.head_dim;
+        const long long nqkv = (long long)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+        const long long widest = std::max<long long>({d.d_model, d.d_ffn, qh});
+        const long long biggest = std::max<long long>({(long long)d.vocab * d.d_model, nqkv * d.d_model,
+                                                       (long long)d.d_ffn * d.d_model, d.d_model * qh,
+                                                       (long long)l.max_rows * widest});
+        if (biggest * 2 >= (1ll << 32)) return HS_ERR_UNSUPPORTED;
+    }
     if (!w->embed || !w->lm_head || !w->norm_f || !w->rope_cs || !w->wqkv || !w->wo || !w->wgate || !w->wup ||
         !w->wdown || !w->norm1 || !w->norm2)
         return HS_ERR_INVALID_ARG;

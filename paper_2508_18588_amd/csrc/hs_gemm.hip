@@ -32,7 +32,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int BN = 128, BK = 64;
+constexpr int BK = 64;
 constexpr int ROW_BYTES = BK * 2;  // one tile row in LDS: 8 chunks of 16 bytes
 
 enum { MODE_PLAIN = 0, MODE_SERIAL = 1, MODE_SPLIT = 2 };
@@ -52,53 +52,48 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 // later LDS read as possibly returning out of order and waits for all of them at once, which serialises fragment
 // reads and matrix-core work; the kernel places the vmcnt waits for these loads itself.  Any wait the compiler
 // inserts for its own loads can only be stricter than needed, because loads complete in issue order.
-__device__ __forceinline__ void load_to_lds_16(const unsigned char* src, unsigned lds_off) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_off), "v"(src) : "memory", "m0");
+// The source address is a wavefront-uniform base (scalar registers) plus a 32-bit unsigned byte offset per lane.
+__device__ __forceinline__ void load_to_lds_16(const unsigned char* base, unsigned off, unsigned lds_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_off), "v"(off), "s"(base)
+                 : "memory", "m0");
 }
 
 }  // namespace
 
-// MI = 32-row MFMA tiles per wavefront in M: the workgroup tile is BM = 64 * MI rows.  SW = stages of the weight
-// ring (the activation ring has two).
+// MI x NI = 32x32 MFMA tiles per wavefront: the workgroup tile is BM = 64 * MI rows by BN = 64 * NI weight rows.
+// SW = stages of the weight ring (the activation ring has two).
 // (External linkage: the host takes the kernel's address to raise its dynamic LDS limit.)
-template <int EPI, int MODE, int MI, int SW>
+template <int EPI, int MODE, int MI, int NI, int SW>
 __global__ __launch_bounds__(256) void hs_gemm_bf16_mfma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                        const bf16_t* __restrict__ W2, void* __restrict__ Cout,
                                                        float* __restrict__ part, const int32_t* __restrict__ m_dev,
-                                                       int m_max, int N, int K, int m_tiles, int m_main,
-                                                       int n_tiles, int tiles_per_chunk) {
-    constexpr int BM = 64 * MI;
+                                                       int m_max, int N, int K, int m_tiles, int n_tiles,
+                                                       int tiles_per_chunk) {
+    constexpr int BM = 64 * MI, BN = 64 * NI;
     constexpr int NLA = BM / 32;        // 1 KB load instructions per wavefront and k-tile for the A tile
     constexpr int NLB = BN / 32;        // ... and for the W tile
     constexpr int SA = 2;
     constexpr int A_BYTES = BM * ROW_BYTES, W_BYTES = BN * ROW_BYTES;
     constexpr int W_RING = SA * A_BYTES;  // byte offset of the weight ring
     static_assert(SW == 2 || SW == 3, "the wait counts below cover two or three weight stages");
+    static_assert(MODE != MODE_SERIAL || MI * NI <= 4, "the serial execution keeps a second set of accumulators");
+    static_assert(EPI != HS_EPI_SWIGLU_BF16 || NI % 2 == 0, "gate and up tiles come in pairs");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     // LDS byte offset of the ring (what M0 carries): the 32-bit value of the pointer in the LDS address space
     const unsigned smem_off = (unsigned)(size_t)(lds_ptr_t)smem;
 
     const int M = *m_dev;
-    // XCD-aware tile assignment.  The first n8 * m_main workgroups (n8 = column tiles rounded up to 8) cover the
-    // row tiles the host expects to be live: id -> (xcd, local), an XCD walks its column tiles with the row tile
-    // running fastest, so the row tiles that share a weight tile run together on one L2.  The remaining
-    // workgroups cover spare row tiles, row tile slowest: they are dispatched last, where an unused one only
-    // costs its early exit, and keep the column-tile -> XCD mapping of the first group.
+    // XCD-aware tile assignment: id -> (xcd, local); an XCD walks its column tiles with the row tile running
+    // fastest, so the row tiles that share a weight tile run together on one L2.
     const int id = blockIdx.x;
-    const int n8 = (n_tiles + 7) & ~7;
-    int n_tile, m_first;
-    if (id < n8 * m_main) {
-        const int xcd = id & 7, local = id >> 3;
-        n_tile = (local / m_main) * 8 + xcd;
-        m_first = local % m_main;
-    } else {
-        const int id2 = id - n8 * m_main;
-        n_tile = id2 % n8;
-        m_first = m_main + id2 / n8;
-    }
+    const int xcd = id & 7, local = id >> 3;
+    const int n_tile = (local / m_tiles) * 8 + xcd;
+    const int m_first = local % m_tiles;
     if (n_tile >= n_tiles) return;
-    // SwiGLU: the tile's 128 B-rows are 64 gate rows followed by the 64 up rows of the same output columns.
-    constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? 64 : 128;
+    // SwiGLU: the tile's BN weight rows are BN/2 gate rows followed by the BN/2 up rows of the same output columns.
+    constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? BN / 2 : BN;
     const int n0 = n_tile * NCOLS;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -116,54 +111,61 @@ __global__ __launch_bounds__(256) void hs_gemm_bf16_mfma(const bf16_t* __restric
     // lane i lands on row i/8, chunk position i%8 and therefore fetches chunk (i%8) ^ swz(row).  Rows beyond M
     // (or N) are clamped to the last valid row: their products are computed and never stored.
     const int lrow = lane >> 3, lpos = lane & 7;
-    const unsigned char* b_src[NLB];
+    // (32-bit byte offsets: the largest matrix of the supported shapes, vocab x d_model bf16, stays below 4 GiB;
+    // the host checks it.)
+    unsigned b_off[NLB];
+    const unsigned char* b_base[NLB];
 #pragma unroll
     for (int j = 0; j < NLB; j++) {
         const int r = (4 * j + wave) * 8 + lrow;
-        int gn;
-        const bf16_t* wsrc = W;
+        int gn = n0 + r;
+        b_base[j] = reinterpret_cast<const unsigned char*>(W);
         if (EPI == HS_EPI_SWIGLU_BF16) {
-            gn = n0 + (r & 63);
-            if (r >= 64) wsrc = W2;
-        } else {
-            gn = n0 + r;
+            gn = n0 + (r % (BN / 2));
+            if ((4 * j + wave) * 8 >= BN / 2) b_base[j] = reinterpret_cast<const unsigned char*>(W2);  // uniform
         }
-        b_src[j] = reinterpret_cast<const unsigned char*>(wsrc + (size_t)min(gn, N - 1) * K) + ((lpos ^ swz(r)) << 4);
+        b_off[j] = (unsigned)min(gn, N - 1) * (unsigned)(K * 2) + ((lpos ^ swz(r)) << 4);
     }
 
     // Fragment geometry: lane l reads tile row (row0 + l%32), k-chunk 2*ks + l/32, at its swizzled position.
     const int l32 = lane & 31, g = lane >> 5, fl = swz(l32);
     const int a_frag = (wm * (BM / 2) + l32) * ROW_BYTES;
-    const int b_frag0 = ((EPI == HS_EPI_SWIGLU_BF16) ? (wn * 32 + l32) : (wn * 64 + l32)) * ROW_BYTES;
-    const int b_frag1 = ((EPI == HS_EPI_SWIGLU_BF16) ? (64 + wn * 32 + l32) : (wn * 64 + 32 + l32)) * ROW_BYTES;
+    // weight tile ni of this wavefront: SwiGLU keeps NI/2 gate tiles then the NI/2 up tiles of the same columns
+    int b_frag[NI];
+#pragma unroll
+    for (int ni = 0; ni < NI; ni++) {
+        const int trow = (EPI == HS_EPI_SWIGLU_BF16)
+                             ? ((ni < NI / 2 ? 0 : BN / 2) + wn * (16 * NI) + 32 * (ni % (NI / 2 > 0 ? NI / 2 : 1)))
+                             : (wn * (32 * NI) + 32 * ni);
+        b_frag[ni] = (trow + l32) * ROW_BYTES;
+    }
 
     for (int m_tile = m_first; m_tile * BM < M; m_tile += m_tiles) {
         const int m0 = m_tile * BM;
-        const unsigned char* a_src[NLA];
+        unsigned a_off[NLA];
 #pragma unroll
         for (int j = 0; j < NLA; j++) {
             const int r = (4 * j + wave) * 8 + lrow;
-            a_src[j] = reinterpret_cast<const unsigned char*>(A + (size_t)min(m0 + r, M - 1) * K) +
-                       ((lpos ^ swz(r)) << 4);
+            a_off[j] = (unsigned)min(m0 + r, M - 1) * (unsigned)(K * 2) + ((lpos ^ swz(r)) << 4);
         }
 #define HS_ISSUE_A(KT, SLOT)                                                                                     \
     {                                                                                                            \
         const unsigned dst_ = smem_off + (SLOT) * A_BYTES + wave * 1024;                                         \
-        const size_t koff_ = (size_t)(KT) * ROW_BYTES;                                                           \
-        _Pragma("unroll") for (int j = 0; j < NLA; j++) load_to_lds_16(a_src[j] + koff_, dst_ + j * 4096);       \
+        const unsigned char* base_ = reinterpret_cast<const unsigned char*>(A) + (size_t)(KT) * ROW_BYTES;       \
+        _Pragma("unroll") for (int j = 0; j < NLA; j++) load_to_lds_16(base_, a_off[j], dst_ + j * 4096);        \
     }
 #define HS_ISSUE_W(KT, SLOT)                                                                                     \
     {                                                                                                            \
         const unsigned dst_ = smem_off + W_RING + (SLOT) * W_BYTES + wave * 1024;                                \
         const size_t koff_ = (size_t)(KT) * ROW_BYTES;                                                           \
-        _Pragma("unroll") for (int j = 0; j < NLB; j++) load_to_lds_16(b_src[j] + koff_, dst_ + j * 4096);       \
+        _Pragma("unroll") for (int j = 0; j < NLB; j++) load_to_lds_16(b_base[j] + koff_, b_off[j], dst_ + j * 4096); \
     }
 
-        f32x16 acc[MI][2], total[MI][2];
+        f32x16 acc[MI][NI], total[MODE == MODE_SERIAL ? MI : 1][MODE == MODE_SERIAL ? NI : 1];
 #pragma unroll
         for (int i = 0; i < MI; i++)
 #pragma unroll
-            for (int j = 0; j < 2; j++)
+            for (int j = 0; j < NI; j++)
 #pragma unroll
                 for (int e = 0; e < 16; e++) {
                     acc[i][j][e] = 0.f;
@@ -196,33 +198,39 @@ __global__ __launch_bounds__(256) void hs_gemm_bf16_mfma(const bf16_t* __restric
             if (kt + SW - 1 < kt1) HS_ISSUE_W(kt + SW - 1, (slot_w == 0) ? SW - 1 : slot_w - 1)
             const unsigned char* sta = smem + slot_a * A_BYTES;
             const unsigned char* stw = smem + W_RING + slot_w * W_BYTES;
-            // All fragment reads of the k-tile are issued up front; the matrix cores start as the first ones arrive
-            // and the rest of the LDS latency hides behind them.
-            bf16x8 fa[BK / 16][MI], fb[BK / 16][2];
+            // Fragment reads run two k-steps (of 16) ahead of the matrix cores: the first MFMAs start as soon as
+            // their operands arrive and the rest of the LDS latency hides behind them.
+            bf16x8 fa[BK / 16][MI], fb[BK / 16][NI];
+#define HS_FRAGS(KS)                                                                                             \
+    {                                                                                                            \
+        const int pos_ = ((2 * (KS) + g) ^ fl) << 4;                                                             \
+        _Pragma("unroll") for (int ni = 0; ni < NI; ni++)                                                        \
+            fb[KS][ni] = *reinterpret_cast<const bf16x8*>(stw + b_frag[ni] + pos_);                              \
+        _Pragma("unroll") for (int mi = 0; mi < MI; mi++)                                                        \
+            fa[KS][mi] = *reinterpret_cast<const bf16x8*>(sta + a_frag + mi * 32 * ROW_BYTES + pos_);            \
+    }
+            HS_FRAGS(0)
+            HS_FRAGS(1)
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ks++) {
-                const int pos = ((2 * ks + g) ^ fl) << 4;
-                fb[ks][0] = *reinterpret_cast<const bf16x8*>(stw + b_frag0 + pos);
-                fb[ks][1] = *reinterpret_cast<const bf16x8*>(stw + b_frag1 + pos);
+                if (ks + 2 < BK / 16) HS_FRAGS(ks + 2)
+                __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the matrix-core block
 #pragma unroll
                 for (int mi = 0; mi < MI; mi++)
-                    fa[ks][mi] = *reinterpret_cast<const bf16x8*>(sta + a_frag + mi * 32 * ROW_BYTES + pos);
+#pragma unroll
+                    for (int ni = 0; ni < NI; ni++)
+                        acc[mi][ni] =
+                            __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][mi], fb[ks][ni], acc[mi][ni], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the matrix-core block
-#pragma unroll
-            for (int ks = 0; ks < BK / 16; ks++)
-#pragma unroll
-                for (int mi = 0; mi < MI; mi++) {
-                    acc[mi][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][mi], fb[ks][0], acc[mi][0], 0, 0, 0);
-                    acc[mi][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][mi], fb[ks][1], acc[mi][1], 0, 0, 0);
-                }
+#undef HS_FRAGS
             if (MODE == MODE_SERIAL) {
                 // end of a chunk: fold its sum into the running total (left-to-right chunk order)
                 if ((kt + 1) % tiles_per_chunk == 0 || kt + 1 == nk) {
 #pragma unroll
                     for (int i = 0; i < MI; i++)
 #pragma unroll
-                        for (int j = 0; j < 2; j++)
+                        for (int j = 0; j < NI; j++)
 #pragma unroll
                             for (int e = 0; e < 16; e++) {
                                 total[i][j][e] += acc[i][j][e];
@@ -240,15 +248,17 @@ __global__ __launch_bounds__(256) void hs_gemm_bf16_mfma(const bf16_t* __restric
         const int lr = 4 * (lane >> 5), lc = lane & 31;
         if (EPI == HS_EPI_SWIGLU_BF16) {
             bf16_t* C = reinterpret_cast<bf16_t*>(Cout);
-            const int col = n0 + wn * 32 + lc;
-            if (col < N) {
+#pragma unroll
+            for (int t = 0; t < NI / 2; t++) {
+                const int col = n0 + wn * (16 * NI) + 32 * t + lc;
+                if (col >= N) continue;
 #pragma unroll
                 for (int mi = 0; mi < MI; mi++)
 #pragma unroll
                     for (int e = 0; e < 16; e++) {
                         int row = m0 + wm * (BM / 2) + mi * 32 + 8 * (e >> 2) + lr + (e & 3);
                         if (row < M) {
-                            float gt = acc[mi][0][e], u = acc[mi][1][e];
+                            float gt = acc[mi][t][e], u = acc[mi][t + NI / 2][e];
                             float s = gt / (1.f + __expf(-gt));
                             C[(size_t)row * N + col] = f32_to_bf16(s * u);
                         }
@@ -260,14 +270,15 @@ __global__ __launch_bounds__(256) void hs_gemm_bf16_mfma(const bf16_t* __restric
 #pragma unroll
             for (int mi = 0; mi < MI; mi++)
 #pragma unroll
-                for (int ni = 0; ni < 2; ni++) {
-                    const int col = n0 + wn * 64 + ni * 32 + lc;
+                for (int ni = 0; ni < NI; ni++) {
+                    const int col = n0 + wn * (32 * NI) + ni * 32 + lc;
                     if (col >= N) continue;
 #pragma unroll
                     for (int e = 0; e < 16; e++) {
                         int row = m0 + wm * (BM / 2) + mi * 32 + 8 * (e >> 2) + lr + (e & 3);
                         if (row < M) {
-                            float v = (MODE == MODE_SERIAL) ? total[mi][ni][e] : acc[mi][ni][e];
+                            float v = (MODE == MODE_SERIAL) ? total[MODE == MODE_SERIAL ? mi : 0][MODE == MODE_SERIAL ? ni : 0][e]
+                                                             : acc[mi][ni][e];
                             float* p = &C[(size_t)row * N + col];
                             if (MODE != MODE_SPLIT && EPI == HS_EPI_ADD_F32) *p += v;
                             else *p = v;
@@ -333,31 +344,32 @@ __global__ void gemm_bf16_plain(const bf16_t* __restrict__ A, const bf16_t* __re
     }
 }
 
-template <int EPI, int MODE, int MI, int SW>
+template <int EPI, int MODE, int MI, int NI, int SW>
 void launch_tile(const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, float* part, const int32_t* m_dev,
                  int m_max, int n, int k, int chunks, int tpc, int rows_hint, hipStream_t st) {
-    constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? 64 : 128;
-    constexpr int BM = 64 * MI;
+    constexpr int BM = 64 * MI, BN = 64 * NI;
+    constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? BN / 2 : BN;
     constexpr size_t lds = (size_t)(2 * BM + SW * BN) * ROW_BYTES;
     static bool configured = false;  // more than 64 KB of dynamic LDS has to be asked for once per kernel
     if (!configured) {
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&hs_gemm_bf16_mfma<EPI, MODE, MI, SW>),
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&hs_gemm_bf16_mfma<EPI, MODE, MI, NI, SW>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         configured = true;
     }
-    // Row tiles in the grid: those the hint calls for, plus as many spare ones, because the row count swings from
-    // step to step and a missing row tile costs a whole second pass of some workgroups.
+    // Row tiles in the grid: what the hint calls for, with an eighth of margin once there is more than one row
+    // per sequence (the row count swings from step to step).  Not more: a workgroup of this kernel holds 80-160 KB
+    // of LDS and is not free to dispatch even if it exits at once -- 256 unused ones cost 10 us.  Rows beyond the
+    // grid are reached by the grid-stride loop of the kernel.
     const int m_tiles_all = (m_max + BM - 1) / BM;
-    int m_main = (rows_hint + BM - 1) / BM;
+    int m_main = MI == 2 && rows_hint <= BM ? 1 : (rows_hint + rows_hint / 8 + BM - 1) / BM;
     if (m_main < 1) m_main = 1;
     if (m_main > m_tiles_all) m_main = m_tiles_all;
-    int m_tiles = 2 * m_main;
-    if (m_tiles > m_tiles_all) m_tiles = m_tiles_all;
+    const int m_tiles = m_main;
     const int n_tiles = (n + NCOLS - 1) / NCOLS;
     const int blocks = ((n_tiles + 7) / 8) * m_tiles * 8;
     dim3 grid(blocks, MODE == MODE_SPLIT ? chunks : 1);
-    hipLaunchKernelGGL((hs_gemm_bf16_mfma<EPI, MODE, MI, SW>), grid, dim3(256), lds, st, a, w, w2, c, part, m_dev, m_max,
-                       n, k, m_tiles, m_main, n_tiles, tpc);
+    hipLaunchKernelGGL((hs_gemm_bf16_mfma<EPI, MODE, MI, NI, SW>), grid, dim3(256), lds, st, a, w, w2, c, part, m_dev, m_max,
+                       n, k, m_tiles, n_tiles, tpc);
 }
 
 template <int EPI>
@@ -373,21 +385,37 @@ void launch(const hs_ctx* ctx, const bf16_t* a, const bf16_t* w, const bf16_t* w
     const int tpc = (nk + chunks - 1) / chunks;
     chunks = (nk + tpc - 1) / tpc;  // no empty chunk
     float* part = reinterpret_cast<float*>(ctx->ws + ctx->lay.gemm_part);
-    // Launch shape from the row hint: narrow outputs run split over K while the row tiles alone would leave compute
-    // units idle.
-    const bool split = chunks > 1 && rows_hint <= 512;
-    if (chunks == 1) {
-        launch_tile<EPI, MODE_PLAIN, 2, 3>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st);
-    } else if (!split) {
-        launch_tile<EPI, MODE_SERIAL, 2, 3>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st);
+    // Launch shape from the row hint.  Tile height: 128 rows while all rows fit one tile, else 256.  Tile width:
+    // 256 weight rows where the output is wide enough to put a workgroup on every compute unit anyway (the wider
+    // tile re-reads half as many activation bytes per weight byte), else 128.  Narrow outputs run split over K
+    // while the row tiles alone would leave compute units idle.
+    const bool tall = rows_hint > 128;
+#define HS_ARGS a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st
+    if constexpr (EPI == HS_EPI_SWIGLU_BF16) {
+        if (tall) launch_tile<EPI, MODE_PLAIN, 4, 4, 3>(HS_ARGS);
+        else launch_tile<EPI, MODE_PLAIN, 2, 4, 3>(HS_ARGS);
+    } else if (chunks == 1) {
+        if (tall) launch_tile<EPI, MODE_PLAIN, 4, 4, 3>(HS_ARGS);
+        else launch_tile<EPI, MODE_PLAIN, 2, 4, 3>(HS_ARGS);
+    } else if (rows_hint > 512) {
+        launch_tile<EPI, MODE_SERIAL, 2, 2, 3>(HS_ARGS);
     } else {
-        launch_tile<EPI, MODE_SPLIT, 2, 3>(a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st);
-        if (EPI != HS_EPI_SWIGLU_BF16) {
-            int rows = rows_hint < 1 ? 1 : (2 * rows_hint > m_max ? m_max : 2 * rows_hint);
-            hipLaunchKernelGGL((gemm_split_reduce<EPI>), dim3((n / 4 + 255) / 256, rows), dim3(256), 0, st, part,
-                               reinterpret_cast<float*>(c), m_dev, m_max, n, chunks);
+        const int n128 = (n + 127) / 128;
+        const int m_tiles = tall ? (rows_hint + 255) / 256 : 1;
+        // workgroups that can be resident at once: two per compute unit with the 128 x 128 tile, else one
+        const bool wide = n128 * chunks * m_tiles > (tall ? 256 : 512);
+        if (tall) {
+            if (wide) launch_tile<EPI, MODE_SPLIT, 4, 4, 3>(HS_ARGS);
+            else launch_tile<EPI, MODE_SPLIT, 4, 2, 3>(HS_ARGS);
+        } else {
+            if (wide) launch_tile<EPI, MODE_SPLIT, 2, 4, 3>(HS_ARGS);
+            else launch_tile<EPI, MODE_SPLIT, 2, 2, 3>(HS_ARGS);
         }
+        int rows = rows_hint < 1 ? 1 : (2 * rows_hint > m_max ? m_max : 2 * rows_hint);
+        hipLaunchKernelGGL((gemm_split_reduce<EPI>), dim3((n / 4 + 255) / 256, rows), dim3(256), 0, st, part,
+                           reinterpret_cast<float*>(c), m_dev, m_max, n, chunks);
     }
+#undef HS_ARGS
 }
 
 }  // namespace
@@ -396,7 +424,7 @@ void launch(const hs_ctx* ctx, const bf16_t* a, const bf16_t* w, const bf16_t* w
 // to 8 chunks so that the split execution can put several hundred workgroups on the chip; every chunk keeps at
 // least 4 k-tiles.
 int hs_gemm_chunks(int n, int k) {
-    const int n_tiles = (n + BN - 1) / BN;
+    const int n_tiles = (n + 127) / 128;  // 128-column tiles, whatever tile shape executes the product
     int chunks = (512 + n_tiles - 1) / n_tiles;
     if (chunks > 8) chunks = 8;
     const int nk = k / BK;
