@@ -211,6 +211,17 @@ hs_status hs_poll_error(hs_ctx* ctx, hs_stream stream, uint32_t* error_bits);
  * 2 last layer's attention output bf16 (same shape), 3 logits f32 [max_rows][vocab]. */
 hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size_t* bytes);
 
+/* One projection on its own, through the same launcher hs_verify uses (unit-level parity tests and timing):
+ * C[m, n] (+)= A[m, k] . W[n, k]^T with bf16 operands, K-contiguous, fp32 accumulation in the shape's fixed K
+ * order.  epi 0: C f32 = product; 1: C f32 += product; 2: SwiGLU, C bf16 [m][n] = silu(A.W^T) * (A.W2^T).
+ * All pointers are device memory owned by the caller; m_dev points at the int32 row count (<= m_max, the leading
+ * dimension of the partial-sum scratch, itself <= the context's max_rows); n, k must not exceed the widest
+ * projection of the context's model (the split execution borrows the context's workspace) and k % 64 == 0.
+ * rows_hint steers launch shapes only.  Enqueues on `stream`; HS_ERR_INVALID_ARG on bad arguments. */
+hs_status hs_debug_gemm(hs_ctx* ctx, int32_t epi, const void* a, const void* w, const void* w2, void* c,
+                        const int32_t* m_dev, int32_t m_max, int32_t n, int32_t k, int32_t rows_hint,
+                        hs_stream stream);
+
 /* Kernel timing with HIP events on the call's stream.  hs_set_profile(ctx, level): 0 off; 1 brackets the attention
  * kernel of every layer and the whole hs_verify call (cheap enough for a timed run); 2 brackets every kernel
  * launch of hs_verify (each pair of events costs a few microseconds of stream time: use it on steps that are not

@@ -34,12 +34,26 @@ def sources():
 def build(force: bool = True) -> str:
     """Compile every HIP source for gfx950 into libhistospec.so (in-tree)."""
     srcs = sources()
-    deps = srcs + [os.path.join(_CSRC, "hs_internal.h"), os.path.join(_ROOT, "include", "histospec.h")]
+    deps = srcs + [os.path.join(_CSRC, "hs_internal.h"), os.path.join(_CSRC, "hs_gemm_common.h"), os.path.join(_ROOT, "include", "histospec.h")]
     if not force and os.path.exists(LIB_PATH) and all(os.path.getmtime(LIB_PATH) >= os.path.getmtime(d) for d in deps):
         return LIB_PATH
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I" + os.path.join(_ROOT, "include"), "-I" + _CSRC] + srcs + ["-o", LIB_PATH]
-    subprocess.check_call(cmd, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    inc = ["-I" + os.path.join(_ROOT, "include"), "-I" + _CSRC]
+    # one object per source, compiled side by side, then one link
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    with tempfile.TemporaryDirectory(prefix="hs_build_") as tmp:
+        objs = [os.path.join(tmp, os.path.basename(s_)[:-4] + ".o") for s_ in srcs]
+        flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+
+        def one(pair):
+            subprocess.check_call([hipcc] + flags + inc + ["-c", pair[0], "-o", pair[1]],
+                                  stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+
+        with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
+            list(ex.map(one, zip(srcs, objs)))
+        subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB_PATH],
+                              stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
     return LIB_PATH
 
 
@@ -92,7 +106,7 @@ class hs_accept_args(C.Structure):
 
 EXPORTS = ("hs_create", "hs_destroy", "hs_last_error", "hs_set_flags", "hs_workspace_bytes", "hs_bind_workspace",
            "hs_draft", "hs_verify", "hs_accept", "hs_kv_commit", "hs_poll_error", "hs_debug_buffer",
-           "hs_set_profile", "hs_get_profile")
+           "hs_set_profile", "hs_get_profile", "hs_debug_gemm")
 
 _lib = None
 
@@ -127,6 +141,7 @@ def lib():
         L.hs_debug_buffer.argtypes = [vp, C.c_int32, C.POINTER(vp), C.POINTER(C.c_size_t)]
         L.hs_set_profile.argtypes = [vp, C.c_int32]
         L.hs_get_profile.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+        L.hs_debug_gemm.argtypes = [vp, C.c_int32, vp, vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp]
         _lib = L
     return _lib
 
@@ -199,6 +214,11 @@ def hs_debug_buffer(ctx, which: int):
 
 def hs_set_profile(ctx, level: int):
     _check(ctx, lib().hs_set_profile(ctx, int(level)))
+
+
+def hs_debug_gemm(ctx, epi: int, a: int, w: int, w2: int, c: int, m_dev: int, m_max: int, n: int, k: int,
+                  rows_hint: int, stream):
+    _check(ctx, lib().hs_debug_gemm(ctx, epi, a, w, w2 or None, c, m_dev, m_max, n, k, rows_hint, stream))
 
 
 def hs_get_profile(ctx):

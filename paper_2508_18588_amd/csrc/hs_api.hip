@@ -43,7 +43,8 @@ void layout_workspace(hs_ctx* ctx) {
     size_t part_cols = std::max({(size_t)hs_gemm_chunks((int)nqkv, d.d_model) * nqkv,
                                  (size_t)hs_gemm_chunks(d.d_model, (int)qh) * d.d_model,
                                  (size_t)hs_gemm_chunks(d.d_model, d.d_ffn) * d.d_model});
-    w.gemm_part = take(M * part_cols * 4);
+    w.gemm_part_bytes = M * part_cols * 4;
+    w.gemm_part = take(w.gemm_part_bytes);
     w.total = off;
 }
 
@@ -338,6 +339,32 @@ hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size
         case 3: *dev_ptr = ctx->ws + ctx->lay.logits; *bytes = M * (size_t)d.vocab * 4; break;
         default: return HS_ERR_INVALID_ARG;
     }
+    return HS_OK;
+}
+
+hs_status hs_debug_gemm(hs_ctx* ctx, int32_t epi, const void* a, const void* w, const void* w2, void* c,
+                        const int32_t* m_dev, int32_t m_max, int32_t n, int32_t k, int32_t rows_hint,
+                        hs_stream stream) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
+    if (epi < HS_EPI_STORE_F32 || epi > HS_EPI_SWIGLU_BF16 || !a || !w || !c || !m_dev ||
+        (epi == HS_EPI_SWIGLU_BF16 && !w2))
+        return fail(ctx, HS_ERR_INVALID_ARG, "hs_debug_gemm: arguments");
+    const hs_model_desc& d = ctx->desc;
+    const long long qh = (long long)d.n_q_heads * d.head_dim;
+    const long long nqkv = (long long)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+    const long long n_lim = std::max<long long>({d.vocab, d.d_ffn, nqkv, d.d_model});
+    const long long k_lim = std::max<long long>({d.d_model, d.d_ffn, qh});
+    if (m_max < 1 || m_max > ctx->lim.max_rows || n < 1 || n > n_lim || k < 64 || k > k_lim || k % 64 != 0)
+        return fail(ctx, HS_ERR_INVALID_ARG, "hs_debug_gemm: shape outside the context's model");
+    // the split execution writes chunks * m_max * n floats of partial sums
+    const int chunks = epi == HS_EPI_SWIGLU_BF16 ? 1 : hs_gemm_chunks(n, k);
+    if (chunks > 1 && (size_t)chunks * m_max * n * 4 > ctx->lay.gemm_part_bytes)
+        return fail(ctx, HS_ERR_CAPACITY, "hs_debug_gemm: partial-sum scratch too small for this shape");
+    (void)hipGetLastError();
+    hs_launch_gemm(ctx, epi, (const bf16_t*)a, (const bf16_t*)w, (const bf16_t*)w2, c, m_dev, m_max, n, k,
+                   rows_hint > 0 ? rows_hint : m_max, (hipStream_t)stream);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_debug_gemm", e);
     return HS_OK;
 }
 

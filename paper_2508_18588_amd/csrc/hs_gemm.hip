@@ -25,40 +25,13 @@
 // as the host-side row hint suggests; a workgroup walks row tiles with that stride until it passes M, so any M up
 // to m_max is covered whatever the hint was.  Workgroup ids are spread so that all row tiles that read the same
 // W tile run on the same XCD (ids are dealt round-robin to the 8 XCDs, each with its own L2).
-#include "hs_internal.h"
+#include "hs_gemm_common.h"
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+using namespace hs_gemm_detail;
 
 namespace {
 
-constexpr int BK = 64;
-constexpr int ROW_BYTES = BK * 2;  // one tile row in LDS: 8 chunks of 16 bytes
-
 enum { MODE_PLAIN = 0, MODE_SERIAL = 1, MODE_SPLIT = 2 };
-
-// vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
-#define HS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
-
-// Chunk swizzle of tile row r: consecutive rows 0..15 map to the 16 distinct (row parity, chunk) bank groups, and
-// rows 0..7 to even values, so that the two k-halves of a fragment read (chunks c and c^1) never collide either.
-__device__ __forceinline__ int swz(int r) { return (((r >> 1) & 3) << 1) | ((r >> 3) & 1); }
-
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-
-// 16 bytes per lane from global memory straight into LDS: lane i's data lands at LDS byte offset lds_off + 16 * i
-// (lds_off is wavefront-uniform and travels in M0).  Counted by vmcnt like any other load.  Issued as inline
-// assembly so that the compiler's wait-count bookkeeping does not see it: told about such a load it treats every
-// later LDS read as possibly returning out of order and waits for all of them at once, which serialises fragment
-// reads and matrix-core work; the kernel places the vmcnt waits for these loads itself.  Any wait the compiler
-// inserts for its own loads can only be stricter than needed, because loads complete in issue order.
-// The source address is a wavefront-uniform base (scalar registers) plus a 32-bit unsigned byte offset per lane.
-__device__ __forceinline__ void load_to_lds_16(const unsigned char* base, unsigned off, unsigned lds_off) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_off), "v"(off), "s"(base)
-                 : "memory", "m0");
-}
 
 }  // namespace
 
@@ -385,6 +358,16 @@ void launch(const hs_ctx* ctx, const bf16_t* a, const bf16_t* w, const bf16_t* w
     const int tpc = (nk + chunks - 1) / chunks;
     chunks = (nk + tpc - 1) / tpc;  // no empty chunk
     float* part = reinterpret_cast<float*>(ctx->ws + ctx->lay.gemm_part);
+    if (rows_hint <= HS_GEMM_STREAM_MAX_ROWS) {
+        // few rows: the projection is a weight stream; one workgroup holds all rows against its weight slab
+        hs_launch_gemm_stream(EPI, a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st);
+        if (chunks > 1) {
+            const int rows = rows_hint < 1 ? 1 : (2 * rows_hint > m_max ? m_max : 2 * rows_hint);
+            hipLaunchKernelGGL((gemm_split_reduce<EPI>), dim3((n / 4 + 255) / 256, rows), dim3(256), 0, st, part,
+                               reinterpret_cast<float*>(c), m_dev, m_max, n, chunks);
+        }
+        return;
+    }
     // Launch shape from the row hint.  Tile height: 128 rows while all rows fit one tile, else 256.  Tile width:
     // 256 weight rows where the output is wide enough to put a workgroup on every compute unit anyway (the wider
     // tile re-reads half as many activation bytes per weight byte), else 128.  Narrow outputs run split over K
@@ -420,13 +403,12 @@ void launch(const hs_ctx* ctx, const bf16_t* a, const bf16_t* w, const bf16_t* w
 
 }  // namespace
 
-// Number of K chunks of a projection: a function of the shape alone.  Narrow outputs (few column tiles) get up
-// to 8 chunks so that the split execution can put several hundred workgroups on the chip; every chunk keeps at
-// least 4 k-tiles.
+// Number of K chunks of a projection: a function of the shape alone.  Narrow outputs get as many chunks as put
+// about one workgroup of the weight-streaming execution (128 weight rows each) on every one of the 256 compute
+// units; every chunk keeps at least 4 k-tiles.
 int hs_gemm_chunks(int n, int k) {
-    const int n_tiles = (n + 127) / 128;  // 128-column tiles, whatever tile shape executes the product
-    int chunks = (512 + n_tiles - 1) / n_tiles;
-    if (chunks > 8) chunks = 8;
+    const int groups = (n + 127) / 128;
+    int chunks = 256 / groups;
     const int nk = k / BK;
     if (chunks > nk / 4) chunks = nk / 4;
     if (chunks < 1) chunks = 1;

@@ -1,0 +1,408 @@
+// Weight-streaming bf16 MFMA GEMM for the row counts of a verify step (up to a few hundred draft-tree rows):
+//   C[M,N] (+)= A[M,K] . W[N,K]^T  with the same arithmetic, in the same order, as the tile-grid kernel.
+//
+// At these row counts a projection is bound by streaming its weights from HBM exactly once, with the matrix cores
+// needed at roughly half their rate just to keep up (220 rows: 220 flop per weight byte).  The kernel is laid out
+// around the weight stream:
+//   * One workgroup per (group of NU 32-row weight units, K chunk); unit and chunk counts are chosen by the host
+//     so that one round of workgroups covers the 256 compute units.  A workgroup holds ALL rows (up to 128*MT)
+//     against its weight slab, so every weight byte is fetched once.
+//   * Row tile t (32 rows) belongs to wavefront t % 4.  A wavefront multiplies only the row tiles that exist
+//     (M is read on the device) against all NU weight units; its accumulators stay in registers for the whole chunk.
+//   * Tiles (64 deep in K) travel from global memory straight into LDS (global_load_lds_dwordx4) through an
+//     SA-stage activation ring and an SW-stage weight ring.
+//   * One instruction stream per SIMD: a wavefront issues in order, so a fragment read that waits its turn at the
+//     LDS (four wavefronts share it) keeps the next MFMA from issuing.  The loop is therefore software-pipelined
+//     over k-steps of 16 -- the fragments of step s+2 are read while step s is multiplied, across tile boundaries --
+//     and the reads are interleaved one by one with the MFMAs (sched_group_barrier), so that the matrix pipe always
+//     has its next instruction while the wavefront negotiates the LDS.  The tile hand-over (wait for the loads of
+//     the next tile, workgroup barrier, issue of new loads) sits in the middle of a tile, after the last fragment
+//     read of the current one has been issued.
+// SwiGLU pairs the gate and up rows of 16 output columns in one 32-row weight unit, so that both pre-activations of
+// a column meet in one MFMA tile (lanes c and c+16).
+#include "hs_gemm_common.h"
+
+using namespace hs_gemm_detail;
+
+namespace {
+
+constexpr int TILE_BYTES = 32 * ROW_BYTES;  // a 32-row tile of either operand, 64 deep: 4 KB
+
+// A pointer known to be the same in every lane, moved to scalar registers.
+__device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char* p) {
+    const unsigned long long v = (unsigned long long)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return (const unsigned char*)(((unsigned long long)hi << 32) | lo);
+}
+
+// s_waitcnt vmcnt(n) for a wavefront-uniform run-time n (the instruction takes an immediate).
+__device__ __forceinline__ void wait_vmcnt_dyn(int n) {
+    switch (n) {
+#define HS_CASE(i) case i: HS_WAIT_VMCNT(i); break;
+        HS_CASE(0) HS_CASE(1) HS_CASE(2) HS_CASE(3) HS_CASE(4) HS_CASE(5) HS_CASE(6) HS_CASE(7) HS_CASE(8)
+        HS_CASE(9) HS_CASE(10) HS_CASE(11) HS_CASE(12) HS_CASE(13) HS_CASE(14) HS_CASE(15) HS_CASE(16)
+        HS_CASE(17) HS_CASE(18) HS_CASE(19) HS_CASE(20) HS_CASE(21) HS_CASE(22) HS_CASE(23) HS_CASE(24)
+        HS_CASE(25) HS_CASE(26) HS_CASE(27) HS_CASE(28) HS_CASE(29) HS_CASE(30) HS_CASE(31) HS_CASE(32)
+#undef HS_CASE
+        default: HS_WAIT_VMCNT(32); break;  // stricter than asked for is always correct
+    }
+}
+
+struct stream_args {
+    const unsigned char* A;
+    const unsigned char* wb[2];  // weight matrices (gate, up) or (W, W)
+    void* Cout;
+    float* part;
+    int M, m_max, N, K, n0, m0, kt0, kt1, chunk;
+};
+
+// One K chunk of one row pass for a wavefront that owns NMI live row tiles (0 = loads and barriers only).
+template <int EPI, bool PARTIAL, int NU, int MT, int SA, int SW, int NMI>
+__device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char* smem, unsigned smem_off,
+                                             const unsigned (&w_off)[NU], int wave, int lane) {
+    static_assert(SA >= 2 && SA <= SW, "the hand-over bookkeeping assumes the activation ring is the shorter one");
+    constexpr int A_STAGE = 4 * MT * TILE_BYTES, W_STAGE = NU * TILE_BYTES, W_RING = SA * A_STAGE;
+    constexpr int NLW = NU;  // 1 KB load instructions per weight tile and wavefront
+    constexpr int NM = NMI > 0 ? NMI : 1;
+    const int lrow = lane >> 3, lpos = lane & 7;
+    const int l32 = lane & 31, g = lane >> 5, fl = swz(l32);
+    const int frag_row = l32 * ROW_BYTES;
+    const unsigned a_chunk = (unsigned)((lpos ^ swz(8 * wave + lrow)) << 4);
+    const int a_row = p.m0 + 8 * wave + lrow;
+    const unsigned row_pitch = (unsigned)p.K * 2u;
+    // 8-row blocks of the activation tile this wavefront fetches: block wave + 4j covers rows 32j + 8*wave .. +7
+    // of the pass; blocks past the last row are not fetched.
+    int n_a = 0;
+#pragma unroll
+    for (int j = 0; j < 4 * MT; j++)
+        if (p.m0 + 8 * wave + 32 * j < p.M) n_a = j + 1;
+    n_a = __builtin_amdgcn_readfirstlane(n_a);
+
+    auto issue_a = [&](int kt) {
+        const unsigned dst = smem_off + (kt % SA) * A_STAGE + wave * 1024;
+        const unsigned char* base = p.A + (size_t)kt * ROW_BYTES;
+#pragma unroll
+        for (int j = 0; j < 4 * MT; j++) {
+            if (j < n_a) {
+                const unsigned off = (unsigned)min(a_row + 32 * j, p.M - 1) * row_pitch + a_chunk;
+                load_to_lds_16(base, off, dst + j * 4096);
+            }
+        }
+    };
+    // weight tile: block wave + 4j = quarter `wave` of unit j; a SwiGLU unit holds 16 gate rows then the 16 up rows
+    // of the same columns, so a wavefront's blocks are all gate rows (wavefronts 0, 1) or all up rows (2, 3)
+    const unsigned char* w_mine = uniform_ptr((EPI == HS_EPI_SWIGLU_BF16 && wave >= 2) ? p.wb[1] : p.wb[0]);
+    auto issue_w = [&](int kt) {
+        const unsigned dst = smem_off + W_RING + (kt % SW) * W_STAGE + wave * 1024;
+        const unsigned char* base = w_mine + (size_t)kt * ROW_BYTES;
+#pragma unroll
+        for (int j = 0; j < NLW; j++) load_to_lds_16(base, w_off[j], dst + j * 4096);
+    };
+    // Hand-over number h (h < kt0 before the loop, then in the middle of tile h): first the activation tile h+SA,
+    // then the weight tile h+SW.  The issue order fixes the wait counts below.
+    // load number l of hand-over h, in issue order: the activation blocks, then the weight blocks
+    auto load_one = [&](int h, int l) {
+        if (l < 4 * MT) {
+            if (l < n_a && h + SA < p.kt1) {
+                const unsigned off = (unsigned)min(a_row + 32 * l, p.M - 1) * row_pitch + a_chunk;
+                load_to_lds_16(p.A + (size_t)(h + SA) * ROW_BYTES, off,
+                               smem_off + ((h + SA) % SA) * A_STAGE + wave * 1024 + l * 4096);
+            }
+        } else if (h + SW < p.kt1) {
+            load_to_lds_16(w_mine + (size_t)(h + SW) * ROW_BYTES, w_off[l - 4 * MT],
+                           smem_off + W_RING + ((h + SW) % SW) * W_STAGE + wave * 1024 + (l - 4 * MT) * 4096);
+        }
+    };
+    auto issue_for = [&](int h) {
+        if (h + SA >= p.kt0 && h + SA < p.kt1) issue_a(h + SA);
+        if (h + SW >= p.kt0 && h + SW < p.kt1) issue_w(h + SW);
+    };
+    // Loads complete in issue order.  Tile t is awaited in the middle of tile t-1, when the hand-overs up to t-2
+    // have been made.  Its activation part was issued at hand-over t-SA, its weight part at t-SW (earlier or the
+    // same).  What may still be outstanding is everything issued after the activation part of tile t: the weight
+    // tile of hand-over t-SA (unless that is tile t itself), and both tiles of the later hand-overs t-SA+1 .. t-2.
+    auto wait_tile = [&](int t) {
+        int cnt = 0;
+        if (SW > SA && t - SA + SW < p.kt1) cnt += NLW;
+#pragma unroll
+        for (int hh = 1; hh <= SA - 2; hh++) {
+            if (t + hh < p.kt1) cnt += n_a;
+            if (t - SA + hh + SW < p.kt1) cnt += NLW;
+        }
+        wait_vmcnt_dyn(cnt);
+    };
+
+    f32x16 acc[NM][NU];
+#pragma unroll
+    for (int i = 0; i < NM; i++)
+#pragma unroll
+        for (int j = 0; j < NU; j++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+    // prologue: the hand-overs a longer-running loop would have made before tile kt0, the last one as in the loop
+#pragma unroll
+    for (int h = -SW; h < -1; h++) issue_for(p.kt0 + h);
+    wait_tile(p.kt0);
+    __builtin_amdgcn_s_barrier();
+    issue_for(p.kt0 - 1);
+
+    bf16x8 fa[BK / 16][NM], fb[BK / 16][NU];
+    // fragments of k-step KS of tile KT: lane l reads tile row l%32, k-chunk 2*KS + l/32, at its swizzled position
+#define HS_FRAGS(KT, KS)                                                                                         \
+    if (NMI > 0) {                                                                                               \
+        const unsigned char* sta_ = smem + ((KT) % SA) * A_STAGE + wave * TILE_BYTES + frag_row;                 \
+        const unsigned char* stw_ = smem + W_RING + ((KT) % SW) * W_STAGE + frag_row;                            \
+        const int pos_ = ((2 * (KS) + g) ^ fl) << 4;                                                             \
+        _Pragma("unroll") for (int ni = 0; ni < NU; ni++)                                                        \
+            fb[KS][ni] = *reinterpret_cast<const bf16x8*>(stw_ + ni * TILE_BYTES + pos_);                        \
+        _Pragma("unroll") for (int mi = 0; mi < NMI; mi++)                                                       \
+            fa[KS][mi] = *reinterpret_cast<const bf16x8*>(sta_ + mi * 4 * TILE_BYTES + pos_);                    \
+    }
+#define HS_MFMAS(KS)                                                                                             \
+    _Pragma("unroll") for (int mi = 0; mi < NMI; mi++)                                                           \
+        _Pragma("unroll") for (int ni = 0; ni < NU; ni++)                                                        \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[KS][mi], fb[KS][ni], acc[mi][ni], 0, 0, 0);
+    // one MFMA, one fragment read, ... while there are reads; then the remaining MFMAs
+#define HS_INTERLEAVE()                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < NMI + NU; i++) {                                                       \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                       \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                       \
+    }                                                                                                            \
+    __builtin_amdgcn_sched_group_barrier(0x008, NMI * NU - (NMI + NU) > 0 ? NMI * NU - (NMI + NU) : 0, 0);
+
+    HS_FRAGS(p.kt0, 0)
+    HS_FRAGS(p.kt0, 1)
+    int kt = p.kt0;
+    for (; kt + 1 < p.kt1; kt++) {
+        __builtin_amdgcn_sched_barrier(0);
+        HS_FRAGS(kt, 2)
+        HS_MFMAS(0)
+        HS_INTERLEAVE()
+        __builtin_amdgcn_sched_barrier(0);
+        HS_FRAGS(kt, 3)
+        HS_MFMAS(1)
+        HS_INTERLEAVE()
+        __builtin_amdgcn_sched_barrier(0);
+        // Hand-over: every fragment read of tile kt has been issued; once they have returned (lgkmcnt) and all
+        // wavefronts have met, the slots of tile kt are free to be refilled.  Tile kt+1 must have landed: each
+        // wavefront waits for its own part before the barrier (a bare barrier: a fenced one would wait for the
+        // tiles in flight as well).
+        wait_tile(kt + 1);
+        __builtin_amdgcn_s_waitcnt((63 & 15) | ((63 >> 4) << 14) | (7 << 4) | (0 << 8));  // lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        // Second half of tile kt: k-steps 2 and 3, the first two fragment sets of tile kt+1, and the loads of this
+        // hand-over -- one after the other behind single MFMAs in a pinned order, because a wavefront that issues a
+        // dozen loads back to back stalls on the address path while its matrix pipe runs dry.
+        if (NMI == 0) {
+            issue_for(kt);
+        } else {
+            const unsigned char* sta_ = smem + ((kt + 1) % SA) * A_STAGE + wave * TILE_BYTES + frag_row;
+            const unsigned char* stw_ = smem + W_RING + ((kt + 1) % SW) * W_STAGE + frag_row;
+            constexpr int NMF = 2 * NM * NU, TL = 4 * MT + NU;
+#pragma unroll
+            for (int q = 0; q < NMF; q++) {
+                const int ks = 2 + q / (NM * NU), mi = (q % (NM * NU)) / NU, ni = q % NU;
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][mi], fb[ks][ni], acc[mi][ni], 0, 0, 0);
+                // this MFMA's share of the k-step's NU + NM fragment reads
+                const int pos_ = ((2 * (ks - 2) + g) ^ fl) << 4;
+#pragma unroll
+                for (int r = (q % (NM * NU)) * (NU + NM) / (NM * NU); r < (q % (NM * NU) + 1) * (NU + NM) / (NM * NU); r++) {
+                    if (r < NU) fb[ks - 2][r] = *reinterpret_cast<const bf16x8*>(stw_ + r * TILE_BYTES + pos_);
+                    else fa[ks - 2][r - NU] = *reinterpret_cast<const bf16x8*>(sta_ + (r - NU) * 4 * TILE_BYTES + pos_);
+                }
+#pragma unroll
+                for (int l = q * TL / NMF; l < (q + 1) * TL / NMF; l++) load_one(kt, l);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    // last tile of the chunk: nothing follows it
+    __builtin_amdgcn_sched_barrier(0);
+    HS_FRAGS(kt, 2)
+    HS_MFMAS(0)
+    HS_INTERLEAVE()
+    __builtin_amdgcn_sched_barrier(0);
+    HS_FRAGS(kt, 3)
+    HS_MFMAS(1)
+    HS_INTERLEAVE()
+    __builtin_amdgcn_sched_barrier(0);
+    HS_MFMAS(2)
+    HS_MFMAS(3)
+#undef HS_FRAGS
+#undef HS_MFMAS
+#undef HS_INTERLEAVE
+
+    // Epilogue.  Accumulator element e of a 32x32 tile: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
+    if (NMI > 0) {
+        const int lr = 4 * (lane >> 5), lc = lane & 31;
+#pragma unroll
+        for (int mi = 0; mi < NMI; mi++) {
+            const int row0 = p.m0 + 32 * (wave + 4 * mi) + lr;
+            if (EPI == HS_EPI_SWIGLU_BF16) {
+                bf16_t* C = reinterpret_cast<bf16_t*>(p.Cout);
+#pragma unroll
+                for (int ni = 0; ni < NU; ni++) {
+                    const int col = p.n0 + 16 * ni + (lc & 15);
+#pragma unroll
+                    for (int e = 0; e < 16; e++) {
+                        const float own = acc[mi][ni][e];
+                        const float other = __shfl_xor(own, 16);  // lanes c and c+16: gate and up of column c
+                        const int row = row0 + 8 * (e >> 2) + (e & 3);
+                        if (lc < 16 && col < p.N && row < p.M) {
+                            const float s = own / (1.f + __expf(-own));
+                            C[(size_t)row * p.N + col] = f32_to_bf16(s * other);
+                        }
+                    }
+                }
+            } else {
+                float* C = PARTIAL ? p.part + (size_t)p.chunk * p.m_max * p.N : reinterpret_cast<float*>(p.Cout);
+#pragma unroll
+                for (int ni = 0; ni < NU; ni++) {
+                    const int col = p.n0 + 32 * ni + lc;
+                    if (col >= p.N) continue;
+#pragma unroll
+                    for (int e = 0; e < 16; e++) {
+                        const int row = row0 + 8 * (e >> 2) + (e & 3);
+                        if (row < p.M) {
+                            float* dst = &C[(size_t)row * p.N + col];
+                            if (!PARTIAL && EPI == HS_EPI_ADD_F32) *dst += acc[mi][ni][e];
+                            else *dst = acc[mi][ni][e];
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+// NU weight units per workgroup, MT row tiles per wavefront (128*MT rows per pass), SA / SW ring stages.
+// (External linkage: the host takes the kernel's address to raise its dynamic LDS limit.)
+template <int EPI, bool PARTIAL, int NU, int MT, int SA, int SW>
+__global__ __launch_bounds__(256) void hs_gemm_stream(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                      const bf16_t* __restrict__ W2, void* __restrict__ Cout,
+                                                      float* __restrict__ part, const int32_t* __restrict__ m_dev,
+                                                      int m_max, int N, int K, int tpc) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const unsigned smem_off = (unsigned)(size_t)(lds_ptr_t)smem;
+    constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? 16 * NU : 32 * NU;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    stream_args p;
+    p.M = *m_dev;
+    p.A = reinterpret_cast<const unsigned char*>(A);
+    p.wb[0] = reinterpret_cast<const unsigned char*>(W);
+    p.wb[1] = reinterpret_cast<const unsigned char*>(EPI == HS_EPI_SWIGLU_BF16 ? W2 : W);
+    p.Cout = Cout;
+    p.part = part;
+    p.m_max = m_max;
+    p.N = N;
+    p.K = K;
+    p.n0 = blockIdx.x * NCOLS;
+    p.chunk = blockIdx.y;
+    const int nk = K / BK;
+    p.kt0 = blockIdx.y * tpc;
+    p.kt1 = min(nk, p.kt0 + tpc);
+
+    // Weight loader geometry: instruction j of wavefront w fills the 1 KB block (w + 4j) of a tile = rows 8w..8w+7
+    // of unit j; lane i lands on row i/8, chunk position i%8 and therefore fetches chunk (i%8) ^ swz(row).  Rows
+    // beyond N are clamped to the last valid row: their products are computed and never stored.
+    // (32-bit byte offsets: the host checks that every operand stays below 4 GiB.)
+    const int lrow = lane >> 3, lpos = lane & 7;
+    unsigned w_off[NU];
+#pragma unroll
+    for (int j = 0; j < NU; j++) {
+        const int row = 8 * wave + lrow;  // row within the unit
+        const int gn = (EPI == HS_EPI_SWIGLU_BF16) ? p.n0 + 16 * j + 8 * (wave & 1) + lrow : p.n0 + 32 * j + row;
+        w_off[j] = (unsigned)min(gn, N - 1) * (unsigned)(K * 2) + ((lpos ^ swz(row)) << 4);
+    }
+
+    for (p.m0 = 0; p.m0 < p.M; p.m0 += 128 * MT) {
+        int nmi = 0;
+#pragma unroll
+        for (int s = 0; s < MT; s++)
+            if (p.m0 + 32 * (wave + 4 * s) < p.M) nmi = s + 1;
+        nmi = __builtin_amdgcn_readfirstlane(nmi);
+        if (nmi == 0) stream_chunk<EPI, PARTIAL, NU, MT, SA, SW, 0>(p, smem, smem_off, w_off, wave, lane);
+        else if (nmi == 1) stream_chunk<EPI, PARTIAL, NU, MT, SA, SW, 1>(p, smem, smem_off, w_off, wave, lane);
+        else if (MT >= 2 && nmi == 2)
+            stream_chunk<EPI, PARTIAL, NU, MT, SA, SW, (MT >= 2 ? 2 : 1)>(p, smem, smem_off, w_off, wave, lane);
+        else if (MT >= 3)
+            stream_chunk<EPI, PARTIAL, NU, MT, SA, SW, (MT >= 3 ? 3 : 1)>(p, smem, smem_off, w_off, wave, lane);
+        __syncthreads();  // the rings are reused by the next row pass
+    }
+}
+
+namespace {
+
+template <int EPI, bool PARTIAL, int NU, int MT, int SA, int SW>
+void launch_stream(const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, float* part, const int32_t* m_dev,
+                   int m_max, int n, int k, int chunks, int tpc, hipStream_t st) {
+    constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? 16 * NU : 32 * NU;
+    constexpr size_t lds = (size_t)(SA * 4 * MT + SW * NU) * TILE_BYTES;
+    static_assert(lds <= 160 * 1024, "LDS of one compute unit");
+    static_assert((SA - 1) * (4 * MT + NU) + NU <= 32, "wait counts");
+    static bool configured = false;  // more than 64 KB of dynamic LDS has to be asked for once per kernel
+    if (!configured) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&hs_gemm_stream<EPI, PARTIAL, NU, MT, SA, SW>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        configured = true;
+    }
+    dim3 grid((n + NCOLS - 1) / NCOLS, chunks);
+    hipLaunchKernelGGL((hs_gemm_stream<EPI, PARTIAL, NU, MT, SA, SW>), grid, dim3(256), lds, st, a, w, w2, c, part,
+                       m_dev, m_max, n, k, tpc);
+}
+
+// Units per workgroup: the candidate that needs the fewest unit-times to cover the output on 256 compute units.
+int choose_units(int units, int chunks) {
+    int best = 4, best_cost = 1 << 30;
+    for (int nu : {5, 4}) {
+        const int wgs = ((units + nu - 1) / nu) * chunks;
+        const int cost = ((wgs + 255) / 256) * nu;
+        if (cost < best_cost) { best = nu; best_cost = cost; }
+    }
+    return best;
+}
+
+template <int EPI, bool PARTIAL>
+void launch_stream_shape(const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, float* part,
+                         const int32_t* m_dev, int m_max, int n, int k, int chunks, int tpc, int rows_hint,
+                         hipStream_t st) {
+    const int unit_cols = (EPI == HS_EPI_SWIGLU_BF16) ? 16 : 32;
+    const int nu = choose_units((n + unit_cols - 1) / unit_cols, chunks);
+    // Rows per pass: 256 leaves LDS for deeper rings; 384 once the hint comes close to 256, so that a step a
+    // little above its average does not pay a second pass over the weights.
+    const bool tall = rows_hint > 224;
+#define HS_ARGS a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, st
+    if (nu == 5) {
+        if (tall) launch_stream<EPI, PARTIAL, 5, 3, 2, 3>(HS_ARGS);
+        else launch_stream<EPI, PARTIAL, 5, 2, 2, 4>(HS_ARGS);
+    } else {
+        if (tall) launch_stream<EPI, PARTIAL, 4, 3, 2, 4>(HS_ARGS);
+        else launch_stream<EPI, PARTIAL, 4, 2, 2, 5>(HS_ARGS);
+    }
+#undef HS_ARGS
+}
+
+}  // namespace
+
+void hs_launch_gemm_stream(int epi, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, float* part,
+                           const int32_t* m_dev, int m_max, int n, int k, int chunks, int tpc, int rows_hint,
+                           hipStream_t st) {
+#define HS_ARGS a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st
+    if (epi == HS_EPI_SWIGLU_BF16) {
+        launch_stream_shape<HS_EPI_SWIGLU_BF16, false>(HS_ARGS);
+    } else if (chunks > 1) {
+        // partial sums: the ordered reduce applies the epilogue
+        launch_stream_shape<HS_EPI_STORE_F32, true>(HS_ARGS);
+    } else if (epi == HS_EPI_ADD_F32) {
+        launch_stream_shape<HS_EPI_ADD_F32, false>(HS_ARGS);
+    } else {
+        launch_stream_shape<HS_EPI_STORE_F32, false>(HS_ARGS);
+    }
+#undef HS_ARGS
+}

@@ -17,7 +17,7 @@ constexpr int HS_DRAFT_SEG = 4096;
 constexpr int HS_MAX_NODES = 64;  // ancestor masks are 64-bit
 
 struct hs_workspace_layout {
-    size_t x, xn, qkv, q, attn, act, part_o, part_ml, logits, draft_best, gemm_part, err, total;
+    size_t x, xn, qkv, q, attn, act, part_o, part_ml, logits, draft_best, gemm_part, gemm_part_bytes, err, total;
 };
 
 struct hs_ctx {

@@ -10,7 +10,7 @@ from dataclasses import dataclass
 import numpy as np
 import torch
 
-from . import (HS_ACCEPT_GREEDY, HS_K_FIXED, hs_accept, hs_accept_args, hs_bind_workspace, hs_create, hs_debug_buffer,
+from . import (HS_ACCEPT_GREEDY, HS_K_FIXED, hs_accept, hs_accept_args, hs_bind_workspace, hs_create, hs_debug_buffer, hs_debug_gemm,
                hs_destroy, hs_draft, hs_draft_args, hs_get_profile, hs_kv_cache, hs_kv_commit, hs_limits,
                hs_model_desc, hs_policy, hs_poll_error, hs_seq_state, hs_set_flags, hs_set_profile, hs_step,
                hs_verify, hs_weights, hs_workspace_bytes)
@@ -229,6 +229,13 @@ class Engine:
 
     def get_profile(self):
         return hs_get_profile(self.ctx)
+
+    def gemm(self, epi: int, a, w, w2, c, m_dev, m_max: int, rows_hint: int = 0):
+        """One projection through hs_debug_gemm: a [m_max, k] bf16 bits, w (and w2) [n, k] bf16 bits, c [m_max, n]
+        (f32 for epi 0/1, bf16 bits for epi 2), m_dev an int32 device tensor holding the live row count."""
+        n, k = int(w.shape[0]), int(w.shape[1])
+        hs_debug_gemm(self.ctx, epi, a.data_ptr(), w.data_ptr(), 0 if w2 is None else w2.data_ptr(), c.data_ptr(),
+                      m_dev.data_ptr(), m_max, n, k, rows_hint, self.stream())
 
     # ---------------------------------------------------------------- hand-made rows (prefill, tests)
 
