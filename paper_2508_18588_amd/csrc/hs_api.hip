@@ -154,7 +154,7 @@ hs_status hs_create(const hs_model_desc* desc, const hs_weights* w, const hs_lim
     ctx->att_part = HS_ATT_PART_DEFAULT;
     if (const char* e = std::getenv("HS_ATT_PART")) {
         int v = std::atoi(e);
-        if (v >= 32 && v % 32 == 0) ctx->att_part = v;
+        if (v >= 32 && v <= 1024 && v % 32 == 0) ctx->att_part = v;  // at most 64 pages per partition
     }
     const long long max_keys = (long long)l.max_blocks_per_seq * 16;
     ctx->max_parts = (int)((max_keys + ctx->att_part - 1) / ctx->att_part);
@@ -235,15 +235,20 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
     pr.begin(3);
     hs_launch_embed(ctx, step, seq->batch, x, st);
     pr.end();
+    // A projection run in the split execution leaves its chunk partials for the next kernel in line (RMSNorm for
+    // the residual projections, rotary/KV write for QKV), which adds them up in chunk order: one launch fewer per
+    // projection.  `pend` carries the number of chunks from the projection to that kernel.
+    int pend = 0;
     for (int l = 0; l < d.n_layers; l++) {
         pr.begin(3);
-        hs_launch_rmsnorm(ctx, x, ctx->norm1[l], xn, m_dev, st);
+        hs_launch_rmsnorm(ctx, x, ctx->norm1[l], xn, m_dev, pend, st);
         pr.end();
         pr.begin(1);
-        hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->wqkv[l], nullptr, qkv, m_dev, m_max, nqkv, d.d_model, hint, st);
+        hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->wqkv[l], nullptr, qkv, m_dev, m_max, nqkv, d.d_model, hint, st,
+                       &pend);
         pr.end();
         pr.begin(3);
-        hs_launch_rope_kv(ctx, l, cache, seq, step, qkv, q, st);
+        hs_launch_rope_kv(ctx, l, cache, seq, step, qkv, q, pend, st);
         pr.end();
         pr.begin(0);
         hs_launch_attention(ctx, l, cache, seq, step, q, attn, st);
@@ -252,20 +257,21 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
         hs_launch_attention_merge(ctx, seq, step, attn, st);
         pr.end();
         pr.begin(1);
-        hs_launch_gemm(ctx, HS_EPI_ADD_F32, attn, ctx->wo[l], nullptr, x, m_dev, m_max, d.d_model, qh, hint, st);
+        hs_launch_gemm(ctx, HS_EPI_ADD_F32, attn, ctx->wo[l], nullptr, x, m_dev, m_max, d.d_model, qh, hint, st, &pend);
         pr.end();
         pr.begin(3);
-        hs_launch_rmsnorm(ctx, x, ctx->norm2[l], xn, m_dev, st);
+        hs_launch_rmsnorm(ctx, x, ctx->norm2[l], xn, m_dev, pend, st);
         pr.end();
         pr.begin(1);
         hs_launch_gemm(ctx, HS_EPI_SWIGLU_BF16, xn, ctx->wgate[l], ctx->wup[l], act, m_dev, m_max, d.d_ffn, d.d_model, hint, st);
         pr.end();
         pr.begin(1);
-        hs_launch_gemm(ctx, HS_EPI_ADD_F32, act, ctx->wdown[l], nullptr, x, m_dev, m_max, d.d_model, d.d_ffn, hint, st);
+        hs_launch_gemm(ctx, HS_EPI_ADD_F32, act, ctx->wdown[l], nullptr, x, m_dev, m_max, d.d_model, d.d_ffn, hint, st,
+                       &pend);
         pr.end();
     }
     pr.begin(3);
-    hs_launch_rmsnorm(ctx, x, ctx->norm_f, xn, m_dev, st);
+    hs_launch_rmsnorm(ctx, x, ctx->norm_f, xn, m_dev, pend, st);
     pr.end();
     pr.begin(2);
     hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->lm_head, nullptr, logits, m_dev, m_max, d.vocab, d.d_model, hint, st);

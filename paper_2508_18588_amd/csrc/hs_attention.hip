@@ -109,6 +109,13 @@ __device__ inline int safe_page(const int32_t* bt, int p0, int total, int max_bl
     return __builtin_amdgcn_readfirstlane(page);
 }
 
+// Per-lane variant: the page of position p0 (which differs from lane to lane), same fall-backs.
+__device__ inline int safe_page_lane(const int32_t* bt, int p0, int total, int max_blocks, int n_blocks) {
+    int pidx = p0 >> 4;
+    int page = (p0 < total && pidx < max_blocks) ? bt[pidx] : bt[0];
+    return (page >= 0 && page < n_blocks) ? page : 0;
+}
+
 // Query fragments (B operand of S^T) and ancestor mask of the lane's row; rows beyond R read as zero.
 template <int HD>
 __device__ inline void load_query_tile(const bf16_t* q, const uint64_t* anc_mask, int r0, int rt, int R, int G,
@@ -209,10 +216,13 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
         // copied as NCP 16-byte chunks per lane (chunk c = lane + 64*ii covers elements [8c, 8c+8))
         constexpr int NCP = HD / 32;
         u32x4 rk[2 * NCP], rv[2 * NCP];
+        // the partition's page numbers, fetched once: lane l holds the page of positions k_begin + 16 l .. + 15
+        // (a partition has at most 64 pages), handed out by readlane -- no table look-up sits between two tiles
+        const int my_page = safe_page_lane(bt, k_begin + 16 * lane, total, max_blocks, n_blocks);
 #define HS_W_FETCH(KB)                                                                                            \
         {                                                                                                         \
             _Pragma("unroll") for (int pp = 0; pp < 2; pp++) {                                                    \
-                const size_t pofs = (size_t)safe_page(bt, (KB) + 16 * pp, total, max_blocks, n_blocks) * page_stride; \
+                const size_t pofs = (size_t)__builtin_amdgcn_readlane(my_page, (((KB) - k_begin) >> 4) + pp) * page_stride; \
                 const bf16_t* kp_ = kbase_ptr + pofs + lane * 8;                                                  \
                 const bf16_t* vp_ = vbase_ptr + pofs + lane * 8;                                                  \
                 _Pragma("unroll") for (int ii = 0; ii < NCP; ii++) {                                              \

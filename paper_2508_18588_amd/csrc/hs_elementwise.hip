@@ -26,15 +26,48 @@ __global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ e
     for (int i = threadIdx.x; i < d; i += 256) x[(size_t)row * d + i] = bf16_to_f32(e[i]);
 }
 
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ w,
+// One workgroup per row.  With chunks > 0 the row of the residual stream first receives the pending partial sums of
+// the preceding projection: t = p0 + p1 + ... in chunk order, x += t -- the arithmetic of the stand-alone ordered
+// reduce, so that the split execution gives the same bits whichever kernel finishes it.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ w,
                                                        bf16_t* __restrict__ out, const int32_t* __restrict__ m_dev,
-                                                       int d, float eps) {
+                                                       int d, float eps, const float* __restrict__ part, int chunks,
+                                                       size_t chunk_stride) {
     __shared__ float red[4];
     int row = blockIdx.x;
     if (row >= *m_dev) return;
-    const float* xr = x + (size_t)row * d;
+    float* xr = x + (size_t)row * d;
     float ss = 0.f;
-    for (int i = threadIdx.x; i < d; i += 256) { float v = xr[i]; ss += v * v; }
+    if (chunks > 0) {
+        // 16-byte loads, the chunk loop unrolled so that several partials of an element are in flight at once
+        // (one workgroup per row: the row count is small and the kernel lives on loads in flight)
+        const float* pr = part + (size_t)row * d;
+        for (int i = threadIdx.x * 4; i < d; i += 1024) {
+            float4 t = *reinterpret_cast<const float4*>(pr + i);
+#pragma unroll 8
+            for (int c = 1; c < chunks; c++) {
+                const float4 q = *reinterpret_cast<const float4*>(pr + c * chunk_stride + i);
+                t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+            }
+            float4 v = *reinterpret_cast<const float4*>(xr + i);
+            v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+            *reinterpret_cast<float4*>(xr + i) = v;
+            ss += v.x * v.x;
+            ss += v.y * v.y;
+            ss += v.z * v.z;
+            ss += v.w * v.w;
+        }
+    } else {
+        // same element-to-thread assignment and summation order as above: the norm must not depend on which
+        // execution the preceding projection used
+        for (int i = threadIdx.x * 4; i < d; i += 1024) {
+            const float4 v = *reinterpret_cast<const float4*>(xr + i);
+            ss += v.x * v.x;
+            ss += v.y * v.y;
+            ss += v.z * v.z;
+            ss += v.w * v.w;
+        }
+    }
     ss = block_sum_256(ss, red);
     float r = rsqrtf(ss / (float)d + eps);
     for (int i = threadIdx.x; i < d; i += 256) out[(size_t)row * d + i] = f32_to_bf16(xr[i] * r * w[i]);
@@ -49,7 +82,9 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float* __restrict__ 
                                                        const int32_t* __restrict__ block_table, int max_blocks,
                                                        int batch, bf16_t* __restrict__ q_out, bf16_t* __restrict__ kc,
                                                        bf16_t* __restrict__ vc, size_t layer_off, int hq, int hkv,
-                                                       int h, int max_pos, int n_blocks) {
+                                                       int h, int max_pos, int n_blocks,
+                                                       const float* __restrict__ part, int chunks,
+                                                       size_t chunk_stride) {
     int row = blockIdx.x;
     if (row >= row_off[batch]) return;
     int b = row2seq[row];
@@ -63,31 +98,49 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float* __restrict__ 
     int in_page = slot & 15;
     int half = h >> 1;
     const float* cs = rope_cs + (size_t)p * half * 2;
-    const float* src = qkv + (size_t)row * (hq + 2 * hkv) * h;
+    const int nqkv = (hq + 2 * hkv) * h;
+    // the row's QKV vector: the projection's output, or the chunk-ordered sum of its pending partials, which is
+    // first gathered into LDS with 16-byte loads (several partials of an element in flight at once)
+    extern __shared__ float row_buf[];
+    if (chunks > 0) {
+        const float* pr = part + (size_t)row * nqkv;
+        for (int i = threadIdx.x * 4; i < nqkv; i += 1024) {
+            float4 t = *reinterpret_cast<const float4*>(pr + i);
+#pragma unroll 8
+            for (int c = 1; c < chunks; c++) {
+                const float4 q4 = *reinterpret_cast<const float4*>(pr + c * chunk_stride + i);
+                t.x += q4.x; t.y += q4.y; t.z += q4.z; t.w += q4.w;
+            }
+            *reinterpret_cast<float4*>(row_buf + i) = t;
+        }
+        __syncthreads();
+    }
+    const float* src = qkv + (size_t)row * nqkv;
+    auto val = [&](int e) -> float { return chunks > 0 ? row_buf[e] : src[e]; };
     // q heads
     for (int i = threadIdx.x; i < hq * half; i += 256) {
         int head = i / half, j = i % half;
         float c = cs[2 * j], s = cs[2 * j + 1];
-        float a = src[head * h + j], bb = src[head * h + j + half];
+        float a = val(head * h + j), bb = val(head * h + j + half);
         bf16_t* dst = q_out + (size_t)row * hq * h + head * h;
         dst[j] = f32_to_bf16(a * c - bb * s);
         dst[j + half] = f32_to_bf16(bb * c + a * s);
     }
     // k heads -> cache [page][kv head][16][h]
-    const float* ksrc = src + (size_t)hq * h;
+    const int koff = hq * h;
     for (int i = threadIdx.x; i < hkv * half; i += 256) {
         int head = i / half, j = i % half;
         float c = cs[2 * j], s = cs[2 * j + 1];
-        float a = ksrc[head * h + j], bb = ksrc[head * h + j + half];
+        float a = val(koff + head * h + j), bb = val(koff + head * h + j + half);
         bf16_t* dst = kc + layer_off + (((size_t)page * hkv + head) * 16 + in_page) * h;
         dst[j] = f32_to_bf16(a * c - bb * s);
         dst[j + half] = f32_to_bf16(bb * c + a * s);
     }
     // v heads -> cache [page][kv head][h][16]
-    const float* vsrc = ksrc + (size_t)hkv * h;
+    const int voff = koff + hkv * h;
     for (int i = threadIdx.x; i < hkv * h; i += 256) {
         int head = i / h, j = i % h;
-        vc[layer_off + (((size_t)page * hkv + head) * h + j) * 16 + in_page] = f32_to_bf16(vsrc[head * h + j]);
+        vc[layer_off + (((size_t)page * hkv + head) * h + j) * 16 + in_page] = f32_to_bf16(val(voff + head * h + j));
     }
 }
 
@@ -133,20 +186,25 @@ void hs_launch_embed(const hs_ctx* ctx, const hs_step* step, int batch, float* x
                        step->row_off + batch, x, ctx->desc.d_model, ctx->desc.vocab);
 }
 
-void hs_launch_rmsnorm(const hs_ctx* ctx, const float* x, const float* w, bf16_t* out, const int32_t* m_dev,
-                       hipStream_t st) {
+void hs_launch_rmsnorm(const hs_ctx* ctx, float* x, const float* w, bf16_t* out, const int32_t* m_dev,
+                       int pending_chunks, hipStream_t st) {
+    const float* part = reinterpret_cast<const float*>(ctx->ws + ctx->lay.gemm_part);
     hipLaunchKernelGGL(rmsnorm_kernel, dim3(ctx->lim.max_rows), dim3(256), 0, st, x, w, out, m_dev,
-                       ctx->desc.d_model, ctx->desc.rms_eps);
+                       ctx->desc.d_model, ctx->desc.rms_eps, part, pending_chunks,
+                       (size_t)ctx->lim.max_rows * ctx->desc.d_model);
 }
 
 void hs_launch_rope_kv(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
-                       const hs_step* step, const float* qkv, bf16_t* q, hipStream_t st) {
+                       const hs_step* step, const float* qkv, bf16_t* q, int pending_chunks, hipStream_t st) {
     const hs_model_desc& d = ctx->desc;
     size_t layer_off = (size_t)layer * cache->n_blocks * d.n_kv_heads * 16 * d.head_dim;
-    hipLaunchKernelGGL(rope_kv_kernel, dim3(ctx->lim.max_rows), dim3(256), 0, st, qkv, ctx->rope_cs, step->pos,
+    const float* part = reinterpret_cast<const float*>(ctx->ws + ctx->lay.gemm_part);
+    const size_t nqkv = (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+    hipLaunchKernelGGL(rope_kv_kernel, dim3(ctx->lim.max_rows), dim3(256), pending_chunks > 0 ? nqkv * 4 : 0, st, qkv, ctx->rope_cs, step->pos,
                        step->row2seq, step->row_off, seq->seq_len, seq->block_table, ctx->lim.max_blocks_per_seq,
                        seq->batch, q, (bf16_t*)cache->k, (bf16_t*)cache->v, layer_off, d.n_q_heads, d.n_kv_heads,
-                       d.head_dim, ctx->lim.max_pos, cache->n_blocks);
+                       d.head_dim, ctx->lim.max_pos, cache->n_blocks, part, pending_chunks,
+                       (size_t)ctx->lim.max_rows * nqkv);
 }
 
 void hs_launch_argmax(const hs_ctx* ctx, const float* logits, int32_t* argmax, const int32_t* m_dev,

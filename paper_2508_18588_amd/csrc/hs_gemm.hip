@@ -347,7 +347,8 @@ void launch_tile(const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, fl
 
 template <int EPI>
 void launch(const hs_ctx* ctx, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, const int32_t* m_dev,
-            int m_max, int n, int k, int rows_hint, hipStream_t st) {
+            int m_max, int n, int k, int rows_hint, hipStream_t st, int* pending) {
+    if (pending) *pending = 0;
     if (ctx->flags & HS_FLAG_REFERENCE_KERNELS) {
         dim3 grid((n + 255) / 256, m_max);
         hipLaunchKernelGGL(gemm_bf16_plain<EPI>, grid, dim3(256), 0, st, a, w, w2, c, m_dev, n, k);
@@ -362,9 +363,13 @@ void launch(const hs_ctx* ctx, const bf16_t* a, const bf16_t* w, const bf16_t* w
         // few rows: the projection is a weight stream; one workgroup holds all rows against its weight slab
         hs_launch_gemm_stream(EPI, a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st);
         if (chunks > 1) {
-            const int rows = rows_hint < 1 ? 1 : (2 * rows_hint > m_max ? m_max : 2 * rows_hint);
-            hipLaunchKernelGGL((gemm_split_reduce<EPI>), dim3((n / 4 + 255) / 256, rows), dim3(256), 0, st, part,
-                               reinterpret_cast<float*>(c), m_dev, m_max, n, chunks);
+            if (pending) {
+                *pending = chunks;
+            } else {
+                const int rows = rows_hint < 1 ? 1 : (2 * rows_hint > m_max ? m_max : 2 * rows_hint);
+                hipLaunchKernelGGL((gemm_split_reduce<EPI>), dim3((n / 4 + 255) / 256, rows), dim3(256), 0, st, part,
+                                   reinterpret_cast<float*>(c), m_dev, m_max, n, chunks);
+            }
         }
         return;
     }
@@ -394,9 +399,13 @@ void launch(const hs_ctx* ctx, const bf16_t* a, const bf16_t* w, const bf16_t* w
             if (wide) launch_tile<EPI, MODE_SPLIT, 2, 4, 3>(HS_ARGS);
             else launch_tile<EPI, MODE_SPLIT, 2, 2, 3>(HS_ARGS);
         }
-        int rows = rows_hint < 1 ? 1 : (2 * rows_hint > m_max ? m_max : 2 * rows_hint);
-        hipLaunchKernelGGL((gemm_split_reduce<EPI>), dim3((n / 4 + 255) / 256, rows), dim3(256), 0, st, part,
-                           reinterpret_cast<float*>(c), m_dev, m_max, n, chunks);
+        if (pending) {
+            *pending = chunks;
+        } else {
+            int rows = rows_hint < 1 ? 1 : (2 * rows_hint > m_max ? m_max : 2 * rows_hint);
+            hipLaunchKernelGGL((gemm_split_reduce<EPI>), dim3((n / 4 + 255) / 256, rows), dim3(256), 0, st, part,
+                               reinterpret_cast<float*>(c), m_dev, m_max, n, chunks);
+        }
     }
 #undef HS_ARGS
 }
@@ -416,10 +425,16 @@ int hs_gemm_chunks(int n, int k) {
 }
 
 void hs_launch_gemm(const hs_ctx* ctx, int epi, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c,
-                    const int32_t* m_dev, int m_max, int n, int k, int rows_hint, hipStream_t st) {
+                    const int32_t* m_dev, int m_max, int n, int k, int rows_hint, hipStream_t st, int* pending) {
     switch (epi) {
-        case HS_EPI_STORE_F32: launch<HS_EPI_STORE_F32>(ctx, a, w, w2, c, m_dev, m_max, n, k, rows_hint, st); break;
-        case HS_EPI_ADD_F32: launch<HS_EPI_ADD_F32>(ctx, a, w, w2, c, m_dev, m_max, n, k, rows_hint, st); break;
-        default: launch<HS_EPI_SWIGLU_BF16>(ctx, a, w, w2, c, m_dev, m_max, n, k, rows_hint, st); break;
+        case HS_EPI_STORE_F32:
+            launch<HS_EPI_STORE_F32>(ctx, a, w, w2, c, m_dev, m_max, n, k, rows_hint, st, pending);
+            break;
+        case HS_EPI_ADD_F32:
+            launch<HS_EPI_ADD_F32>(ctx, a, w, w2, c, m_dev, m_max, n, k, rows_hint, st, pending);
+            break;
+        default:
+            launch<HS_EPI_SWIGLU_BF16>(ctx, a, w, w2, c, m_dev, m_max, n, k, rows_hint, st, pending);
+            break;
     }
 }

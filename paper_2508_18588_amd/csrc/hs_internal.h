@@ -65,15 +65,23 @@ static inline __host__ __device__ bf16_t f32_to_bf16(float f) {
 enum { HS_EPI_STORE_F32 = 0, HS_EPI_ADD_F32 = 1, HS_EPI_SWIGLU_BF16 = 2 };
 // rows_hint (host-side estimate of the live row count) selects the tile height and the split execution
 // (one workgroup per K chunk + an ordered reduce); results are identical whatever it is.
+// pending: if not null and the split execution was chosen, the ordered reduce is NOT launched: *pending receives the
+// number of chunk partials left in the workspace ([chunk][m_max][n] floats at lay.gemm_part) for the next kernel in
+// line to add up in chunk order and apply the epilogue (store / add to c); otherwise *pending = 0.
 void hs_launch_gemm(const hs_ctx* ctx, int epi, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c,
-                    const int32_t* m_dev, int m_max, int n, int k, int rows_hint, hipStream_t st);
+                    const int32_t* m_dev, int m_max, int n, int k, int rows_hint, hipStream_t st,
+                    int* pending = nullptr);
 int hs_gemm_chunks(int n, int k);
 
 void hs_launch_embed(const hs_ctx* ctx, const hs_step* step, int batch, float* x, hipStream_t st);
-void hs_launch_rmsnorm(const hs_ctx* ctx, const float* x, const float* w, bf16_t* out, const int32_t* m_dev,
-                       hipStream_t st);
+// RMSNorm of the residual stream; with pending_chunks > 0 it first adds the pending chunk partials of the
+// preceding projection (in chunk order) to x.
+void hs_launch_rmsnorm(const hs_ctx* ctx, float* x, const float* w, bf16_t* out, const int32_t* m_dev,
+                       int pending_chunks, hipStream_t st);
+// Rotary embedding + KV write; with pending_chunks > 0 the QKV values are the chunk-ordered sums of the pending
+// partials instead of qkv.
 void hs_launch_rope_kv(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
-                       const hs_step* step, const float* qkv, bf16_t* q, hipStream_t st);
+                       const hs_step* step, const float* qkv, bf16_t* q, int pending_chunks, hipStream_t st);
 void hs_launch_attention(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
                          const hs_step* step, const bf16_t* q, bf16_t* out, hipStream_t st);
 void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, bf16_t* out,
