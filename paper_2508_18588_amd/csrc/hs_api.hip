@@ -149,12 +149,23 @@ hs_status hs_create(const hs_model_desc* desc, const hs_weights* w, const hs_lim
         ctx->norm1.push_back(w->norm1[i]);
         ctx->norm2.push_back(w->norm2[i]);
     }
-    // Split-KV partition length: a tuning knob (multiple of 32 keys); results are identical across calls for a
-    // fixed value.
-    ctx->att_part = HS_ATT_PART_DEFAULT;
+    // Split-KV partition length (a multiple of 32 keys, at most 64 pages): a function of the context's limits only,
+    // so results are identical across calls.  The longest of 1024 / 512 / 256 keys that still cuts a full batch at
+    // maximum length into a few thousand partitions per layer: longer partitions mean fewer partial results for the
+    // merge kernel to re-read, shorter ones keep a small batch spread over the whole chip.
+    {
+        const long long keys = (long long)l.max_blocks_per_seq * 16;
+        ctx->att_part = 256;
+        for (int part : {1024, 512}) {
+            if ((long long)l.max_batch * d.n_kv_heads * ((keys + part - 1) / part) >= 4096) {
+                ctx->att_part = part;
+                break;
+            }
+        }
+    }
     if (const char* e = std::getenv("HS_ATT_PART")) {
         int v = std::atoi(e);
-        if (v >= 32 && v <= 1024 && v % 32 == 0) ctx->att_part = v;  // at most 64 pages per partition
+        if (v >= 32 && v <= 1024 && v % 32 == 0) ctx->att_part = v;
     }
     const long long max_keys = (long long)l.max_blocks_per_seq * 16;
     ctx->max_parts = (int)((max_keys + ctx->att_part - 1) / ctx->att_part);

@@ -1,4 +1,4 @@
-// Helpers shared by the two bf16 MFMA GEMM kernels (tile-grid kernel and weight-streaming kernel).
+// Helpers of the bf16 MFMA GEMM (launcher and kernel live in two translation units).
 #pragma once
 #include "hs_internal.h"
 
@@ -35,10 +35,8 @@ __device__ __forceinline__ void load_to_lds_16(const unsigned char* base, unsign
 
 }  // namespace hs_gemm_detail
 
-// Weight-streaming execution for few rows (defined in hs_gemm_stream.hip).  `chunks`/`tpc` are the K chunking of
+// The MFMA kernel (defined in hs_gemm_stream.hip).  `chunks`/`tpc` are the K chunking of
 // the shape (chunks > 1: chunk sums go to `part`, laid out [chunk][m_max][n], for the ordered reduce).
 void hs_launch_gemm_stream(int epi, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, float* part,
                            const int32_t* m_dev, int m_max, int n, int k, int chunks, int tpc, int rows_hint,
                            hipStream_t st);
-// Largest row hint the streaming execution is meant for.
-constexpr int HS_GEMM_STREAM_MAX_ROWS = 384;

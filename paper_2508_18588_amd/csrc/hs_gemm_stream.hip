@@ -285,7 +285,7 @@ template <int EPI, bool PARTIAL, int NU, int MT, int SA, int SW>
 __global__ __launch_bounds__(256) void hs_gemm_stream(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                       const bf16_t* __restrict__ W2, void* __restrict__ Cout,
                                                       float* __restrict__ part, const int32_t* __restrict__ m_dev,
-                                                      int m_max, int N, int K, int tpc) {
+                                                      int m_max, int N, int K, int tpc, int n_groups, int n_pass) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const unsigned smem_off = (unsigned)(size_t)(lds_ptr_t)smem;
     constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? 16 * NU : 32 * NU;
@@ -302,7 +302,19 @@ __global__ __launch_bounds__(256) void hs_gemm_stream(const bf16_t* __restrict__
     p.m_max = m_max;
     p.N = N;
     p.K = K;
-    p.n0 = blockIdx.x * NCOLS;
+    // Workgroup id -> (weight group, row pass): ids are dealt round-robin to the 8 XCDs (each with its own L2); an
+    // XCD takes a weight group and runs its row passes back to back, so that the passes which stream the same
+    // weight slab meet in one L2.
+    // (With a single pass the id is the group: no padding of the grid, a workgroup that only exits still has to
+    // wait for a compute unit with this kernel's LDS free.)
+    int group = blockIdx.x, pass = 0;
+    if (n_pass > 1) {
+        const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+        group = (local / n_pass) * 8 + xcd;
+        pass = local % n_pass;
+    }
+    if (group >= n_groups) return;
+    p.n0 = group * NCOLS;
     p.chunk = blockIdx.y;
     const int nk = K / BK;
     p.kt0 = blockIdx.y * tpc;
@@ -321,7 +333,7 @@ __global__ __launch_bounds__(256) void hs_gemm_stream(const bf16_t* __restrict__
         w_off[j] = (unsigned)min(gn, N - 1) * (unsigned)(K * 2) + ((lpos ^ swz(row)) << 4);
     }
 
-    for (p.m0 = 0; p.m0 < p.M; p.m0 += 128 * MT) {
+    for (p.m0 = pass * 128 * MT; p.m0 < p.M; p.m0 += n_pass * 128 * MT) {
         int nmi = 0;
 #pragma unroll
         for (int s = 0; s < MT; s++)
@@ -341,7 +353,7 @@ namespace {
 
 template <int EPI, bool PARTIAL, int NU, int MT, int SA, int SW>
 void launch_stream(const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, float* part, const int32_t* m_dev,
-                   int m_max, int n, int k, int chunks, int tpc, hipStream_t st) {
+                   int m_max, int n, int k, int chunks, int tpc, int rows_hint, hipStream_t st) {
     constexpr int NCOLS = (EPI == HS_EPI_SWIGLU_BF16) ? 16 * NU : 32 * NU;
     constexpr size_t lds = (size_t)(SA * 4 * MT + SW * NU) * TILE_BYTES;
     static_assert(lds <= 160 * 1024, "LDS of one compute unit");
@@ -352,9 +364,14 @@ void launch_stream(const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, 
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         configured = true;
     }
-    dim3 grid((n + NCOLS - 1) / NCOLS, chunks);
+    // row passes in the grid: what the hint calls for (rows beyond are reached by the pass loop of the kernel)
+    const int n_groups = (n + NCOLS - 1) / NCOLS;
+    int n_pass = (rows_hint + 128 * MT - 1) / (128 * MT);
+    if (n_pass < 1) n_pass = 1;
+    if (n_pass > (m_max + 128 * MT - 1) / (128 * MT)) n_pass = (m_max + 128 * MT - 1) / (128 * MT);
+    dim3 grid(n_pass > 1 ? ((n_groups + 7) / 8) * 8 * n_pass : n_groups, chunks);
     hipLaunchKernelGGL((hs_gemm_stream<EPI, PARTIAL, NU, MT, SA, SW>), grid, dim3(256), lds, st, a, w, w2, c, part,
-                       m_dev, m_max, n, k, tpc);
+                       m_dev, m_max, n, k, tpc, n_groups, n_pass);
 }
 
 // Units per workgroup: the candidate that needs the fewest unit-times to cover the output on 256 compute units.
@@ -377,7 +394,7 @@ void launch_stream_shape(const bf16_t* a, const bf16_t* w, const bf16_t* w2, voi
     // Rows per pass: 256 leaves LDS for deeper rings; 384 once the hint comes close to 256, so that a step a
     // little above its average does not pay a second pass over the weights.
     const bool tall = rows_hint > 224;
-#define HS_ARGS a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, st
+#define HS_ARGS a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st
     if (nu == 5) {
         if (tall) launch_stream<EPI, PARTIAL, 5, 3, 2, 3>(HS_ARGS);
         else launch_stream<EPI, PARTIAL, 5, 2, 2, 4>(HS_ARGS);

@@ -9,8 +9,9 @@
 
 typedef uint16_t bf16_t;  // storage type: upper half of an fp32
 
-// Keys per split-KV partition of the verify attention.  Partitions are keyed to absolute position, so a row's
-// reduction order does not depend on how many draft rows share its sequence.
+// Keys per split-KV partition of the verify attention when nothing else is known (hs_create picks 256, 512 or 1024
+// from the context's limits).  Partitions are keyed to absolute position, so a row's reduction order does not
+// depend on how many draft rows share its sequence.
 constexpr int HS_ATT_PART_DEFAULT = 512;
 // History segment scanned by one workgroup of the draft kernel.
 constexpr int HS_DRAFT_SEG = 4096;
