@@ -5,14 +5,18 @@
 
 namespace {
 
-__device__ inline float block_sum_256(float v, float* red) {
-    // fixed tree: xor-shuffle inside each wavefront, then the 4 wavefront sums in order
+constexpr int NORM_THREADS = 1024;  // one workgroup of 16 wavefronts per row: few rows, many loads in flight each
+
+__device__ inline float block_sum(float v, float* red) {
+    // fixed tree: xor-shuffle inside each wavefront, then the wavefront sums left to right
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
-    return (red[0] + red[1]) + (red[2] + red[3]);
+    float s = red[0];
+    for (int w = 1; w < NORM_THREADS / 64; w++) s += red[w];
+    return s;
 }
 
 __global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ embed, const int32_t* __restrict__ tok,
@@ -29,11 +33,11 @@ __global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ e
 // One workgroup per row.  With chunks > 0 the row of the residual stream first receives the pending partial sums of
 // the preceding projection: t = p0 + p1 + ... in chunk order, x += t -- the arithmetic of the stand-alone ordered
 // reduce, so that the split execution gives the same bits whichever kernel finishes it.
-__global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ w,
+__global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ w,
                                                        bf16_t* __restrict__ out, const int32_t* __restrict__ m_dev,
                                                        int d, float eps, const float* __restrict__ part, int chunks,
                                                        size_t chunk_stride) {
-    __shared__ float red[4];
+    __shared__ float red[NORM_THREADS / 64];
     int row = blockIdx.x;
     if (row >= *m_dev) return;
     float* xr = x + (size_t)row * d;
@@ -42,7 +46,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
         // 16-byte loads, the chunk loop unrolled so that several partials of an element are in flight at once
         // (one workgroup per row: the row count is small and the kernel lives on loads in flight)
         const float* pr = part + (size_t)row * d;
-        for (int i = threadIdx.x * 4; i < d; i += 1024) {
+        for (int i = threadIdx.x * 4; i < d; i += 4 * NORM_THREADS) {
             float4 t = *reinterpret_cast<const float4*>(pr + i);
 #pragma unroll 8
             for (int c = 1; c < chunks; c++) {
@@ -60,7 +64,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
     } else {
         // same element-to-thread assignment and summation order as above: the norm must not depend on which
         // execution the preceding projection used
-        for (int i = threadIdx.x * 4; i < d; i += 1024) {
+        for (int i = threadIdx.x * 4; i < d; i += 4 * NORM_THREADS) {
             const float4 v = *reinterpret_cast<const float4*>(xr + i);
             ss += v.x * v.x;
             ss += v.y * v.y;
@@ -68,14 +72,14 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
             ss += v.w * v.w;
         }
     }
-    ss = block_sum_256(ss, red);
+    ss = block_sum(ss, red);
     float r = rsqrtf(ss / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += 256) out[(size_t)row * d + i] = f32_to_bf16(xr[i] * r * w[i]);
+    for (int i = threadIdx.x; i < d; i += NORM_THREADS) out[(size_t)row * d + i] = f32_to_bf16(xr[i] * r * w[i]);
 }
 
 // One workgroup per row.  Rotates q and k heads at the row's position (pairs i, i + h/2), writes q as bf16,
 // K into its page row-major and V into its page with the token index fastest.
-__global__ __launch_bounds__(256) void rope_kv_kernel(const float* __restrict__ qkv, const float* __restrict__ rope_cs,
+__global__ __launch_bounds__(NORM_THREADS) void rope_kv_kernel(const float* __restrict__ qkv, const float* __restrict__ rope_cs,
                                                        const int32_t* __restrict__ pos, const int32_t* __restrict__ row2seq,
                                                        const int32_t* __restrict__ row_off,
                                                        const int32_t* __restrict__ seq_len,
@@ -104,7 +108,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float* __restrict__ 
     extern __shared__ float row_buf[];
     if (chunks > 0) {
         const float* pr = part + (size_t)row * nqkv;
-        for (int i = threadIdx.x * 4; i < nqkv; i += 1024) {
+        for (int i = threadIdx.x * 4; i < nqkv; i += 4 * NORM_THREADS) {
             float4 t = *reinterpret_cast<const float4*>(pr + i);
 #pragma unroll 8
             for (int c = 1; c < chunks; c++) {
@@ -118,7 +122,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float* __restrict__ 
     const float* src = qkv + (size_t)row * nqkv;
     auto val = [&](int e) -> float { return chunks > 0 ? row_buf[e] : src[e]; };
     // q heads
-    for (int i = threadIdx.x; i < hq * half; i += 256) {
+    for (int i = threadIdx.x; i < hq * half; i += NORM_THREADS) {
         int head = i / half, j = i % half;
         float c = cs[2 * j], s = cs[2 * j + 1];
         float a = val(head * h + j), bb = val(head * h + j + half);
@@ -128,7 +132,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float* __restrict__ 
     }
     // k heads -> cache [page][kv head][16][h]
     const int koff = hq * h;
-    for (int i = threadIdx.x; i < hkv * half; i += 256) {
+    for (int i = threadIdx.x; i < hkv * half; i += NORM_THREADS) {
         int head = i / half, j = i % half;
         float c = cs[2 * j], s = cs[2 * j + 1];
         float a = val(koff + head * h + j), bb = val(koff + head * h + j + half);
@@ -138,7 +142,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float* __restrict__ 
     }
     // v heads -> cache [page][kv head][h][16]
     const int voff = koff + hkv * h;
-    for (int i = threadIdx.x; i < hkv * h; i += 256) {
+    for (int i = threadIdx.x; i < hkv * h; i += NORM_THREADS) {
         int head = i / h, j = i % h;
         vc[layer_off + (((size_t)page * hkv + head) * h + j) * 16 + in_page] = f32_to_bf16(val(voff + head * h + j));
     }
@@ -189,7 +193,7 @@ void hs_launch_embed(const hs_ctx* ctx, const hs_step* step, int batch, float* x
 void hs_launch_rmsnorm(const hs_ctx* ctx, float* x, const float* w, bf16_t* out, const int32_t* m_dev,
                        int pending_chunks, hipStream_t st) {
     const float* part = reinterpret_cast<const float*>(ctx->ws + ctx->lay.gemm_part);
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(ctx->lim.max_rows), dim3(256), 0, st, x, w, out, m_dev,
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), 0, st, x, w, out, m_dev,
                        ctx->desc.d_model, ctx->desc.rms_eps, part, pending_chunks,
                        (size_t)ctx->lim.max_rows * ctx->desc.d_model);
 }
@@ -200,7 +204,7 @@ void hs_launch_rope_kv(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, c
     size_t layer_off = (size_t)layer * cache->n_blocks * d.n_kv_heads * 16 * d.head_dim;
     const float* part = reinterpret_cast<const float*>(ctx->ws + ctx->lay.gemm_part);
     const size_t nqkv = (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
-    hipLaunchKernelGGL(rope_kv_kernel, dim3(ctx->lim.max_rows), dim3(256), pending_chunks > 0 ? nqkv * 4 : 0, st, qkv, ctx->rope_cs, step->pos,
+    hipLaunchKernelGGL(rope_kv_kernel, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), pending_chunks > 0 ? nqkv * 4 : 0, st, qkv, ctx->rope_cs, step->pos,
                        step->row2seq, step->row_off, seq->seq_len, seq->block_table, ctx->lim.max_blocks_per_seq,
                        seq->batch, q, (bf16_t*)cache->k, (bf16_t*)cache->v, layer_off, d.n_q_heads, d.n_kv_heads,
                        d.head_dim, ctx->lim.max_pos, cache->n_blocks, part, pending_chunks,
