@@ -22,7 +22,7 @@ sys.path.insert(0, ROOT)
 # HBM bytes per launch of the attention kernel at config 3, from the two rocprofv3 --pmc runs (FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0, factors read off 1 GiB copies in the same runs) summarised under profiles/: counters cannot be
 # read inside a timed run, so the figure is carried here and re-measured whenever the kernel changes.
-ATTN_TRAFFIC_BYTES_PER_LAUNCH = 2.346e9
+ATTN_TRAFFIC_BYTES_PER_LAUNCH = 2.330e9
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
@@ -227,6 +227,12 @@ def main():
                                     "gemm_weight_stream_gbs": round(layer_w_bytes / (gemm_ms * 1e-3) / 1e9, 1),
                                     "lm_head_tflops": round(lm_flops / (lm_ms * 1e-3) / 1e12, 1)}}
 
+    # ---- the projections at the configuration's maximum row count (every sequence drafting k_max tokens): the regime
+    # in which they are bound by the matrix cores rather than by streaming weights.  One layer's four projections and
+    # the LM head, each launched alone through hs_debug_gemm on random activations, timed with events on the stream.
+    if prof is not None and n_layers == shape.n_layers:
+        extras["gemm_at_max_rows"] = gemm_probe(eng, shape, B * (wp["k_max"] + 1))
+
     # ---- CPU oracle on a bounded sample: one sequence, its first speculative step at full model size
     cpu = None
     if not args.no_cpu_baseline:
@@ -261,6 +267,50 @@ def main():
             f"({3 * 2 * 2 ** 30 / (time.perf_counter() - t3) / 1e9:.0f} GB/s read+write)")
     eng.close()
     print(json.dumps(result), flush=True)
+
+
+def gemm_probe(eng, shape, rows):
+    import torch
+    dev = eng.dev
+    g = torch.Generator(device=dev).manual_seed(7)
+    d, F, V = shape.d_model, shape.d_ffn, shape.vocab
+    qh = shape.n_q_heads * shape.head_dim
+    rows = min(rows, eng.max_rows)
+    m_dev = torch.full((1,), rows, dtype=torch.int32, device=dev)
+    a_d = torch.randn(eng.max_rows, d, device=dev, generator=g).to(torch.bfloat16).view(torch.int16)
+    a_f = torch.randn(eng.max_rows, F, device=dev, generator=g).to(torch.bfloat16).view(torch.int16)
+    a_q = a_d[:, :qh].contiguous()
+    W = eng.w
+    cases = [("qkv", 0, a_d, W["wqkv"][0], None), ("o", 1, a_q, W["wo"][0], None),
+             ("gate_up", 2, a_d, W["wgate"][0], W["wup"][0]), ("down", 1, a_f, W["wdown"][0], None),
+             ("lm_head", 0, a_d, W["lm_head"], None)]
+    out = {"rows": rows}
+    layer_flops = layer_ms = 0.0
+    for name, epi, a, w, w2 in cases:
+        n, k = int(w.shape[0]), int(w.shape[1])
+        c = torch.zeros(eng.max_rows, n, dtype=torch.int16 if epi == 2 else torch.float32, device=dev)
+        for _ in range(2):
+            eng.gemm(epi, a, w, w2, c, m_dev, eng.max_rows, rows)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 5
+        e0.record()
+        for _ in range(reps):
+            eng.gemm(epi, a, w, w2, c, m_dev, eng.max_rows, rows)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        flops = 2.0 * rows * n * k * (2 if w2 is not None else 1)
+        out[name + "_tflops"] = round(flops / (ms * 1e-3) / 1e12, 1)
+        if name != "lm_head":
+            layer_flops += flops
+            layer_ms += ms
+        del c
+    out["layer_tflops"] = round(layer_flops / (layer_ms * 1e-3) / 1e12, 1)
+    out["layer_frac_of_bf16_mfma_peak"] = round(out["layer_tflops"] / MFMA_BF16_PEAK_TFLOPS, 4)
+    out["lm_head_frac_of_bf16_mfma_peak"] = round(out["lm_head_tflops"] / MFMA_BF16_PEAK_TFLOPS, 4)
+    out["note"] = ("each projection launched alone (split-K ones include their ordered reduce), activations random; "
+                   "the timed steps above run at rows_per_step, where the projections stream weights")
+    return out
 
 
 def cpu_baseline(eng, shape, w, rope, toks, hists, pol, first, B, n_layers, weights_to_host):

@@ -391,9 +391,10 @@ void launch_stream_shape(const bf16_t* a, const bf16_t* w, const bf16_t* w2, voi
                          hipStream_t st) {
     const int unit_cols = (EPI == HS_EPI_SWIGLU_BF16) ? 16 : 32;
     const int nu = choose_units((n + unit_cols - 1) / unit_cols, chunks);
-    // Rows per pass: 256 leaves LDS for deeper rings; 384 once the hint comes close to 256, so that a step a
-    // little above its average does not pay a second pass over the weights.
-    const bool tall = rows_hint > 224;
+    // Rows per pass: 256 leaves LDS for a deeper weight ring; 384 once the hint is within a factor 1.6 of 256 (the
+    // row count of a speculative step swings by a third around its mean), so that a step above its average does
+    // not pay a second pass over the weights.  Row tiles that do not exist cost nothing in either shape.
+    const bool tall = rows_hint > 160;
 #define HS_ARGS a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st
     if (nu == 5) {
         if (tall) launch_stream<EPI, PARTIAL, 5, 3, 2, 3>(HS_ARGS);
