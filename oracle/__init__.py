@@ -52,6 +52,8 @@ def lib():
         L.orc_suffix_match.argtypes = [i32p, C.c_int, i32p, C.c_int, C.c_int, C.c_int, intp, intp]
         L.orc_suffix_match_backoff.argtypes = L.orc_suffix_match.argtypes
         L.orc_trace_sim.argtypes = [i32p, C.c_int, i32p, C.c_int, C.c_int]
+        L.orc_reward_draft.argtypes = [C.c_int, i32p, i32p, i32p, i32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                       i32p, intp, intp, intp, intp]
         L.orc_k_policy.argtypes = [C.c_int] * 5
         L.orc_draft_len.argtypes = [C.c_int] * 4
         L.orc_aimd.argtypes = [C.c_int] * 6
@@ -103,6 +105,23 @@ def suffix_match(hist, x, w: int, m_min: int, backoff: bool = False):
     fn = lib().orc_suffix_match_backoff if backoff else lib().orc_suffix_match
     fn(hp, len(h), xp, len(xx), w, m_min, C.byref(p), C.byref(m))
     return p.value, m.value
+
+
+def reward_draft(hists, rewards, x, w: int, m_min: int, k: int, occ_max: int = 1024):
+    """Reward-priority draft over all responses of one prompt.  Returns dict(tok, m, n_occ, g, p)."""
+    arrs = [np.ascontiguousarray(h, dtype=np.int32) for h in hists]
+    off = np.zeros(len(arrs) + 1, np.int32)
+    off[1:] = np.cumsum([len(a) for a in arrs])
+    flat, fp = _i32(np.concatenate(arrs) if off[-1] else np.zeros(1, np.int32))
+    o, o_p = _i32(off)
+    r, rp = _i32(rewards)
+    xx, xp = _i32(x)
+    out = np.zeros(max(k, 1), np.int32)
+    m, no, g, p = C.c_int(), C.c_int(), C.c_int(), C.c_int()
+    n = lib().orc_reward_draft(len(arrs), fp, o_p, rp, xp, len(xx), w, m_min, k, occ_max,
+                               out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(m), C.byref(no), C.byref(g),
+                               C.byref(p))
+    return dict(tok=out[:n].copy(), m=m.value, n_occ=no.value, g=g.value, p=p.value)
 
 
 def trace_sim(cur, hist, key: int = 3) -> int:

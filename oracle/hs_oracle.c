@@ -18,6 +18,10 @@
  *                          historical response, following tokens are the
  *                          draft) and Sec. 5.4 (pattern length 7 shrinking
  *                          to 3 when nothing matches).
+ *   orc_reward_draft       Sec. 5.3: all responses of the prompt's last rollout
+ *                          are indexed together; where the continuations of
+ *                          the matched pattern branch, the branch with the
+ *                          largest sum of rewards is followed.
  *   orc_trace_sim          Sec. 5.1 token-similarity study (3-token key).
  *   orc_k_policy, orc_aimd Sec. 5.4 (window starts at 2, +2 when every draft
  *                          token is accepted, cap 32, back to 2 on a reject).
@@ -84,6 +88,98 @@ int orc_suffix_match_backoff(const int32_t* hist, int lh, const int32_t* x, int 
     *p_out = -1;
     *m_out = 0;
     return 0;
+}
+
+/*
+ * Reward-aware draft from ALL responses of the prompt's last rollout (Sec. 5.3).
+ * The paper indexes the responses in one suffix tree per prompt: a node stands
+ * for a token sequence, the leaves below it are the places where that sequence
+ * occurs, a leaf's priority is the reward of the response it lies in, a node's
+ * priority the sum over its leaves; where the continuations of the matched
+ * pattern differ, the child with the highest priority is followed.  Written out
+ * on the flat responses, without a tree:
+ *
+ *   1. m* = the longest common suffix (capped at w, at least m_min) between x
+ *      and any place in any response that still has a token after it: end
+ *      positions p in [1, len_g - 1] of response g.
+ *   2. The occurrences are all (g, p) whose common suffix reaches m*, taken in
+ *      the order of g, then p; at most occ_max of them are kept (a limit of the
+ *      implementation, part of the definition so that both sides agree).
+ *   3. Draft token j = 1, 2, ...: every live occurrence that has a token at
+ *      p + j - 1 votes for that token with its response's reward.  The token
+ *      with the largest reward sum is taken; equal sums: the one with more
+ *      votes; still equal: the smaller token id.  Occurrences that voted
+ *      otherwise, or ran out of tokens, drop out.  The walk ends after k tokens
+ *      or when no live occurrence has a token left.
+ *
+ * hist = the G responses back to back, off[g] .. off[g+1] the extent of response
+ * g; reward[g] >= 0.  Writes the draft tokens to out_tok (room for k), *m_out =
+ * m* (0 if nothing matches), *n_occ = occurrences kept, *g_out / *p_out = the
+ * first occurrence (in the order above) that is still live at the end: the
+ * draft equals the tokens after it.  Returns the draft length.
+ */
+int orc_reward_draft(int G, const int32_t* hist, const int32_t* off, const int32_t* reward, const int32_t* x, int n,
+                     int w, int m_min, int k, int occ_max, int32_t* out_tok, int* m_out, int* n_occ, int* g_out,
+                     int* p_out) {
+    *m_out = 0; *n_occ = 0; *g_out = -1; *p_out = -1;
+    int m_star = 0;
+    for (int g = 0; g < G; g++) {
+        const int32_t* h = hist + off[g];
+        int lh = off[g + 1] - off[g];
+        for (int p = 1; p <= lh - 1; p++) {
+            int m = common_suffix(h, p, x, n, w);
+            if (m >= m_min && m > m_star) m_star = m;
+        }
+    }
+    if (m_star == 0 || occ_max < 1) return 0;
+    int* og = (int*)malloc(sizeof(int) * (size_t)occ_max);
+    int* op = (int*)malloc(sizeof(int) * (size_t)occ_max);
+    char* live = (char*)malloc((size_t)occ_max);
+    int no = 0;
+    for (int g = 0; g < G && no < occ_max; g++) {
+        const int32_t* h = hist + off[g];
+        int lh = off[g + 1] - off[g];
+        for (int p = 1; p <= lh - 1 && no < occ_max; p++)
+            if (common_suffix(h, p, x, n, w) >= m_star) { og[no] = g; op[no] = p; live[no] = 1; no++; }
+    }
+    int len = 0;
+    for (int j = 0; j < k; j++) {
+        /* the vote: for each candidate token (taken from the live occurrences), its reward sum and vote count */
+        int have = 0, best_tok = 0, best_votes = 0;
+        long long best_sum = 0;
+        for (int i = 0; i < no; i++) {
+            if (!live[i]) continue;
+            int lh = off[og[i] + 1] - off[og[i]];
+            if (op[i] + j >= lh) continue;
+            int t = hist[off[og[i]] + op[i] + j];
+            long long sum = 0;
+            int votes = 0;
+            for (int q = 0; q < no; q++) {
+                if (!live[q]) continue;
+                int lq = off[og[q] + 1] - off[og[q]];
+                if (op[q] + j >= lq) continue;
+                if (hist[off[og[q]] + op[q] + j] == t) { sum += reward[og[q]]; votes++; }
+            }
+            if (!have || sum > best_sum || (sum == best_sum && votes > best_votes) ||
+                (sum == best_sum && votes == best_votes && t < best_tok)) {
+                have = 1; best_tok = t; best_sum = sum; best_votes = votes;
+            }
+        }
+        if (!have) break;
+        for (int i = 0; i < no; i++) {
+            if (!live[i]) continue;
+            int lh = off[og[i] + 1] - off[og[i]];
+            if (op[i] + j >= lh || hist[off[og[i]] + op[i] + j] != best_tok) live[i] = 0;
+        }
+        out_tok[len++] = best_tok;
+    }
+    *m_out = m_star;
+    *n_occ = no;
+    for (int i = 0; i < no; i++)
+        if (live[i]) { *g_out = og[i]; *p_out = op[i]; break; }
+    if (len == 0 && no > 0) { *g_out = og[0]; *p_out = op[0]; }
+    free(og); free(op); free(live);
+    return len;
 }
 
 /*
