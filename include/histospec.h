@@ -94,6 +94,7 @@ typedef struct hs_limits {
     int32_t max_pos;            /* rows of rope_cs; no position may reach it.  A history candidate is scanned
                                    up to max_pos + 32 tokens */
     int32_t w_max;              /* row length of the pattern tail, 1..32 */
+    int32_t g_max;              /* responses per sequence hs_draft_group may be given, 0 (entry point unused)..32 */
 } hs_limits;
 
 /* Paged KV cache (DEVICE, bf16, zero-initialised by the caller).
@@ -141,6 +142,17 @@ typedef struct hs_draft_args {
     hs_policy policy;
 } hs_draft_args;
 
+/* Arguments of hs_draft_group: the n_resp responses the prompt of sequence b got in its last rollout are
+ * hist[hist_off[b*n_resp + g] .. hist_off[b*n_resp + g + 1]), g = 0..n_resp-1 (each carrying the last window-1 prompt
+ * tokens in front, as for hs_draft), reward[b*n_resp + g] in 0..2^20 the reward that response earned. */
+typedef struct hs_group_draft_args {
+    int32_t n_resp;           /* 1..g_max */
+    const int32_t* hist;      /* DEVICE */
+    const int32_t* hist_off;  /* DEVICE [batch*n_resp + 1] */
+    const int32_t* reward;    /* DEVICE [batch*n_resp] */
+    hs_policy policy;
+} hs_group_draft_args;
+
 /* One iteration's arrays (DEVICE, caller-owned).  Sizes: per-candidate arrays batch*c_max, per-row arrays
  * max_rows, per-sequence arrays max_batch. */
 typedef struct hs_step {
@@ -161,6 +173,9 @@ typedef struct hs_step {
     int32_t* path_row;     /* [batch][k_max+1] node index of the root and of each accepted node */
     int32_t rows_hint;     /* HOST: rows M the caller expects this step (e.g. last step's row_off[batch]), 0 =
                               unknown.  Only steers how kernels are launched; results do not depend on it. */
+    int32_t* draft_src;    /* [batch] hs_draft_group only (may be NULL otherwise): the response the draft was read
+                              from, -1 = no match.  hs_draft_group uses entry b (not b*n_cand) of draft_start,
+                              match_len and draft_len. */
 } hs_step;
 
 typedef struct hs_accept_args {
@@ -186,6 +201,21 @@ hs_status hs_bind_workspace(hs_ctx* ctx, void* dev_ptr, size_t bytes);
  * at least m_min; leftmost on ties).  Writes draft_start/match_len/draft_len, builds the node arrays and
  * row_off.  Reads seq.tail/tail_len/seq_len/k_state/budget_left. */
 hs_status hs_draft(hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step, hs_stream stream);
+
+/* Reward-aware draft from ALL responses of the prompt's last rollout (Sec. 5.3: the responses are indexed together,
+ * every branch carries the summed rewards of the responses below it, and where the continuations of the matched
+ * pattern differ the branch with the highest priority is followed).  Stated on the flat responses:
+ *   1. m* = longest common suffix (capped at `window`, at least m_min) between the committed tokens and any place
+ *      p in [1, len-1] of any response;
+ *   2. the occurrences of that pattern, in (response, position) order, at most 1024 of them;
+ *   3. draft token by draft token, every live occurrence votes for its next token with its response's reward; the
+ *      largest reward sum wins, then the larger number of votes, then the smaller token id; occurrences that voted
+ *      otherwise or ran out of text drop out; the walk ends after the policy's K tokens (cut by k_max and the
+ *      response budget - 1) or when no live occurrence has a token left.
+ * The result is a chain: draft_src[b] / draft_start[b] name the first surviving occurrence (the draft is the text
+ * after it), match_len[b] = m*, draft_len[b] the tokens drafted; node arrays and row_off as for hs_draft. */
+hs_status hs_draft_group(hs_ctx* ctx, const hs_group_draft_args* args, const hs_seq_state* seq, hs_step* step,
+                         hs_stream stream);
 
 /* One target-model forward pass over all M rows (Sec. 2.2).  Writes every row's K/V into the cache at slot
  * L_b + node index, attends over positions [0, L_b) plus the node's ancestors-or-self, and writes

@@ -71,7 +71,7 @@ class hs_weights(C.Structure):
 
 class hs_limits(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("max_batch", "k_max", "c_max", "max_rows", "max_blocks_per_seq", "max_pos",
-                                         "w_max")]
+                                         "w_max", "g_max")]
 
 
 class hs_kv_cache(C.Structure):
@@ -94,10 +94,15 @@ class hs_draft_args(C.Structure):
     _fields_ = [("n_cand", C.c_int32), ("hist", C.c_void_p), ("hist_off", C.c_void_p), ("policy", hs_policy)]
 
 
+class hs_group_draft_args(C.Structure):
+    _fields_ = [("n_resp", C.c_int32), ("hist", C.c_void_p), ("hist_off", C.c_void_p), ("reward", C.c_void_p),
+                ("policy", hs_policy)]
+
+
 class hs_step(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("draft_start", "match_len", "draft_len", "row_off", "tok", "pos", "parent",
                                           "anc_mask", "row2seq", "logits", "argmax", "accept_len", "n_out",
-                                          "out_tok", "path_row")] + [("rows_hint", C.c_int32)]
+                                          "out_tok", "path_row")] + [("rows_hint", C.c_int32), ("draft_src", C.c_void_p)]
 
 
 class hs_accept_args(C.Structure):
@@ -105,7 +110,7 @@ class hs_accept_args(C.Structure):
 
 
 EXPORTS = ("hs_create", "hs_destroy", "hs_last_error", "hs_set_flags", "hs_workspace_bytes", "hs_bind_workspace",
-           "hs_draft", "hs_verify", "hs_accept", "hs_kv_commit", "hs_poll_error", "hs_debug_buffer",
+           "hs_draft", "hs_draft_group", "hs_verify", "hs_accept", "hs_kv_commit", "hs_poll_error", "hs_debug_buffer",
            "hs_set_profile", "hs_get_profile", "hs_debug_gemm")
 
 _lib = None
@@ -133,6 +138,8 @@ def lib():
         L.hs_workspace_bytes.restype = C.c_size_t
         L.hs_bind_workspace.argtypes = [vp, vp, C.c_size_t]
         L.hs_draft.argtypes = [vp, C.POINTER(hs_draft_args), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
+        L.hs_draft_group.argtypes = [vp, C.POINTER(hs_group_draft_args), C.POINTER(hs_seq_state), C.POINTER(hs_step),
+                                     vp]
         L.hs_verify.argtypes = [vp, C.POINTER(hs_kv_cache), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
         L.hs_accept.argtypes = [vp, C.POINTER(hs_accept_args), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
         L.hs_kv_commit.argtypes = [vp, C.POINTER(hs_kv_cache), C.POINTER(hs_seq_state), C.POINTER(hs_step),
@@ -186,6 +193,10 @@ def hs_bind_workspace(ctx, dev_ptr: int, nbytes: int):
 
 def hs_draft(ctx, args: hs_draft_args, seq: hs_seq_state, step: hs_step, stream=None):
     _check(ctx, lib().hs_draft(ctx, C.byref(args), C.byref(seq), C.byref(step), stream))
+
+
+def hs_draft_group(ctx, args: hs_group_draft_args, seq: hs_seq_state, step: hs_step, stream=None):
+    _check(ctx, lib().hs_draft_group(ctx, C.byref(args), C.byref(seq), C.byref(step), stream))
 
 
 def hs_verify(ctx, cache: hs_kv_cache, seq: hs_seq_state, step: hs_step, stream=None):

@@ -39,7 +39,7 @@ void layout_workspace(hs_ctx* ctx) {
     w.part_o = take(M * d.n_q_heads * (size_t)ctx->max_parts * d.head_dim * 4);
     w.part_ml = take(M * d.n_q_heads * (size_t)ctx->max_parts * 2 * 4);
     w.logits = take(M * (size_t)d.vocab * 4);
-    w.draft_best = take((size_t)l.max_batch * l.c_max * ctx->max_segs * 8);
+    w.draft_best = take((size_t)l.max_batch * std::max(l.c_max, l.g_max) * ctx->max_segs * 8);
     size_t part_cols = std::max({(size_t)hs_gemm_chunks((int)nqkv, d.d_model) * nqkv,
                                  (size_t)hs_gemm_chunks(d.d_model, (int)qh) * d.d_model,
                                  (size_t)hs_gemm_chunks(d.d_model, d.d_ffn) * d.d_model});
@@ -111,7 +111,7 @@ hs_status hs_create(const hs_model_desc* desc, const hs_weights* w, const hs_lim
         return HS_ERR_UNSUPPORTED;
     const hs_limits& l = *lim;
     if (l.max_batch < 1 || l.k_max < 0 || l.k_max > 32 || l.c_max < 1 || l.c_max > 2 || l.max_blocks_per_seq < 1 ||
-        l.max_pos < 1 || l.w_max < 1 || l.w_max > 32 || l.max_rows < 1)
+        l.max_pos < 1 || l.w_max < 1 || l.w_max > 32 || l.max_rows < 1 || l.g_max < 0 || l.g_max > 32)
         return HS_ERR_INVALID_ARG;
     const int nodes = 1 + l.c_max * l.k_max;
     if (nodes > HS_MAX_NODES || (d.n_q_heads / d.n_kv_heads) * nodes > 256) return HS_ERR_UNSUPPORTED;
@@ -212,6 +212,22 @@ hs_status hs_draft(hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* s
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated runtime calls
     hs_launch_draft(ctx, args, seq, step, (hipStream_t)stream);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_draft", e);
+    return HS_OK;
+}
+
+hs_status hs_draft_group(hs_ctx* ctx, const hs_group_draft_args* args, const hs_seq_state* seq, hs_step* step,
+                         hs_stream stream) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
+    if (!args || !args->hist || !args->hist_off || !args->reward)
+        return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_group: null history or rewards");
+    if (args->n_resp < 1 || args->n_resp > ctx->lim.g_max) return fail(ctx, HS_ERR_CAPACITY, "hs_draft_group: n_resp");
+    if (!policy_ok(ctx, &args->policy)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_group: policy out of range");
+    if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_group: sequence state");
+    if (!step_ok(step) || !step->draft_src) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_group: step arrays");
+    (void)hipGetLastError();
+    hs_launch_draft_group(ctx, args, seq, step, (hipStream_t)stream);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_draft_group", e);
     return HS_OK;
 }
 

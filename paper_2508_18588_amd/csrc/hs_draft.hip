@@ -98,7 +98,9 @@ __global__ __launch_bounds__(256) void draft_build_kernel(
     int32_t* __restrict__ draft_start, int32_t* __restrict__ match_len, int32_t* __restrict__ draft_len,
     int32_t* __restrict__ row_off, int32_t* __restrict__ tok, int32_t* __restrict__ pos,
     int32_t* __restrict__ parent, uint64_t* __restrict__ anc_mask, int32_t* __restrict__ row2seq,
-    uint32_t* __restrict__ err) {
+    uint32_t* __restrict__ err, int group_n, const int32_t* __restrict__ draft_src) {
+    // group_n > 0: the draft of sequence b was chosen by the group walk (response draft_src[b] of its group_n
+    // responses, start draft_start[b], length draft_len[b]); this kernel then only lays out the rows (n_cand == 1)
     __shared__ int sw[4];
     __shared__ int carry_s;
     if (threadIdx.x == 0) carry_s = 0;
@@ -110,7 +112,13 @@ __global__ __launch_bounds__(256) void draft_build_kernel(
         int shared = 0;
         if (b < batch && budget_left[b] > 0) {
             L = seq_len[b] - 1;
-            for (int c = 0; c < n_cand; c++) {
+            if (group_n > 0) {
+                const int g = draft_src[b];
+                pstart[0] = draft_start[b];
+                klen[0] = g >= 0 ? draft_len[b] : 0;
+                hoff[0] = g >= 0 ? hist_off[b * group_n + g] + pstart[0] : 0;
+            }
+            for (int c = 0; c < n_cand && group_n == 0; c++) {
                 const int bc = b * n_cand + c;
                 const int off = hist_off[bc], lh = hist_off[bc + 1] - off;
                 unsigned long long k = 0ull;
@@ -195,6 +203,163 @@ __global__ __launch_bounds__(256) void draft_build_kernel(
     if (threadIdx.x == 0) row_off[batch] = min(carry_s, max_rows);
 }
 
+
+// ---- reward-aware draft over all responses of the prompt's last rollout (Sec. 5.3) ----
+//
+// The paper keeps one suffix tree per prompt over the responses of its last rollout, with a priority on every node
+// (the summed rewards of the responses whose text runs through it), and follows the highest-priority child where
+// the continuations of the matched pattern branch.  On the GPU the tree is never built: the scan kernel above finds
+// the longest match in every response segment; this kernel, one workgroup per sequence, collects the occurrences of
+// that longest pattern in (response, position) order and lets them vote, draft token by draft token, for their
+// next token with their response's reward (ties: more votes, then the smaller token id).  Occurrences that voted
+// for another token, or ran out of text, drop out.  The draft is the text after the first surviving occurrence.
+constexpr int HS_OCC_MAX = 1024;  // occurrences kept per sequence (in order); part of the rule, see the header
+
+__device__ inline unsigned long long block_max_u64(unsigned long long v, unsigned long long* red) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        unsigned long long other = shfl_xor_u64(v, o);
+        if (other > v) v = other;
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    unsigned long long r = red[0];
+    for (int w = 1; w < 4; w++) if (red[w] > r) r = red[w];
+    return r;
+}
+
+__global__ __launch_bounds__(256) void draft_group_walk_kernel(
+    const int32_t* __restrict__ hist, const int32_t* __restrict__ hist_off, const int32_t* __restrict__ reward,
+    int n_resp, const unsigned long long* __restrict__ best, int max_segs, const int32_t* __restrict__ tail,
+    const int32_t* __restrict__ tail_len, int w_max, const int32_t* __restrict__ k_state,
+    const int32_t* __restrict__ budget_left, hs_policy pol, int32_t* __restrict__ draft_start,
+    int32_t* __restrict__ match_len, int32_t* __restrict__ draft_len, int32_t* __restrict__ draft_src) {
+    __shared__ int32_t pat[32];
+    __shared__ int32_t occ_off[HS_OCC_MAX];   // offset in `hist` of the token that follows the occurrence
+    __shared__ int32_t occ_end[HS_OCC_MAX];   // end offset of its response
+    __shared__ int32_t occ_rew[HS_OCC_MAX];
+    __shared__ int32_t occ_tok[HS_OCC_MAX];   // this step's vote; -2 = live but out of text, -1 = dropped out
+    __shared__ unsigned long long red[4];
+    __shared__ int sw[4];
+    __shared__ int n_occ_s;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    auto none = [&]() {
+        if (tid == 0) { draft_start[b] = -1; match_len[b] = 0; draft_len[b] = 0; draft_src[b] = -1; }
+    };
+    const int n_pat = min(min(tail_len[b], pol.window), w_max);
+    if (budget_left[b] <= 0 || n_pat < pol.m_min || n_pat <= 0) { none(); return; }
+    if (tid < n_pat) pat[tid] = tail[(size_t)b * w_max + (w_max - 1 - tid)];
+    if (tid == 0) n_occ_s = 0;
+    // longest match over all segments of all responses
+    unsigned long long k = 0ull;
+    for (int i = tid; i < n_resp * max_segs; i += 256) {
+        const int g = i / max_segs, sgm = i % max_segs;
+        const int lh = hist_off[b * n_resp + g + 1] - hist_off[b * n_resp + g];
+        if (sgm * HS_DRAFT_SEG + 1 <= lh - 1) {
+            unsigned long long v = best[(size_t)(b * n_resp + g) * max_segs + sgm] >> 32;
+            if (v > k) k = v;
+        }
+    }
+    const int m_star = (int)block_max_u64(k, red);   // (contains the barriers that publish pat and n_occ_s)
+    if (m_star < pol.m_min || m_star <= 0) { none(); return; }
+    // occurrences, in (response, position) order: only segments whose best match reaches m_star hold any
+    for (int g = 0; g < n_resp; g++) {
+        const int off = hist_off[b * n_resp + g], lh = hist_off[b * n_resp + g + 1] - off;
+        const int rew = reward[b * n_resp + g];
+        for (int sgm = 0; sgm < max_segs && sgm * HS_DRAFT_SEG + 1 <= lh - 1; sgm++) {
+            if ((int)(best[(size_t)(b * n_resp + g) * max_segs + sgm] >> 32) < m_star) continue;   // uniform
+            const int p_hi = min((sgm + 1) * HS_DRAFT_SEG, lh - 1);
+            for (int p0 = sgm * HS_DRAFT_SEG + 1; p0 <= p_hi; p0 += 256) {
+                const int p = p0 + tid;
+                int hit = 0;
+                if (p <= p_hi && p >= m_star) {
+                    int m = 0;
+                    while (m < m_star && hist[off + p - 1 - m] == pat[m]) m++;
+                    hit = m == m_star;
+                }
+                int total;
+                const int before = block_excl_scan_256(hit, &total, sw);
+                const int base = n_occ_s;
+                if (hit && base + before < HS_OCC_MAX) {
+                    occ_off[base + before] = off + p;
+                    occ_end[base + before] = off + lh;
+                    occ_rew[base + before] = rew;
+                }
+                __syncthreads();
+                if (tid == 0) n_occ_s = min(HS_OCC_MAX, base + total);
+                __syncthreads();
+                if (n_occ_s >= HS_OCC_MAX) break;
+            }
+            if (n_occ_s >= HS_OCC_MAX) break;
+        }
+        if (n_occ_s >= HS_OCC_MAX) break;
+    }
+    const int n_occ = n_occ_s;
+    // draft length the policy asks for
+    int kk = pol.k_mode == HS_K_FIXED ? pol.k_fixed : (pol.k_mode == HS_K_MATCHLEN ? m_star : k_state[b]);
+    kk = max(0, min(min(kk, pol.k_max), budget_left[b] - 1));
+    // the walk
+    for (int i = tid; i < n_occ; i += 256) occ_tok[i] = 0;   // live
+    __syncthreads();
+    int len = 0;
+    for (int j = 0; j < kk; j++) {
+        for (int i = tid; i < n_occ; i += 256)
+            if (occ_tok[i] != -1) occ_tok[i] = (occ_off[i] + j < occ_end[i]) ? hist[occ_off[i] + j] : -2;
+        __syncthreads();
+        // every live occurrence prices its own token: (reward sum, votes) packed, larger is better
+        unsigned long long key = 0ull;
+        for (int i = tid; i < n_occ; i += 256) {
+            const int t = occ_tok[i];
+            if (t < 0) continue;
+            unsigned long long sum = 0ull;
+            unsigned votes = 0u;
+            for (int q = 0; q < n_occ; q++)
+                if (occ_tok[q] == t) { sum += (unsigned long long)occ_rew[q]; votes++; }
+            const unsigned long long v = ((sum << 11) | votes) + 1ull;   // + 1: a live vote always beats "none"
+            if (v > key) key = v;
+        }
+        const unsigned long long top = block_max_u64(key, red);
+        if (top == 0ull) break;   // nobody has a token left: the live occurrences stay live (marked -2)
+        // among the tokens with the top price, the smallest id
+        unsigned long long cand = 0ull;
+        for (int i = tid; i < n_occ; i += 256) {
+            const int t = occ_tok[i];
+            if (t < 0) continue;
+            unsigned long long sum = 0ull;
+            unsigned votes = 0u;
+            for (int q = 0; q < n_occ; q++)
+                if (occ_tok[q] == t) { sum += (unsigned long long)occ_rew[q]; votes++; }
+            if (((sum << 11) | votes) + 1ull == top) {
+                const unsigned long long v = 0xFFFFFFFFull - (unsigned)t;
+                if (v > cand) cand = v;
+            }
+        }
+        const int chosen = (int)(0xFFFFFFFFull - block_max_u64(cand, red));
+        for (int i = tid; i < n_occ; i += 256)
+            if (occ_tok[i] != chosen) occ_tok[i] = -1;
+        len++;
+        __syncthreads();
+    }
+    // first surviving occurrence (every occurrence is live if nothing was drafted; one that only ran out of text
+    // at the step that ended the walk is still live)
+    unsigned long long firstk = 0ull;
+    for (int i = tid; i < n_occ; i += 256)
+        if (len == 0 || occ_tok[i] != -1) { firstk = 0xFFFFFFFFull - (unsigned)i; break; }
+    const unsigned long long fk = block_max_u64(firstk, red);
+    if (fk == 0ull || n_occ <= 0) { none(); return; }   // cannot happen: the chosen token came from a live occurrence
+    const int first = (int)(0xFFFFFFFFull - fk);
+    if (tid == 0) {
+        // its response: the one that ends where the occurrence's response ends
+        int g = 0;
+        while (g + 1 < n_resp && hist_off[b * n_resp + g + 1] != occ_end[first]) g++;
+        draft_src[b] = g;
+        draft_start[b] = occ_off[first] - hist_off[b * n_resp + g];
+        match_len[b] = m_star;
+        draft_len[b] = len;
+    }
+}
+
 }  // namespace
 
 void hs_launch_draft(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
@@ -210,5 +375,25 @@ void hs_launch_draft(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_
                        seq->batch, best, ctx->max_segs, seq->seq_len, seq->tail, ctx->lim.w_max, seq->k_state,
                        seq->budget_left, p, ctx->lim.max_blocks_per_seq, ctx->lim.max_pos, ctx->lim.max_rows,
                        step->draft_start, step->match_len, step->draft_len, step->row_off, step->tok, step->pos,
-                       step->parent, step->anc_mask, step->row2seq, err);
+                       step->parent, step->anc_mask, step->row2seq, err, 0, nullptr);
+}
+
+void hs_launch_draft_group(const hs_ctx* ctx, const hs_group_draft_args* args, const hs_seq_state* seq,
+                           hs_step* step, hipStream_t st) {
+    unsigned long long* best = reinterpret_cast<unsigned long long*>(ctx->ws + ctx->lay.draft_best);
+    uint32_t* err = reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.err);
+    const hs_policy& p = args->policy;
+    dim3 grid(ctx->max_segs, seq->batch * args->n_resp);
+    hipLaunchKernelGGL(draft_scan_kernel, grid, dim3(256), 0, st, args->hist, args->hist_off, args->n_resp,
+                       seq->tail, seq->tail_len, seq->budget_left, ctx->lim.w_max, p.window, p.m_min,
+                       ctx->max_segs, best);
+    hipLaunchKernelGGL(draft_group_walk_kernel, dim3(seq->batch), dim3(256), 0, st, args->hist, args->hist_off,
+                       args->reward, args->n_resp, best, ctx->max_segs, seq->tail, seq->tail_len, ctx->lim.w_max,
+                       seq->k_state, seq->budget_left, p, step->draft_start, step->match_len, step->draft_len,
+                       step->draft_src);
+    hipLaunchKernelGGL(draft_build_kernel, dim3(1), dim3(256), 0, st, args->hist, args->hist_off, 1, seq->batch,
+                       best, ctx->max_segs, seq->seq_len, seq->tail, ctx->lim.w_max, seq->k_state, seq->budget_left,
+                       p, ctx->lim.max_blocks_per_seq, ctx->lim.max_pos, ctx->lim.max_rows, step->draft_start,
+                       step->match_len, step->draft_len, step->row_off, step->tok, step->pos, step->parent,
+                       step->anc_mask, step->row2seq, err, args->n_resp, step->draft_src);
 }

@@ -91,6 +91,8 @@ void hs_launch_argmax(const hs_ctx* ctx, const float* logits, int32_t* argmax, c
                       hipStream_t st);
 void hs_launch_draft(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
                      hipStream_t st);
+void hs_launch_draft_group(const hs_ctx* ctx, const hs_group_draft_args* args, const hs_seq_state* seq,
+                           hs_step* step, hipStream_t st);
 void hs_launch_accept(const hs_ctx* ctx, const hs_accept_args* args, const hs_seq_state* seq, hs_step* step,
                       const float* logits, hipStream_t st);
 void hs_launch_commit(const hs_ctx* ctx, const hs_kv_cache* cache, hs_seq_state* seq, const hs_step* step,

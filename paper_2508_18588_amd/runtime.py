@@ -11,7 +11,7 @@ import numpy as np
 import torch
 
 from . import (HS_ACCEPT_GREEDY, HS_K_FIXED, hs_accept, hs_accept_args, hs_bind_workspace, hs_create, hs_debug_buffer, hs_debug_gemm,
-               hs_destroy, hs_draft, hs_draft_args, hs_get_profile, hs_kv_cache, hs_kv_commit, hs_limits,
+               hs_destroy, hs_draft, hs_draft_args, hs_draft_group, hs_group_draft_args, hs_get_profile, hs_kv_cache, hs_kv_commit, hs_limits,
                hs_model_desc, hs_policy, hs_poll_error, hs_seq_state, hs_set_flags, hs_set_profile, hs_step,
                hs_verify, hs_weights, hs_workspace_bytes)
 
@@ -50,7 +50,7 @@ class Engine:
 
     def __init__(self, shape, weights: dict, rope, max_batch: int, k_max: int, c_max: int, max_len: int,
                  w_max: int = 32, seq_caps=None, shuffle_pages_seed: int | None = None, n_layers: int | None = None,
-                 keep_logits: bool = True):
+                 keep_logits: bool = True, g_max: int = 0):
         self.shape = shape
         self.dev = torch.device("cuda:0")
         L = len(weights["wqkv"]) if n_layers is None else n_layers
@@ -93,7 +93,8 @@ class Engine:
         hw = hs_weights(w["embed"].data_ptr(), w["lm_head"].data_ptr(), w["norm_f"].data_ptr(), parr(w["wqkv"]),
                         parr(w["wo"]), parr(w["wgate"]), parr(w["wup"]), parr(w["wdown"]), parr(w["norm1"]),
                         parr(w["norm2"]), self.rope.data_ptr())
-        lim = hs_limits(max_batch, k_max, c_max, self.max_rows, self.max_blocks, self.max_pos, w_max)
+        self.g_max = g_max
+        lim = hs_limits(max_batch, k_max, c_max, self.max_rows, self.max_blocks, self.max_pos, w_max, g_max)
         self.ctx = hs_create(desc, hw, lim)
         nbytes = hs_workspace_bytes(self.ctx)
         self.workspace = torch.zeros(nbytes + 256, dtype=torch.uint8, device=self.dev)
@@ -113,6 +114,7 @@ class Engine:
         self.tokens = torch.zeros(B, self.tokens_stride, **i32)
         self.counters = torch.zeros(4, dtype=torch.int64, device=self.dev)
         self.st = {n: torch.zeros(B * c_max, **i32) for n in ("draft_start", "match_len", "draft_len")}
+        self.st["draft_src"] = torch.zeros(B, **i32)
         self.st.update({n: torch.zeros(M, **i32) for n in ("tok", "pos", "parent", "row2seq", "argmax")})
         self.st["row_off"] = torch.zeros(B + 1, **i32)
         self.st["anc_mask"] = torch.zeros(M, dtype=torch.int64, device=self.dev)
@@ -137,7 +139,7 @@ class Engine:
                               s["parent"].data_ptr(), s["anc_mask"].data_ptr(), s["row2seq"].data_ptr(),
                               self.logits.data_ptr() if self.logits is not None else None, s["argmax"].data_ptr(),
                               s["accept_len"].data_ptr(), s["n_out"].data_ptr(), s["out_tok"].data_ptr(),
-                              s["path_row"].data_ptr(), getattr(self, "rows_hint", 0))
+                              s["path_row"].data_ptr(), getattr(self, "rows_hint", 0), s["draft_src"].data_ptr())
 
     def close(self):
         if self.ctx:
@@ -196,6 +198,32 @@ class Engine:
     def draft(self, policy: Policy):
         args = hs_draft_args(self.n_cand, self.hist.data_ptr(), self.hist_off.data_ptr(), policy.c())
         hs_draft(self.ctx, args, self.c_seq, self.c_step, self.stream())
+
+    def set_group_history(self, groups, rewards):
+        """groups[b][g] = int array: response g of sequence b's prompt in its last rollout (already carrying its
+        prompt context); rewards[b][g] = the reward it earned (non-negative int)."""
+        self.n_resp = len(groups[0])
+        flat, off, rew = [], [0], []
+        for row, rr in zip(groups, rewards):
+            assert len(row) == self.n_resp == len(rr)
+            for h, r in zip(row, rr):
+                flat.append(np.asarray(h, np.int32))
+                off.append(off[-1] + len(h))
+                rew.append(int(r))
+        self.ghist = _dev(np.concatenate(flat) if off[-1] else np.zeros(1, np.int32))
+        self.ghist_off = _dev(np.asarray(off, np.int32))
+        self.greward = _dev(np.asarray(rew, np.int32))
+
+    def draft_group(self, policy: Policy):
+        args = hs_group_draft_args(self.n_resp, self.ghist.data_ptr(), self.ghist_off.data_ptr(),
+                                   self.greward.data_ptr(), policy.c())
+        hs_draft_group(self.ctx, args, self.c_seq, self.c_step, self.stream())
+
+    def step_group(self, policy: Policy, mode: int = HS_ACCEPT_GREEDY, temperature: float = 1.0, seed: int = 0):
+        self.draft_group(policy)
+        self.verify()
+        self.accept(mode, temperature, seed)
+        self.commit(policy)
 
     def set_rows_hint(self, rows: int):
         """Tell the library how many rows to expect (a launch-shape hint; results do not depend on it)."""

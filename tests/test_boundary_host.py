@@ -28,10 +28,11 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_struct_sizes_match_the_header_layout():
     assert C.sizeof(hs.hs_model_desc) == 36
-    assert C.sizeof(hs.hs_limits) == 28
+    assert C.sizeof(hs.hs_limits) == 32
     assert C.sizeof(hs.hs_policy) == 32
     assert C.sizeof(hs.hs_weights) == 11 * 8
-    assert C.sizeof(hs.hs_step) == 16 * 8
+    assert C.sizeof(hs.hs_step) == 17 * 8
+    assert C.sizeof(hs.hs_group_draft_args) == 8 + 3 * 8 + 32
     assert C.sizeof(hs.hs_accept_args) == 16
     assert C.sizeof(hs.hs_kv_cache) == 24
 
