@@ -55,6 +55,9 @@ def lib():
         L.orc_reward_draft.argtypes = [C.c_int, i32p, i32p, i32p, i32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                        i32p, intp, intp, intp, intp]
         L.orc_k_policy.argtypes = [C.c_int] * 5
+        L.orc_gate_step.argtypes = [i32p, C.c_int, C.c_uint32, C.c_uint32]
+        L.orc_gate_table.argtypes = [C.POINTER(C.c_float), i32p, C.c_int, C.c_double, C.c_int, i32p]
+        L.orc_gate_table.restype = None
         L.orc_draft_len.argtypes = [C.c_int] * 4
         L.orc_aimd.argtypes = [C.c_int] * 6
         L.orc_build_tree.argtypes = [C.c_int, C.POINTER(i32p), intp, C.c_int32, C.c_int, i32p, i32p, i32p, u64p,
@@ -128,6 +131,22 @@ def trace_sim(cur, hist, key: int = 3) -> int:
     c, cp = _i32(cur)
     h, hp = _i32(hist)
     return lib().orc_trace_sim(cp, len(c), hp, len(h), key)
+
+
+def gate_step(gate: np.ndarray, live: int, drafted_total: int, accepted_total: int) -> int:
+    """Advance the speculation gate (int32[32], updated in place) by one step; returns 1 if speculation runs."""
+    assert gate.dtype == np.int32 and gate.flags.c_contiguous and gate.size >= 25
+    return lib().orc_gate_step(gate.ctypes.data_as(C.POINTER(C.c_int32)), live, drafted_total & 0xFFFFFFFF,
+                               accepted_total & 0xFFFFFFFF)
+
+
+def gate_table(ms, rows, k_bar: float, b_max: int) -> np.ndarray:
+    m = np.ascontiguousarray(ms, dtype=np.float32)
+    r, rp = _i32(rows)
+    out = np.zeros(17, np.int32)
+    lib().orc_gate_table(m.ctypes.data_as(C.POINTER(C.c_float)), rp, len(m), float(k_bar), b_max,
+                         out.ctypes.data_as(C.POINTER(C.c_int32)))
+    return out
 
 
 def k_policy(mode, k_fixed, k_state, match_len, k_max) -> int:

@@ -25,6 +25,11 @@
  *   orc_trace_sim          Sec. 5.1 token-similarity study (3-token key).
  *   orc_k_policy, orc_aimd Sec. 5.4 (window starts at 2, +2 when every draft
  *                          token is accepted, cap 32, back to 2 on a reject).
+ *   orc_gate_step,
+ *   orc_gate_table         Sec. 5.4, last paragraph: the acceptance rate is
+ *                          monitored and speculation is switched off while the
+ *                          batch is larger than the largest batch at which it
+ *                          still pays at that rate (a pre-profiled table).
  *   orc_seq_*              Sec. 2.2: the target model's forward pass (a
  *                          standard pre-norm decoder; shape from the
  *                          benchmark configurations).
@@ -40,6 +45,71 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+
+/* ------------------------------------------------- speculation on / off */
+
+/*
+ * Throughput-aware speculation control (Sec. 5.4, last paragraph).  The paper:
+ * acceptance rates are monitored; pre-profiling gives, per acceptance rate, the
+ * largest batch at which speculation still raises throughput; above it
+ * speculation is switched off.  The rest is this build's reading, in integers
+ * so that both sides agree exactly:
+ *   - monitor: decayed sums D (drafted) and A (accepted) over the steps so
+ *     far, each step X <- X - (X >> 3) + x (a memory of about eight steps);
+ *   - rate bucket = 16 A / D rounded down, 0..16 (16 when nothing was drafted
+ *     lately: no evidence against speculating);
+ *   - speculation runs this step iff live <= table[bucket], or it has been
+ *     off for probe_every steps in a row (one probing step refreshes the
+ *     monitor; probe_every = 0: never probe).
+ * gate: [0] D, [1] A, [2] steps since speculation last ran, [3] last decision,
+ * [4] probe_every, [5] / [6] drafted / accepted totals seen so far (mod 2^32),
+ * [7] decisions made, [8..24] table.  Returns the decision (1 = speculate).
+ */
+int orc_gate_step(int32_t* gate, int live, uint32_t drafted_total, uint32_t accepted_total) {
+    uint32_t d = drafted_total - (uint32_t)gate[5], a = accepted_total - (uint32_t)gate[6];
+    gate[5] = (int32_t)drafted_total;
+    gate[6] = (int32_t)accepted_total;
+    gate[0] = gate[0] - (gate[0] >> 3) + (int32_t)d;
+    gate[1] = gate[1] - (gate[1] >> 3) + (int32_t)a;
+    int steps_off = (gate[7] > 0 && gate[3] == 0) ? gate[2] + 1 : 0;
+    int bucket = 16;
+    if (gate[0] > 0) {
+        long long q = (long long)gate[1] * 16 / gate[0];
+        bucket = q > 16 ? 16 : (int)q;
+    }
+    int on = live <= gate[8 + bucket] || (gate[4] > 0 && steps_off >= gate[4]);
+    gate[2] = steps_off;
+    gate[3] = on;
+    gate[7] += 1;
+    return on;
+}
+
+/* Step time at `rows` rows from profiled points (rows ascending): straight lines between neighbours, the outer
+ * lines continued beyond the ends. */
+static double profile_ms(const float* ms, const int32_t* rows, int n, double m) {
+    int i = 0;
+    while (i + 2 < n && m > rows[i + 1]) i++;
+    double x0 = rows[i], x1 = rows[i + 1];
+    return ms[i] + (ms[i + 1] - ms[i]) * (m - x0) / (x1 - x0);
+}
+
+/*
+ * The pre-profiled table: for acceptance rate i/16 the largest batch b <= b_max
+ * at which a step with drafts of k_bar tokens per sequence emits at least as
+ * many tokens per second as a step without: (1 + rate k_bar) / t(b (1 + k_bar))
+ * >= 1 / t(b); 0 if there is none.  t = the verify step time as a function of
+ * the row count, from n >= 2 profiled points.
+ */
+void orc_gate_table(const float* ms, const int32_t* rows, int n, double k_bar, int b_max, int32_t* table) {
+    for (int i = 0; i <= 16; i++) {
+        double rate = i / 16.0;
+        table[i] = 0;
+        for (int b = 1; b <= b_max; b++) {
+            double t0 = profile_ms(ms, rows, n, b), t1 = profile_ms(ms, rows, n, b * (1.0 + k_bar));
+            if ((1.0 + rate * k_bar) * t0 >= t1) table[i] = b;
+        }
+    }
+}
 
 /* ------------------------------------------------------------------ draft */
 
