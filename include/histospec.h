@@ -120,7 +120,20 @@ typedef struct hs_seq_state {
     int32_t* tokens;          /* optional [batch][tokens_stride]: committed tokens are also appended here at n_b */
     int32_t tokens_stride;
     uint64_t* counters;       /* optional [4]: sequence-steps, drafted, accepted, emitted tokens (accumulated) */
+    int32_t* gate;            /* optional [HS_GATE_WORDS], needs counters: throughput-aware speculation control (see
+                                 hs_gate_table_build); zero-initialised by the caller except [4] and the table */
 } hs_seq_state;
+
+/* Throughput-aware speculation control (Sec. 5.4, last paragraph: the acceptance rate is monitored, pre-profiling
+ * gives the largest batch at which speculation still raises throughput at each rate, above it speculation is
+ * switched off).  With hs_seq_state.gate set, hs_draft / hs_draft_group decide once per step for the whole batch:
+ *   monitor   D, A <- X - (X >> 3) + (tokens drafted / accepted by the previous step), from `counters`;
+ *   bucket    16 A / D rounded down, capped at 16; 16 when D == 0;
+ *   decision  speculate iff (sequences with budget left) <= table[bucket], or speculation has been off for
+ *             probe_every steps in a row (probe_every = 0: never probe).  Off: every sequence gets a one-row step.
+ * Words: [0] D, [1] A, [2] steps since speculation last ran, [3] last decision, [4] probe_every (caller-set),
+ * [5] / [6] drafted / accepted totals seen (mod 2^32), [7] decisions made, [8..24] table (caller-set). */
+enum { HS_GATE_WORDS = 32, HS_GATE_TABLE = 8 };
 
 /* Draft policy (Sec. 5.4).  Pattern = the last `window` committed tokens; a match must cover at least m_min
  * of them.  HS_K_FIXED drafts k_fixed tokens, HS_K_MATCHLEN as many as matched (clamped to 1..k_max),
@@ -240,6 +253,14 @@ hs_status hs_poll_error(hs_ctx* ctx, hs_stream stream, uint32_t* error_bits);
  * (after the last RMSNorm), 1 last layer's queries bf16 [max_rows][n_q_heads*head_dim] (after rotation),
  * 2 last layer's attention output bf16 (same shape), 3 logits f32 [max_rows][vocab]. */
 hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size_t* bytes);
+
+/* HOST helper: the table of the speculation gate from a profiled step time.  ms[i] = duration of one decode step
+ * (all four calls) at rows[i] rows, rows ascending, n_points >= 2 (straight lines between neighbours, the outer
+ * lines continued beyond the ends).  table17[i] = the largest batch b <= b_max at which drafting k_bar tokens per
+ * sequence with acceptance rate i/16 emits at least as many tokens per second as not drafting:
+ * (1 + k_bar i/16) t(b) >= t(b (1 + k_bar)); 0 if there is none.  No device work. */
+hs_status hs_gate_table_build(const float* ms, const int32_t* rows, int32_t n_points, float k_bar, int32_t b_max,
+                              int32_t* table17);
 
 /* One projection on its own, through the same launcher hs_verify uses (unit-level parity tests and timing):
  * C[m, n] (+)= A[m, k] . W[n, k]^T with bf16 operands, K-contiguous, fp32 accumulation in the shape's fixed K

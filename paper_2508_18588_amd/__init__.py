@@ -22,6 +22,7 @@ HS_DEV_BLOCK_TABLE_OVERFLOW, HS_DEV_POSITION_OVERFLOW, HS_DEV_ROW_OVERFLOW = 1, 
 HS_K_FIXED, HS_K_MATCHLEN, HS_K_AIMD = 0, 1, 2
 HS_ACCEPT_GREEDY, HS_ACCEPT_REJECTION = 0, 1
 HS_FLAG_REFERENCE_KERNELS = 1
+HS_GATE_WORDS, HS_GATE_TABLE = 32, 8
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -82,7 +83,7 @@ class hs_seq_state(C.Structure):
     _fields_ = [("batch", C.c_int32), ("seq_len", C.c_void_p), ("block_table", C.c_void_p), ("tail", C.c_void_p),
                 ("tail_len", C.c_void_p), ("k_state", C.c_void_p), ("budget_left", C.c_void_p),
                 ("seq_id", C.c_void_p), ("tokens", C.c_void_p), ("tokens_stride", C.c_int32),
-                ("counters", C.c_void_p)]
+                ("counters", C.c_void_p), ("gate", C.c_void_p)]
 
 
 class hs_policy(C.Structure):
@@ -111,7 +112,7 @@ class hs_accept_args(C.Structure):
 
 EXPORTS = ("hs_create", "hs_destroy", "hs_last_error", "hs_set_flags", "hs_workspace_bytes", "hs_bind_workspace",
            "hs_draft", "hs_draft_group", "hs_verify", "hs_accept", "hs_kv_commit", "hs_poll_error", "hs_debug_buffer",
-           "hs_set_profile", "hs_get_profile", "hs_debug_gemm")
+           "hs_set_profile", "hs_get_profile", "hs_debug_gemm", "hs_gate_table_build")
 
 _lib = None
 
@@ -148,6 +149,8 @@ def lib():
         L.hs_debug_buffer.argtypes = [vp, C.c_int32, C.POINTER(vp), C.POINTER(C.c_size_t)]
         L.hs_set_profile.argtypes = [vp, C.c_int32]
         L.hs_get_profile.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+        L.hs_gate_table_build.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int32), C.c_int32, C.c_float, C.c_int32,
+                                          C.POINTER(C.c_int32)]
         L.hs_debug_gemm.argtypes = [vp, C.c_int32, vp, vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp]
         _lib = L
     return _lib
@@ -230,6 +233,18 @@ def hs_set_profile(ctx, level: int):
 def hs_debug_gemm(ctx, epi: int, a: int, w: int, w2: int, c: int, m_dev: int, m_max: int, n: int, k: int,
                   rows_hint: int, stream):
     _check(ctx, lib().hs_debug_gemm(ctx, epi, a, w, w2 or None, c, m_dev, m_max, n, k, rows_hint, stream))
+
+
+def hs_gate_table_build(ms, rows, k_bar: float, b_max: int):
+    """Table of the speculation gate (17 ints) from a profiled step time; host arithmetic in the library."""
+    n = len(ms)
+    m = (C.c_float * n)(*[float(x) for x in ms])
+    r = (C.c_int32 * n)(*[int(x) for x in rows])
+    out = (C.c_int32 * 17)()
+    st = lib().hs_gate_table_build(m, r, n, float(k_bar), int(b_max), out)
+    if st != HS_OK:
+        raise HsError(st, "hs_gate_table_build rejected the profile")
+    return list(out)
 
 
 def hs_get_profile(ctx):

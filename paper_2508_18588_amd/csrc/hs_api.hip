@@ -83,7 +83,8 @@ bool step_ok(const hs_step* s) {
 
 bool seq_ok(const hs_ctx* ctx, const hs_seq_state* s) {
     return s && s->batch >= 1 && s->batch <= ctx->lim.max_batch && s->seq_len && s->block_table && s->tail &&
-           s->tail_len && s->k_state && s->budget_left && s->seq_id && (!s->tokens || s->tokens_stride > 0);
+           s->tail_len && s->k_state && s->budget_left && s->seq_id && (!s->tokens || s->tokens_stride > 0) &&
+           (!s->gate || s->counters);
 }
 
 bool policy_ok(const hs_ctx* ctx, const hs_policy* p) {
@@ -371,6 +372,29 @@ hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size
         case 2: *dev_ptr = ctx->ws + ctx->lay.attn; *bytes = M * qh * 2; break;
         case 3: *dev_ptr = ctx->ws + ctx->lay.logits; *bytes = M * (size_t)d.vocab * 4; break;
         default: return HS_ERR_INVALID_ARG;
+    }
+    return HS_OK;
+}
+
+hs_status hs_gate_table_build(const float* ms, const int32_t* rows, int32_t n_points, float k_bar, int32_t b_max,
+                              int32_t* table17) {
+    if (!ms || !rows || !table17 || n_points < 2 || !(k_bar >= 0.f) || b_max < 0) return HS_ERR_INVALID_ARG;
+    for (int i = 1; i < n_points; i++)
+        if (rows[i] <= rows[i - 1]) return HS_ERR_INVALID_ARG;
+    // step time at m rows: the segment of the profile that contains m, the outer segments continued beyond the ends
+    auto t = [&](double m) {
+        int seg = n_points - 2;
+        for (int i = 0; i + 1 < n_points - 1; i++)
+            if (m <= rows[i + 1]) { seg = i; break; }
+        const double rise = (double)ms[seg + 1] - (double)ms[seg], run = (double)rows[seg + 1] - (double)rows[seg];
+        return (double)ms[seg] + rise * (m - (double)rows[seg]) / run;
+    };
+    for (int i = 0; i <= 16; i++) {
+        const double gain = 1.0 + (double)k_bar * i / 16.0;
+        int best = 0;
+        for (int b = 1; b <= b_max; b++)
+            if (gain * t(b) >= t(b * (1.0 + (double)k_bar))) best = b;
+        table17[i] = best;
     }
     return HS_OK;
 }

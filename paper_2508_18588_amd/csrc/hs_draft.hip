@@ -98,13 +98,44 @@ __global__ __launch_bounds__(256) void draft_build_kernel(
     int32_t* __restrict__ draft_start, int32_t* __restrict__ match_len, int32_t* __restrict__ draft_len,
     int32_t* __restrict__ row_off, int32_t* __restrict__ tok, int32_t* __restrict__ pos,
     int32_t* __restrict__ parent, uint64_t* __restrict__ anc_mask, int32_t* __restrict__ row2seq,
-    uint32_t* __restrict__ err, int group_n, const int32_t* __restrict__ draft_src) {
+    uint32_t* __restrict__ err, int group_n, const int32_t* __restrict__ draft_src, int32_t* __restrict__ gate,
+    const unsigned long long* __restrict__ counters) {
     // group_n > 0: the draft of sequence b was chosen by the group walk (response draft_src[b] of its group_n
     // responses, start draft_start[b], length draft_len[b]); this kernel then only lays out the rows (n_cand == 1)
     __shared__ int sw[4];
     __shared__ int carry_s;
-    if (threadIdx.x == 0) carry_s = 0;
+    __shared__ int live_s, spec_on_s;
+    if (threadIdx.x == 0) { carry_s = 0; live_s = 0; spec_on_s = 1; }
     __syncthreads();
+    if (gate) {
+        // Throughput-aware speculation control (Sec. 5.4, last paragraph): one decision per step for the whole batch.
+        // The monitor takes the previous step's drafted / accepted tokens from the counters hs_kv_commit keeps.
+        int live = 0;
+        for (int b = threadIdx.x; b < batch; b += 256) live += budget_left[b] > 0;
+        if (live) atomicAdd(&live_s, live);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t dt = (uint32_t)counters[1], at = (uint32_t)counters[2];
+            const uint32_t d = dt - (uint32_t)gate[5], a = at - (uint32_t)gate[6];
+            gate[5] = (int32_t)dt;
+            gate[6] = (int32_t)at;
+            gate[0] = gate[0] - (gate[0] >> 3) + (int32_t)d;
+            gate[1] = gate[1] - (gate[1] >> 3) + (int32_t)a;
+            const int steps_off = (gate[7] > 0 && gate[3] == 0) ? gate[2] + 1 : 0;
+            int bucket = 16;
+            if (gate[0] > 0) {
+                const long long q = (long long)gate[1] * 16 / gate[0];
+                bucket = q > 16 ? 16 : (int)q;
+            }
+            const int on = live_s <= gate[HS_GATE_TABLE + bucket] || (gate[4] > 0 && steps_off >= gate[4]);
+            gate[2] = steps_off;
+            gate[3] = on;
+            gate[7] += 1;
+            spec_on_s = on;
+        }
+        __syncthreads();
+    }
+    const bool spec_on = spec_on_s != 0;
     for (int b0 = 0; b0 < batch; b0 += 256) {
         const int b = b0 + threadIdx.x;
         int nn = 0, L = 0;
@@ -115,7 +146,7 @@ __global__ __launch_bounds__(256) void draft_build_kernel(
             if (group_n > 0) {
                 const int g = draft_src[b];
                 pstart[0] = draft_start[b];
-                klen[0] = g >= 0 ? draft_len[b] : 0;
+                klen[0] = (g >= 0 && spec_on) ? draft_len[b] : 0;
                 hoff[0] = g >= 0 ? hist_off[b * group_n + g] + pstart[0] : 0;
             }
             for (int c = 0; c < n_cand && group_n == 0; c++) {
@@ -138,6 +169,7 @@ __global__ __launch_bounds__(256) void draft_build_kernel(
                     kk = min(kk, lh - p);
                     kk = min(kk, budget_left[b] - 1);
                     kk = max(kk, 0);
+                    if (!spec_on) kk = 0;
                 }
                 pstart[c] = p; klen[c] = kk; hoff[c] = off + (p < 0 ? 0 : p);
                 draft_start[bc] = p;
@@ -375,7 +407,8 @@ void hs_launch_draft(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_
                        seq->batch, best, ctx->max_segs, seq->seq_len, seq->tail, ctx->lim.w_max, seq->k_state,
                        seq->budget_left, p, ctx->lim.max_blocks_per_seq, ctx->lim.max_pos, ctx->lim.max_rows,
                        step->draft_start, step->match_len, step->draft_len, step->row_off, step->tok, step->pos,
-                       step->parent, step->anc_mask, step->row2seq, err, 0, nullptr);
+                       step->parent, step->anc_mask, step->row2seq, err, 0, nullptr, seq->gate,
+                       (const unsigned long long*)seq->counters);
 }
 
 void hs_launch_draft_group(const hs_ctx* ctx, const hs_group_draft_args* args, const hs_seq_state* seq,
@@ -395,5 +428,6 @@ void hs_launch_draft_group(const hs_ctx* ctx, const hs_group_draft_args* args, c
                        best, ctx->max_segs, seq->seq_len, seq->tail, ctx->lim.w_max, seq->k_state, seq->budget_left,
                        p, ctx->lim.max_blocks_per_seq, ctx->lim.max_pos, ctx->lim.max_rows, step->draft_start,
                        step->match_len, step->draft_len, step->row_off, step->tok, step->pos, step->parent,
-                       step->anc_mask, step->row2seq, err, args->n_resp, step->draft_src);
+                       step->anc_mask, step->row2seq, err, args->n_resp, step->draft_src, seq->gate,
+                       (const unsigned long long*)seq->counters);
 }

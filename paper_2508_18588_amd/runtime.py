@@ -10,7 +10,7 @@ from dataclasses import dataclass
 import numpy as np
 import torch
 
-from . import (HS_ACCEPT_GREEDY, HS_K_FIXED, hs_accept, hs_accept_args, hs_bind_workspace, hs_create, hs_debug_buffer, hs_debug_gemm,
+from . import (HS_ACCEPT_GREEDY, HS_GATE_TABLE, HS_GATE_WORDS, HS_K_FIXED, hs_gate_table_build, hs_accept, hs_accept_args, hs_bind_workspace, hs_create, hs_debug_buffer, hs_debug_gemm,
                hs_destroy, hs_draft, hs_draft_args, hs_draft_group, hs_group_draft_args, hs_get_profile, hs_kv_cache, hs_kv_commit, hs_limits,
                hs_model_desc, hs_policy, hs_poll_error, hs_seq_state, hs_set_flags, hs_set_profile, hs_step,
                hs_verify, hs_weights, hs_workspace_bytes)
@@ -113,6 +113,7 @@ class Engine:
         self.tokens_stride = max(caps) + nodes
         self.tokens = torch.zeros(B, self.tokens_stride, **i32)
         self.counters = torch.zeros(4, dtype=torch.int64, device=self.dev)
+        self.gate = None
         self.st = {n: torch.zeros(B * c_max, **i32) for n in ("draft_start", "match_len", "draft_len")}
         self.st["draft_src"] = torch.zeros(B, **i32)
         self.st.update({n: torch.zeros(M, **i32) for n in ("tok", "pos", "parent", "row2seq", "argmax")})
@@ -133,7 +134,8 @@ class Engine:
         self.c_seq = hs_seq_state(self.batch, self.seq_len.data_ptr(), self.block_table.data_ptr(),
                                   self.tail.data_ptr(), self.tail_len.data_ptr(), self.k_state.data_ptr(),
                                   self.budget_left.data_ptr(), self.seq_id.data_ptr(), self.tokens.data_ptr(),
-                                  self.tokens_stride, self.counters.data_ptr())
+                                  self.tokens_stride, self.counters.data_ptr(),
+                                  self.gate.data_ptr() if self.gate is not None else None)
         self.c_step = hs_step(s["draft_start"].data_ptr(), s["match_len"].data_ptr(), s["draft_len"].data_ptr(),
                               s["row_off"].data_ptr(), s["tok"].data_ptr(), s["pos"].data_ptr(),
                               s["parent"].data_ptr(), s["anc_mask"].data_ptr(), s["row2seq"].data_ptr(),
@@ -244,6 +246,25 @@ class Engine:
         self.verify()
         self.accept(mode, temperature, seed)
         self.commit(policy)
+
+    def set_gate(self, table, probe_every: int = 0):
+        """Switch on throughput-aware speculation control with this 17-entry table (None: off).  The monitor starts
+        empty and picks the counters up where they stand."""
+        if table is None:
+            self.gate = None
+        else:
+            assert len(table) == 17
+            g = np.zeros(HS_GATE_WORDS, np.int32)
+            g[4] = probe_every
+            c = self.counters.cpu().numpy().astype(np.uint64)
+            g[5], g[6] = np.uint32(c[1] & 0xFFFFFFFF).astype(np.int32), np.uint32(c[2] & 0xFFFFFFFF).astype(np.int32)
+            g[HS_GATE_TABLE:HS_GATE_TABLE + 17] = table
+            self.gate = _dev(g)
+        self._structs()
+
+    @staticmethod
+    def gate_table(ms, rows, k_bar: float, b_max: int):
+        return hs_gate_table_build(ms, rows, k_bar, b_max)
 
     def poll_error(self) -> int:
         return hs_poll_error(self.ctx, self.stream())

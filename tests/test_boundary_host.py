@@ -126,3 +126,25 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(hs, "LIB_PATH", "/nonexistent/libhistospec.so")
     with pytest.raises(RuntimeError, match="only implementation"):
         hs.lib()
+
+
+def test_gate_table_host_helper_equals_the_oracle():
+    """hs_gate_table_build is host arithmetic (no device work): the table from a profiled step time must be the
+    oracle's for the same points, on an affine profile, one with a plateau and a measured-looking one; bad
+    profiles are rejected."""
+    import numpy as np
+    import oracle
+    cases = [
+        (np.array([1, 64, 512, 4096, 40000], np.int32), lambda r: 18.0 + 0.011 * r, 8.0, 4096),
+        (np.array([1, 300, 3000], np.int32), lambda r: np.where(r <= 300, 10.0, 10.0 + (r - 300) / 30.0), 4.0, 1000),
+        (np.array([128, 256, 640, 1152, 2176], np.int32), lambda r: 18.4 + 0.0001 * r + 2e-6 * r * r, 3.5, 512),
+        (np.array([8, 4096], np.int32), lambda r: 1.0 + 0.5 * r, 2.25, 64),
+    ]
+    for rows, f, k_bar, b_max in cases:
+        ms = f(rows.astype(np.float64)).astype(np.float32)
+        got = hs.hs_gate_table_build(ms, rows, k_bar, b_max)
+        assert got == oracle.gate_table(ms, rows, k_bar, b_max).tolist(), (rows, got)
+    with pytest.raises(hs.HsError):
+        hs.hs_gate_table_build([1.0], [4], 2.0, 8)
+    with pytest.raises(hs.HsError):
+        hs.hs_gate_table_build([1.0, 2.0, 3.0], [4, 4, 9], 2.0, 8)

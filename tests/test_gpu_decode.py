@@ -8,20 +8,31 @@ import pytest
 import torch
 
 import oracle
-from hs_inputs import CONFIG_SHAPES, ModelShape, make_weights, rope_table, make_prompts, config_seed
+from hs_inputs import (CONFIG_SHAPES, ModelShape, make_weights, rope_table, make_prompts, config_seed, mutate,
+                       history_with_context)
 from gpu_common import LOGIT_TOL, OracleBatch, make_histories, np_of, top2_margin
 
 pytestmark = pytest.mark.gpu
 
 
-def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=()):
-    """Run until every budget is spent.  Returns statistics."""
+def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=(), gate=None):
+    """Run until every budget is spent.  Returns statistics.  gate: the oracle's copy of the speculation gate's
+    words (the engine holds its own); the oracle decides each step from the oracle-side totals, and a step it
+    switches off must come out of the HIP path as one row per live sequence."""
+    import dataclasses
     B = len(ob.x)
-    stats = dict(steps=0, accepted=0, emitted=0, flagged=0, max_logit_err=0.0, rows=0)
+    stats = dict(steps=0, accepted=0, emitted=0, flagged=0, max_logit_err=0.0, rows=0, drafted=0, off_steps=0)
+    pol_on = pol
+    pol_off = dataclasses.replace(pol, k_mode=oracle.K_FIXED, k_fixed=0)
     for _ in range(max_steps):
         if all(b <= 0 for b in ob.budget):
             break
-        eng.step(pol)
+        if gate is not None:
+            live = sum(b > 0 for b in ob.budget)
+            on = oracle.gate_step(gate, live, stats["drafted"], stats["accepted"])
+            pol = pol_on if on else pol_off
+            stats["off_steps"] += not on
+        eng.step(pol_on)
         torch.cuda.synchronize()
         assert eng.poll_error() == 0
         st = {k: np_of(v) for k, v in eng.st.items()}
@@ -59,10 +70,11 @@ def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=()):
                 visited = set(path_o.tolist()) | set(path_g.tolist())
                 assert min(top2_margin(want[r]) for r in visited) <= LOGIT_TOL, (b, out_g, out_o)
                 stats["flagged"] += 1
-            ob.commit(b, tree, a_g, out_g, path_g, pol)   # the oracle follows the GPU's tokens
+            ob.commit(b, tree, a_g, out_g, path_g, pol_on)   # the oracle follows the GPU's tokens
             stats["accepted"] += a_g
             stats["emitted"] += int(n)
             stats["rows"] += len(tree["tok"])
+            stats["drafted"] += len(tree["tok"]) - 1
         # state after commit
         assert np_of(eng.seq_len)[:B].tolist() == [len(x) for x in ob.x]
         assert np_of(eng.budget_left)[:B].tolist() == ob.budget
@@ -70,8 +82,14 @@ def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=()):
         for b in range(B):
             m = min(len(ob.x[b]), eng.w_max)
             assert tl[b] == m and tail[b, eng.w_max - m:].tolist() == ob.x[b][-m:]
-        if pol.k_mode == oracle.K_AIMD:
+        if pol_on.k_mode == oracle.K_AIMD:
             assert np_of(eng.k_state)[:B].tolist() == ob.k_state
+        if gate is not None:
+            assert np_of(eng.gate).tolist() == gate.tolist()
+            c = np_of(eng.counters)
+            assert (int(c[1]), int(c[2])) == (stats["drafted"], stats["accepted"])
+            if not on:
+                assert int(ro[B]) == live and not st["draft_len"][:B * len(cands[0])].any()
         stats["steps"] += 1
     toks = np_of(eng.tokens)
     for b in range(B):
@@ -220,6 +238,42 @@ def test_speculative_equals_autoregressive_bitwise_on_gpu(config1):
         assert outs[0][0][b, 64:].tolist() == rolls[b].tolist()
     assert outs[0][1] == 256 and outs[1][1] < 200
     assert outs[0][2][2] == 0 and outs[1][2][2] > 300   # accepted-token counters
+
+
+@pytest.mark.parametrize("k_mode", ["fixed", "aimd"])
+def test_speculation_gate_lockstep(config1, k_mode):
+    """Throughput-aware speculation control (Sec. 5.4, last paragraph): histories that are accurate for the first
+    80 tokens and 40 % wrong afterwards, ragged budgets.  The gate's table lets speculation run at any rate once one
+    sequence is left, and for up to four only from rate bucket 10 (62 %) on; it probes every 5 steps.  Every word of
+    the gate, every decision and the rows of every step must equal the oracle's."""
+    from paper_2508_18588_amd import HS_K_AIMD, HS_K_FIXED
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    shape, w, rope, model, prompts, rollouts = config1
+    rng = np.random.default_rng(4242)
+    cands = []
+    for b in range(4):
+        r = np.asarray(rollouts[b], np.int32)
+        h = np.concatenate([mutate(r[:80], 0.03, 0.0, shape.vocab, rng), mutate(r[80:], 0.40, 0.0, shape.vocab, rng)])
+        cands.append([history_with_context(prompts[b], h, 8)])
+    pol = Policy(window=8, m_min=2, k_mode=HS_K_AIMD if k_mode == "aimd" else HS_K_FIXED, k_fixed=4, k_max=8,
+                 aimd_cap=8)
+    budgets = [256, 200, 150, 110]
+    table = [1] * 10 + [4] * 7
+    eng = Engine(shape, w, rope, max_batch=4, k_max=8, c_max=1, max_len=64 + 256, shuffle_pages_seed=11)
+    eng.load_sequences(list(prompts), budgets=budgets)
+    eng.set_history(cands)
+    eng.prefill(list(prompts))
+    eng.set_gate(table, probe_every=5)
+    gate = np.zeros(32, np.int32)
+    gate[4] = 5
+    gate[8:25] = table
+    ob = OracleBatch(model, list(prompts), budgets, 64 + 256 + 16)
+    stats = lockstep(eng, ob, cands, pol, max_steps=600, gate=gate)
+    eng.close()
+    print("gate", k_mode, stats, gate[:8].tolist())
+    assert stats["emitted"] == sum(budgets)
+    assert 20 <= stats["off_steps"] <= stats["steps"] - 20      # both states were held for a while
+    assert stats["accepted"] > 40
 
 
 def test_tree_drafts_two_candidates_lockstep(config1):
