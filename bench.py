@@ -252,6 +252,9 @@ def main():
                    "acceptance_rate": round(accepted / max(1, drafted), 3),
                    "autoregressive_tokens_per_s": round(B / ar_ms * 1e3, 1),
                    "speedup_vs_autoregressive": round((emitted / elapsed) / (B / ar_ms * 1e3), 3),
+                   # Sec. 5.4 (throughput-aware control): drafting pays while the acceptance rate stays above this
+                   "break_even_acceptance_rate": round(max(0.0, ms_per_step / ar_ms - 1.0) * seq_steps
+                                                       / max(1, drafted), 3),
                    "kv_resident_gb": round(float(len0.sum()) * kv_tok_bytes * n_layers / 1e9, 1), **extras},
         "roofline": roofline, "cpu_baseline": cpu,
     }
