@@ -235,6 +235,26 @@ hs_status hs_draft_group(hs_ctx* ctx, const hs_group_draft_args* args, const hs_
  * step.argmax and the logits (step.logits, or the workspace if NULL). */
 hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* seq, hs_step* step, hs_stream stream);
 
+/* Chunked prefill: recomputes the KV cache of text that already exists -- the prompt, or the prompt plus the tokens a
+ * migrated / deferred rollout had generated before it was moved (Sec. 6.3: such rollouts keep their tokens and
+ * continue after the cache has been recomputed rather than transferred).  One call pushes, for every sequence, its
+ * next min(chunk, seq_len[b] - 1 - kv_done[b]) tokens from the token log seq.tokens (positions kv_done[b]...)
+ * through the decoder: token i attends to positions [0, kv_done[b] + i], its K/V go to slot kv_done[b] + i of every
+ * layer, and kv_done[b] advances.  (The newest token, position seq_len - 1, is the root of the next hs_verify and is
+ * never prefilled.)  Sequences are served in index order until max_rows rows are laid out; one that does not fit
+ * entirely gets the rows that are left, later ones none: call again until kv_done[b] == seq_len[b] - 1 for all b
+ * (ceil(total tokens / max_rows) calls at least; the host knows the lengths).  No logits are computed.
+ * Overwrites step.row_off / tok / pos / parent / row2seq (the other step arrays are not touched).  The result at a
+ * position does not depend on how the text is cut into chunks or calls. */
+enum { HS_PREFILL_CHUNK_MAX = 1024 };
+typedef struct hs_prefill_args {
+    int32_t chunk;      /* HOST: at most this many tokens per sequence and call, 1..HS_PREFILL_CHUNK_MAX */
+    int32_t rows_hint;  /* HOST: rows expected in this call (launch shapes only), 0 = unknown */
+    int32_t* kv_done;   /* DEVICE [batch] in/out: positions of sequence b already in the cache */
+} hs_prefill_args;
+hs_status hs_prefill(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* seq, hs_step* step,
+                     const hs_prefill_args* args, hs_stream stream);
+
 /* Acceptance (Sec. 2.2).  Greedy: follow children whose token equals the parent's argmax.  Rejection: accept
  * child j at a node with probability p(tok), p = softmax(logits/temperature) with earlier rejected tokens
  * removed; finish with one inverse-CDF sample (token-id order).  Uniforms: Philox-4x32-10, key = seed, counter

@@ -110,9 +110,16 @@ class hs_accept_args(C.Structure):
     _fields_ = [("mode", C.c_int32), ("temperature", C.c_float), ("seed", C.c_uint64)]
 
 
+class hs_prefill_args(C.Structure):
+    _fields_ = [("chunk", C.c_int32), ("rows_hint", C.c_int32), ("kv_done", C.c_void_p)]
+
+
+HS_PREFILL_CHUNK_MAX = 1024
+
+
 EXPORTS = ("hs_create", "hs_destroy", "hs_last_error", "hs_set_flags", "hs_workspace_bytes", "hs_bind_workspace",
            "hs_draft", "hs_draft_group", "hs_verify", "hs_accept", "hs_kv_commit", "hs_poll_error", "hs_debug_buffer",
-           "hs_set_profile", "hs_get_profile", "hs_debug_gemm", "hs_gate_table_build")
+           "hs_set_profile", "hs_get_profile", "hs_debug_gemm", "hs_gate_table_build", "hs_prefill")
 
 _lib = None
 
@@ -142,6 +149,8 @@ def lib():
         L.hs_draft_group.argtypes = [vp, C.POINTER(hs_group_draft_args), C.POINTER(hs_seq_state), C.POINTER(hs_step),
                                      vp]
         L.hs_verify.argtypes = [vp, C.POINTER(hs_kv_cache), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
+        L.hs_prefill.argtypes = [vp, C.POINTER(hs_kv_cache), C.POINTER(hs_seq_state), C.POINTER(hs_step),
+                                 C.POINTER(hs_prefill_args), vp]
         L.hs_accept.argtypes = [vp, C.POINTER(hs_accept_args), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
         L.hs_kv_commit.argtypes = [vp, C.POINTER(hs_kv_cache), C.POINTER(hs_seq_state), C.POINTER(hs_step),
                                    C.POINTER(hs_policy), vp]
@@ -204,6 +213,10 @@ def hs_draft_group(ctx, args: hs_group_draft_args, seq: hs_seq_state, step: hs_s
 
 def hs_verify(ctx, cache: hs_kv_cache, seq: hs_seq_state, step: hs_step, stream=None):
     _check(ctx, lib().hs_verify(ctx, C.byref(cache), C.byref(seq), C.byref(step), stream))
+
+
+def hs_prefill(ctx, cache: hs_kv_cache, seq: hs_seq_state, step: hs_step, args: hs_prefill_args, stream=None):
+    _check(ctx, lib().hs_prefill(ctx, C.byref(cache), C.byref(seq), C.byref(step), C.byref(args), stream))
 
 
 def hs_accept(ctx, args: hs_accept_args, seq: hs_seq_state, step: hs_step, stream=None):

@@ -45,6 +45,7 @@ void layout_workspace(hs_ctx* ctx) {
                                  (size_t)hs_gemm_chunks(d.d_model, d.d_ffn) * d.d_model});
     w.gemm_part_bytes = M * part_cols * 4;
     w.gemm_part = take(w.gemm_part_bytes);
+    w.pf_len = take((size_t)l.max_batch * 4);
     w.total = off;
 }
 
@@ -312,6 +313,57 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
         ctx->ev_last = whole_slot + 1;
     }
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_verify", e);
+    return HS_OK;
+}
+
+hs_status hs_prefill(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* seq, hs_step* step,
+                     const hs_prefill_args* args, hs_stream stream) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
+    if (!cache_ok(cache)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_prefill: cache");
+    if (!seq_ok(ctx, seq) || !seq->tokens) return fail(ctx, HS_ERR_INVALID_ARG, "hs_prefill: sequence state / token log");
+    if (!step || !step->row_off || !step->tok || !step->pos || !step->parent || !step->row2seq)
+        return fail(ctx, HS_ERR_INVALID_ARG, "hs_prefill: step arrays");
+    if (!args || !args->kv_done || args->chunk < 1 || args->chunk > HS_PREFILL_CHUNK_MAX)
+        return fail(ctx, HS_ERR_INVALID_ARG, "hs_prefill: arguments");
+    if (ctx->flags & HS_FLAG_REFERENCE_KERNELS) return fail(ctx, HS_ERR_UNSUPPORTED, "hs_prefill: no plain-kernel mode");
+    hipStream_t st = (hipStream_t)stream;
+    const hs_model_desc& d = ctx->desc;
+    const int m_max = ctx->lim.max_rows;
+    const int32_t* m_dev = step->row_off + seq->batch;
+    float* x = (float*)(ctx->ws + ctx->lay.x);
+    bf16_t* xn = (bf16_t*)(ctx->ws + ctx->lay.xn);
+    float* qkv = (float*)(ctx->ws + ctx->lay.qkv);
+    bf16_t* q = (bf16_t*)(ctx->ws + ctx->lay.q);
+    bf16_t* attn = (bf16_t*)(ctx->ws + ctx->lay.attn);
+    bf16_t* act = (bf16_t*)(ctx->ws + ctx->lay.act);
+    int32_t* len_plus1 = (int32_t*)(ctx->ws + ctx->lay.pf_len);
+    const int qh = d.n_q_heads * d.head_dim;
+    const int nqkv = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
+    const int hint = args->rows_hint > 0 ? args->rows_hint : m_max;
+    // the row kernels place a row at slot (sequence length - 1 + its index): here that is kv_done + i
+    hs_seq_state pf = *seq;
+    pf.seq_len = len_plus1;
+
+    (void)hipGetLastError();
+    hs_launch_prefill_rows(ctx, seq, args->kv_done, args->chunk, step, len_plus1, st);
+    hs_launch_embed(ctx, step, seq->batch, x, st);
+    int pend = 0;
+    for (int l = 0; l < d.n_layers; l++) {
+        hs_launch_rmsnorm(ctx, x, ctx->norm1[l], xn, m_dev, pend, st);
+        hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->wqkv[l], nullptr, qkv, m_dev, m_max, nqkv, d.d_model, hint, st,
+                       &pend);
+        hs_launch_rope_kv(ctx, l, cache, &pf, step, qkv, q, pend, st);
+        pend = 0;
+        if (l + 1 == d.n_layers) break;   // the last layer's K/V are written: nothing downstream is needed
+        hs_launch_attention_prefill(ctx, l, cache, &pf, len_plus1, step, q, attn, args->chunk, st);
+        hs_launch_gemm(ctx, HS_EPI_ADD_F32, attn, ctx->wo[l], nullptr, x, m_dev, m_max, d.d_model, qh, hint, st, &pend);
+        hs_launch_rmsnorm(ctx, x, ctx->norm2[l], xn, m_dev, pend, st);
+        hs_launch_gemm(ctx, HS_EPI_SWIGLU_BF16, xn, ctx->wgate[l], ctx->wup[l], act, m_dev, m_max, d.d_ffn, d.d_model, hint, st);
+        hs_launch_gemm(ctx, HS_EPI_ADD_F32, act, ctx->wdown[l], nullptr, x, m_dev, m_max, d.d_model, d.d_ffn, hint, st,
+                       &pend);
+    }
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_prefill", e);
     return HS_OK;
 }
 

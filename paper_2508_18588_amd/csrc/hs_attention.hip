@@ -38,7 +38,9 @@ __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 // One 32-key sub-tile for one 32-row query tile: S^T = K.Q^T, online softmax per lane, O^T += V^T.P^T.
 // sK points at the sub-tile's 32 key rows, sV at its two 16-token pages.  Every query row's arithmetic is
 // independent of which other rows are in flight.
-template <int HD>
+// CHAIN (prefill): the rows are consecutive tokens; L is then a position below which every row of the tile sees every
+// key and `total` the lane's own bound (keys < total are visible), no ancestor mask.
+template <int HD, bool CHAIN = false>
 __device__ inline void attn_subtile(const bf16_t* sK, const bf16_t* sV, const bf16x8 (&qf)[HD / 16],
                                     f32x16 (&o)[HD / 32], float& m_run, float& l_run, uint64_t anc, int kbase, int L,
                                     int total, float scale_log2, int half, int l32) {
@@ -57,7 +59,7 @@ __device__ inline void attn_subtile(const bf16_t* sK, const bf16_t* sV, const bf
 #pragma unroll
         for (int e = 0; e < 16; e++) {
             int kp = kbase + 8 * (e >> 2) + 4 * half + (e & 3);
-            bool vis = kp < L || (kp < total && ((anc >> (kp - L)) & 1ull));
+            bool vis = kp < L || (kp < total && (CHAIN || ((anc >> (kp - L)) & 1ull)));
             s[e] = vis ? s[e] : -INFINITY;
         }
     }
@@ -124,7 +126,7 @@ __device__ inline void load_query_tile(const bf16_t* q, const uint64_t* anc_mask
     bool ok = rho < R;
     int node = ok ? rho / G : 0;
     int g = ok ? rho - node * G : 0;
-    anc = ok ? anc_mask[r0 + node] : 0ull;
+    anc = (ok && anc_mask) ? anc_mask[r0 + node] : 0ull;
     const bf16_t* qp = q + ((size_t)(r0 + node) * hq + j * G + g) * HD;
 #pragma unroll
     for (int ks = 0; ks < HD / 16; ks++) {
@@ -334,6 +336,123 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
     }
 }
 
+// Prefill of a chunk of consecutive tokens per sequence (KV recomputation of a resumed rollout): token i of the chunk
+// attends to positions [0, L + i].  One workgroup per (block of 256 query rows, KV head, sequence) walks the keys
+// from position 0 in 64-key tiles -- a row's arithmetic depends on absolute key positions only, not on how the text
+// was cut into chunks -- and writes the normalised output itself: with hundreds of rows per sequence there is
+// enough parallelism without cutting the key axis.  Row tiles of 32 rows (rows of one token's G query heads are
+// adjacent) are dealt to the four wavefronts, two each; a row tile skips the key tiles that lie wholly behind it.
+template <int HD>
+__global__ __launch_bounds__(256, 1) void attn_prefill_mfma(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc, size_t layer_off,
+    const int32_t* __restrict__ len_plus1, const int32_t* __restrict__ block_table, int max_blocks, int n_blocks,
+    const int32_t* __restrict__ row_off, bf16_t* __restrict__ out, int hq, int hkv, float scale_log2) {
+    constexpr int KS = HD + 8, VS = 20, NKS = HD / 16, NDT = HD / 32, RTW = 2, TILE = 64, NCK = HD / 32;
+    __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];
+    __shared__ __attribute__((aligned(16))) bf16_t sV[4 * HD * VS];
+
+    const int j = blockIdx.y, b = blockIdx.z;
+    const int r0 = row_off[b];
+    const int nn = row_off[b + 1] - r0;
+    if (nn <= 0) return;
+    const int L = len_plus1[b] - 1;
+    const int total = L + nn;
+    const int G = hq / hkv;
+    const int R = nn * G;
+    const int row_base = blockIdx.x * (128 * RTW);
+    if (row_base >= R) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int32_t* bt = block_table + (size_t)b * max_blocks;
+    const bf16_t* kbase_ptr = kc + layer_off + (size_t)j * 16 * HD;
+    const bf16_t* vbase_ptr = vc + layer_off + (size_t)j * HD * 16;
+    const size_t page_stride = (size_t)hkv * 16 * HD;
+    // keys this block needs: up to the position of its last row's token
+    const int last_node = min(nn - 1, (min(R, row_base + 128 * RTW) - 1) / G);
+    const int k_end = L + last_node + 1;
+
+    bf16x8 qf[RTW][NKS];
+    f32x16 o[RTW][NDT];
+    float m_run[RTW], l_run[RTW];
+    int lim_lane[RTW], lim_min[RTW], lim_max[RTW];
+    bool rt_on[RTW];
+#pragma unroll
+    for (int t = 0; t < RTW; t++) {
+        const int rt = blockIdx.x * (4 * RTW) + wave + 4 * t;
+        rt_on[t] = rt * 32 < R;
+        uint64_t unused;
+        load_query_tile<HD>(q, nullptr, r0, rt_on[t] ? rt : 0, rt_on[t] ? R : 0, G, hq, j, half, l32, qf[t], unused);
+        const int rho = rt * 32 + l32;
+        lim_lane[t] = (rt_on[t] && rho < R) ? L + rho / G + 1 : 0;
+        lim_min[t] = L + (rt * 32) / G + 1;
+        lim_max[t] = L + min(nn - 1, (rt * 32 + 31) / G) + 1;
+#pragma unroll
+        for (int dt = 0; dt < NDT; dt++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) o[t][dt][e] = 0.f;
+        m_run[t] = -INFINITY;
+        l_run[t] = 0.f;
+    }
+
+    u32x4 rk[NCK], rv[NCK];
+    const int wave_c0 = tid & ~63;
+#define HS_P_FETCH(KB)                                                                                            \
+    {                                                                                                             \
+        _Pragma("unroll") for (int i = 0; i < NCK; i++) {                                                         \
+            const int kk = (wave_c0 + 256 * i) / (2 * HD);                                                        \
+            const int within = (tid + 256 * i) % (2 * HD);                                                        \
+            const size_t pofs = (size_t)safe_page(bt, (KB) + 16 * kk, total, max_blocks, n_blocks) * page_stride; \
+            rk[i] = *reinterpret_cast<const u32x4*>(kbase_ptr + pofs + within * 8);                               \
+            rv[i] = *reinterpret_cast<const u32x4*>(vbase_ptr + pofs + within * 8);                               \
+        }                                                                                                         \
+    }
+    HS_P_FETCH(0)
+    for (int kbase = 0; kbase < k_end; kbase += TILE) {
+        __syncthreads();  // previous tile fully consumed
+#pragma unroll
+        for (int i = 0; i < NCK; i++) {
+            const int kk = (wave_c0 + 256 * i) / (2 * HD);
+            const int within = (tid + 256 * i) % (2 * HD);
+            int key = kk * 16 + within / (HD / 8), c16 = within % (HD / 8);
+            *reinterpret_cast<u32x4*>(&sK[key * KS + c16 * 8]) = rk[i];
+            int dim = within >> 1, hf = within & 1;
+            u32x2* dst = reinterpret_cast<u32x2*>(&sV[(kk * HD + dim) * VS + hf * 8]);
+            dst[0] = u32x2{rv[i].x, rv[i].y};
+            dst[1] = u32x2{rv[i].z, rv[i].w};
+        }
+        __syncthreads();
+        if (kbase + TILE < k_end) HS_P_FETCH(kbase + TILE)
+#pragma unroll
+        for (int sub = 0; sub < 2; sub++) {
+            const int kb = kbase + 32 * sub;
+#pragma unroll
+            for (int t = 0; t < RTW; t++) {
+                if (!rt_on[t] || kb >= lim_max[t]) continue;   // wavefront-uniform: nothing of this sub-tile is visible
+                attn_subtile<HD, true>(sK + sub * 32 * KS, sV + sub * 2 * HD * VS, qf[t], o[t], m_run[t], l_run[t], 0ull,
+                                       kb, lim_min[t], lim_lane[t], scale_log2, half, l32);
+            }
+        }
+    }
+#undef HS_P_FETCH
+#pragma unroll
+    for (int t = 0; t < RTW; t++) {
+        const int rho = (blockIdx.x * (4 * RTW) + wave + 4 * t) * 32 + l32;
+        if (!rt_on[t] || rho >= R) continue;
+        const int node = rho / G, g = rho - node * G;
+        const float inv = 1.f / l_run[t];     // a row always sees its own key: the sum is positive
+        bf16_t* po = out + ((size_t)(r0 + node) * hq + j * G + g) * HD;
+#pragma unroll
+        for (int dt = 0; dt < NDT; dt++)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; g4++) {
+                u32x2 w;
+                w.x = (uint32_t)f32_to_bf16(o[t][dt][4 * g4] * inv) | ((uint32_t)f32_to_bf16(o[t][dt][4 * g4 + 1] * inv) << 16);
+                w.y = (uint32_t)f32_to_bf16(o[t][dt][4 * g4 + 2] * inv) | ((uint32_t)f32_to_bf16(o[t][dt][4 * g4 + 3] * inv) << 16);
+                *reinterpret_cast<u32x2*>(po + dt * 32 + 8 * g4 + 4 * half) = w;
+            }
+    }
+}
+
 // Combine the partitions of one (row, query head) in partition order: one wavefront per (row, head), four per
 // workgroup.  Lane p holds partition p's (max, sum); weights are broadcast from there.
 template <int HD>
@@ -459,6 +578,26 @@ void hs_launch_attention(const hs_ctx* ctx, int layer, const hs_kv_cache* cache,
         if (two) launch_mfma<64, 2>(ctx, layer_off, cache, seq, step, q, out, st);
         else launch_mfma<64, 1>(ctx, layer_off, cache, seq, step, q, out, st);
     }
+}
+
+void hs_launch_attention_prefill(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
+                                 const int32_t* len_plus1, const hs_step* step, const bf16_t* q, bf16_t* out, int chunk,
+                                 hipStream_t st) {
+    const hs_model_desc& d = ctx->desc;
+    const size_t layer_off = (size_t)layer * cache->n_blocks * d.n_kv_heads * 16 * d.head_dim;
+    const int G = d.n_q_heads / d.n_kv_heads;
+    const float scale_log2 = 1.4426950408889634f / sqrtf((float)d.head_dim);
+    dim3 grid((chunk * G + 255) / 256, d.n_kv_heads, seq->batch);
+    if (d.head_dim == 128)
+        hipLaunchKernelGGL((attn_prefill_mfma<128>), grid, dim3(256), 0, st, q, (const bf16_t*)cache->k,
+                           (const bf16_t*)cache->v, layer_off, len_plus1, seq->block_table,
+                           ctx->lim.max_blocks_per_seq, cache->n_blocks, step->row_off, out, d.n_q_heads, d.n_kv_heads,
+                           scale_log2);
+    else
+        hipLaunchKernelGGL((attn_prefill_mfma<64>), grid, dim3(256), 0, st, q, (const bf16_t*)cache->k,
+                           (const bf16_t*)cache->v, layer_off, len_plus1, seq->block_table,
+                           ctx->lim.max_blocks_per_seq, cache->n_blocks, step->row_off, out, d.n_q_heads, d.n_kv_heads,
+                           scale_log2);
 }
 
 void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, bf16_t* out,

@@ -183,7 +183,75 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
     }
 }
 
+// Rows of one prefill call: sequence b contributes its next n_b = min(chunk, seq_len - 1 - kv_done) tokens (taken
+// from its token log), sequences served in index order until max_rows rows are laid out.  One workgroup.
+// len_plus1[b] = kv_done[b] + 1 before the call (the later kernels' "sequence length": cached positions + 1);
+// kv_done advances by n_b.
+__global__ __launch_bounds__(256) void prefill_rows_kernel(
+    const int32_t* __restrict__ seq_len, int32_t* __restrict__ kv_done, const int32_t* __restrict__ tokens,
+    int tokens_stride, int batch, int chunk, int max_rows, int max_pos, int32_t* __restrict__ row_off,
+    int32_t* __restrict__ tok, int32_t* __restrict__ pos, int32_t* __restrict__ parent, int32_t* __restrict__ row2seq,
+    int32_t* __restrict__ len_plus1, uint32_t* __restrict__ err) {
+    __shared__ int sw[4];
+    __shared__ int carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int b0 = 0; b0 < batch; b0 += 256) {
+        const int b = b0 + threadIdx.x;
+        int want = 0, done = 0;
+        if (b < batch) {
+            done = max(kv_done[b], 0);
+            want = max(0, min(chunk, seq_len[b] - 1 - done));
+            if (done + want > max_pos) {        // rotary table too short: nothing of this sequence is laid out
+                atomicOr(err, (uint32_t)HS_DEV_POSITION_OVERFLOW);
+                want = 0;
+            }
+        }
+        int incl = want;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            int t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) sw[wave] = incl;
+        __syncthreads();
+        int before = carry_s;
+        for (int w2 = 0; w2 < wave; w2++) before += sw[w2];
+        const int start = before + incl - want;
+        if (b < batch) {
+            const int s0 = min(start, max_rows);
+            const int n = max(0, min(want, max_rows - s0));
+            row_off[b] = s0;
+            len_plus1[b] = done + 1;
+            kv_done[b] = done + n;
+        }
+        __syncthreads();
+        if (threadIdx.x == 255) carry_s = before + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) row_off[batch] = min(carry_s, max_rows);
+    __syncthreads();   // this workgroup's row_off / len_plus1 writes are visible to all its threads
+    for (int b = 0; b < batch; b++) {
+        const int s0 = row_off[b], n = row_off[b + 1] - s0, done = len_plus1[b] - 1;
+        for (int i = threadIdx.x; i < n; i += 256) {
+            tok[s0 + i] = tokens[(size_t)b * tokens_stride + done + i];
+            pos[s0 + i] = done + i;
+            parent[s0 + i] = i - 1;
+            row2seq[s0 + i] = b;
+        }
+    }
+}
+
 }  // namespace
+
+void hs_launch_prefill_rows(const hs_ctx* ctx, const hs_seq_state* seq, int32_t* kv_done, int chunk, hs_step* step,
+                            int32_t* len_plus1, hipStream_t st) {
+    hipLaunchKernelGGL(prefill_rows_kernel, dim3(1), dim3(256), 0, st, seq->seq_len, kv_done, seq->tokens,
+                       seq->tokens_stride, seq->batch, chunk, ctx->lim.max_rows, ctx->lim.max_pos, step->row_off,
+                       step->tok, step->pos, step->parent, step->row2seq, len_plus1,
+                       reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.err));
+}
 
 void hs_launch_embed(const hs_ctx* ctx, const hs_step* step, int batch, float* x, hipStream_t st) {
     hipLaunchKernelGGL(embed_kernel, dim3(ctx->lim.max_rows), dim3(256), 0, st, ctx->embed, step->tok,

@@ -18,7 +18,7 @@ constexpr int HS_DRAFT_SEG = 4096;
 constexpr int HS_MAX_NODES = 64;  // ancestor masks are 64-bit
 
 struct hs_workspace_layout {
-    size_t x, xn, qkv, q, attn, act, part_o, part_ml, logits, draft_best, gemm_part, gemm_part_bytes, err, total;
+    size_t x, xn, qkv, q, attn, act, part_o, part_ml, logits, draft_best, gemm_part, gemm_part_bytes, err, pf_len, total;
 };
 
 struct hs_ctx {
@@ -85,6 +85,13 @@ void hs_launch_rope_kv(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, c
                        const hs_step* step, const float* qkv, bf16_t* q, int pending_chunks, hipStream_t st);
 void hs_launch_attention(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
                          const hs_step* step, const bf16_t* q, bf16_t* out, hipStream_t st);
+// Chunked prefill: row arrays of one call (rows of sequence b = its next tokens from the token log) and the causal
+// attention over [0, kv_done + i] for token i of the chunk.  len_plus1[b] = cached positions + 1.
+void hs_launch_prefill_rows(const hs_ctx* ctx, const hs_seq_state* seq, int32_t* kv_done, int chunk, hs_step* step,
+                            int32_t* len_plus1, hipStream_t st);
+void hs_launch_attention_prefill(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
+                                 const int32_t* len_plus1, const hs_step* step, const bf16_t* q, bf16_t* out, int chunk,
+                                 hipStream_t st);
 void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, bf16_t* out,
                                hipStream_t st);
 void hs_launch_argmax(const hs_ctx* ctx, const float* logits, int32_t* argmax, const int32_t* m_dev,

@@ -12,7 +12,7 @@ import torch
 
 from . import (HS_ACCEPT_GREEDY, HS_GATE_TABLE, HS_GATE_WORDS, HS_K_FIXED, hs_gate_table_build, hs_accept, hs_accept_args, hs_bind_workspace, hs_create, hs_debug_buffer, hs_debug_gemm,
                hs_destroy, hs_draft, hs_draft_args, hs_draft_group, hs_group_draft_args, hs_get_profile, hs_kv_cache, hs_kv_commit, hs_limits,
-               hs_model_desc, hs_policy, hs_poll_error, hs_seq_state, hs_set_flags, hs_set_profile, hs_step,
+               hs_model_desc, hs_policy, hs_poll_error, hs_prefill, hs_prefill_args, hs_seq_state, hs_set_flags, hs_set_profile, hs_step,
                hs_verify, hs_weights, hs_workspace_bytes)
 
 
@@ -50,14 +50,15 @@ class Engine:
 
     def __init__(self, shape, weights: dict, rope, max_batch: int, k_max: int, c_max: int, max_len: int,
                  w_max: int = 32, seq_caps=None, shuffle_pages_seed: int | None = None, n_layers: int | None = None,
-                 keep_logits: bool = True, g_max: int = 0):
+                 keep_logits: bool = True, g_max: int = 0, max_rows: int | None = None):
         self.shape = shape
         self.dev = torch.device("cuda:0")
         L = len(weights["wqkv"]) if n_layers is None else n_layers
         self.n_layers = L
         self.max_batch, self.k_max, self.c_max, self.w_max = max_batch, k_max, c_max, w_max
         nodes = 1 + c_max * k_max
-        self.max_rows = max_batch * nodes
+        # rows of one call: a verify step needs max_batch * nodes; a larger value lets hs_prefill take bigger bites
+        self.max_rows = max(max_batch * nodes, max_rows or 0)
         # ---- weights
         self.w = {k: ([_dev(x) for x in v] if isinstance(v, list) else _dev(v)) for k, v in weights.items()}
         self.rope = _dev(rope)
@@ -174,6 +175,7 @@ class Engine:
         self.tail.copy_(torch.from_numpy(tail))
         self.tail_len.copy_(torch.from_numpy(tl))
         self.seq_len.copy_(torch.from_numpy(sl))
+        self._lens = sl.astype(np.int64)
         bl = np.zeros(self.max_batch, np.int32)
         bl[:B] = budgets
         self.budget_left.copy_(torch.from_numpy(bl))
@@ -344,6 +346,28 @@ class Engine:
             self.verify()
         self.seq_len.copy_(saved)
         torch.cuda.synchronize()
+
+    def prefill_chunked(self, chunk: int = 512, kv_done=None):
+        """Recompute the cache of every loaded sequence's committed text (all tokens but the newest) with hs_prefill,
+        `chunk` tokens per sequence and call; kv_done = positions already cached (default none).  Returns the number
+        of calls.  The lengths are host knowledge (load_sequences), so no device value is read back."""
+        B = self.batch
+        todo = np.maximum(self._lens[:B] - 1 - (np.zeros(B, np.int64) if kv_done is None else np.asarray(kv_done)), 0)
+        self.kv_done = torch.zeros(self.max_batch, dtype=torch.int32, device=self.dev)
+        if kv_done is not None:
+            self.kv_done[:B].copy_(torch.as_tensor(np.asarray(kv_done, np.int32)))
+        calls = 0
+        while todo.sum() > 0:
+            # the library serves sequences in index order until max_rows rows are laid out: mirror that here
+            left = self.max_rows
+            for b in range(B):
+                n = int(min(chunk, todo[b], left))
+                todo[b] -= n
+                left -= n
+            args = hs_prefill_args(int(chunk), int(self.max_rows - left), self.kv_done.data_ptr())
+            hs_prefill(self.ctx, self.c_cache, self.c_seq, self.c_step, args, self.stream())
+            calls += 1
+        return calls
 
     def debug_tensor(self, which: int):
         """0 final hidden (bf16 bits), 1 queries, 2 attention output, 3 workspace logits -- as flat torch views."""

@@ -56,6 +56,25 @@ class OracleBatch:
         self.budget[b] -= len(out)
 
 
+def check_cache(eng, ob, layer, every=None):
+    """Cache contents at [0, L) must equal the K/V the oracle computed for the committed tokens (K and V have the
+    logits' scale 0.02 sqrt(d_model), so the logit tolerance applies)."""
+    shape = eng.shape
+    hkv, h = shape.n_kv_heads, shape.head_dim
+    kc = np_of(eng.kc).view(np.uint16).reshape(eng.n_layers, eng.n_blocks, hkv, 16, h)
+    vc = np_of(eng.vc).view(np.uint16).reshape(eng.n_layers, eng.n_blocks, hkv, h, 16)
+    bt = np_of(eng.block_table)
+    f = lambda bits: (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    for b, s in enumerate(ob.seqs):
+        for pos in range(0, len(s), every or max(1, len(s) // 40)):
+            k, v = s.kv(layer, pos)
+            page, ip = bt[b, pos // 16], pos % 16
+            gk = f(kc[layer, page, :, ip, :]).reshape(-1)
+            gv = f(vc[layer, page, :, :, ip]).reshape(-1)
+            np.testing.assert_allclose(gk, k, atol=LOGIT_TOL, rtol=2e-2)
+            np.testing.assert_allclose(gv, v, atol=LOGIT_TOL, rtol=2e-2)
+
+
 def top2_margin(row):
     part = np.partition(row, -2)
     return float(part[-1] - part[-2])

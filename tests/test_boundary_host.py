@@ -34,6 +34,7 @@ def test_struct_sizes_match_the_header_layout():
     assert C.sizeof(hs.hs_step) == 17 * 8
     assert C.sizeof(hs.hs_group_draft_args) == 8 + 3 * 8 + 32
     assert C.sizeof(hs.hs_accept_args) == 16
+    assert C.sizeof(hs.hs_prefill_args) == 16
     assert C.sizeof(hs.hs_kv_cache) == 24
 
 

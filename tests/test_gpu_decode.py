@@ -10,7 +10,7 @@ import torch
 import oracle
 from hs_inputs import (CONFIG_SHAPES, ModelShape, make_weights, rope_table, make_prompts, config_seed, mutate,
                        history_with_context)
-from gpu_common import LOGIT_TOL, OracleBatch, make_histories, np_of, top2_margin
+from gpu_common import LOGIT_TOL, OracleBatch, check_cache, make_histories, np_of, top2_margin
 
 pytestmark = pytest.mark.gpu
 
@@ -97,25 +97,6 @@ def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=(), gate=None):
     for layer in check_kv_layers:
         check_cache(eng, ob, layer)
     return stats
-
-
-def check_cache(eng, ob, layer):
-    """Cache contents at [0, L) must equal the K/V the oracle computed for the committed tokens (K and V have the
-    logits' scale 0.02 sqrt(d_model), so the logit tolerance applies)."""
-    shape = eng.shape
-    hkv, h = shape.n_kv_heads, shape.head_dim
-    kc = np_of(eng.kc).view(np.uint16).reshape(eng.n_layers, eng.n_blocks, hkv, 16, h)
-    vc = np_of(eng.vc).view(np.uint16).reshape(eng.n_layers, eng.n_blocks, hkv, h, 16)
-    bt = np_of(eng.block_table)
-    f = lambda bits: (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
-    for b, s in enumerate(ob.seqs):
-        for pos in range(0, len(s), max(1, len(s) // 40)):
-            k, v = s.kv(layer, pos)
-            page, ip = bt[b, pos // 16], pos % 16
-            gk = f(kc[layer, page, :, ip, :]).reshape(-1)
-            gv = f(vc[layer, page, :, :, ip]).reshape(-1)
-            np.testing.assert_allclose(gk, k, atol=LOGIT_TOL, rtol=2e-2)
-            np.testing.assert_allclose(gv, v, atol=LOGIT_TOL, rtol=2e-2)
 
 
 def setup_rollout(shape, w, rope, B, prompt_len, n_new, seed):

@@ -1,0 +1,172 @@
+"""GPU parity of hs_prefill (chunked KV recomputation of text that already exists -- the prompt plus what a migrated
+rollout had generated, Sec. 6.3 of the paper) against the oracle's plain sequence forward: the K/V of every position
+and layer within the logit tolerance, the decode steps that follow within the same bars as everywhere else, and the
+cache bit-identical however the text is cut into chunks and calls."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from hs_inputs import CONFIG_SHAPES, ModelShape, make_weights, rope_table, config_seed
+from gpu_common import OracleBatch, check_cache, np_of
+from test_gpu_decode import lockstep
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def toy():
+    shape = CONFIG_SHAPES[1]
+    return shape, make_weights(shape, seed=config_seed(1)), rope_table(2048, shape.head_dim)
+
+
+def texts(rng, lens, vocab):
+    return [rng.integers(0, vocab, n).astype(np.int32) for n in lens]
+
+
+def run_prefill(shape, w, rope, toks, chunk, max_rows, kv_done=None, k_max=4, pages_seed=3):
+    from paper_2508_18588_amd.runtime import Engine
+    eng = Engine(shape, w, rope, max_batch=len(toks), k_max=k_max, c_max=1, max_len=max(len(t) for t in toks) + 16,
+                 shuffle_pages_seed=pages_seed, max_rows=max_rows)
+    eng.load_sequences(toks, budgets=[8] * len(toks))
+    calls = eng.prefill_chunked(chunk, kv_done)
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 0
+    return eng, calls
+
+
+@pytest.mark.parametrize("chunk,max_rows", [(512, 1400), (64, 200), (1024, 4000), (37, 111)])
+def test_prefill_cache_equals_oracle_and_decode_continues(toy, chunk, max_rows):
+    """Ragged batch (1 .. 1100 tokens; one sequence with nothing to prefill), several calls per batch because of
+    max_rows, row blocks with a ragged tail, chunks that straddle pages.  Every cached position of both layers is
+    compared with the oracle's sequence forward; then four plain decode steps run in lock-step."""
+    from paper_2508_18588_amd.runtime import Policy
+    shape, w, rope = toy
+    rng = np.random.default_rng(chunk)
+    lens = [1, 2, 17, 300, 1100, 65, 513]
+    toks = texts(rng, lens, shape.vocab)
+    eng, calls = run_prefill(shape, w, rope, toks, chunk, max_rows)
+    total = sum(n - 1 for n in lens)
+    assert calls >= -(-total // eng.max_rows)
+    assert np_of(eng.kv_done)[:len(lens)].tolist() == [n - 1 for n in lens]
+    model = oracle.Model(shape, w, rope)
+    ob = OracleBatch(model, toks, [8] * len(toks), max(lens) + 16)
+    for layer in range(shape.n_layers):
+        check_cache(eng, ob, layer, every=1)
+    eng.set_history([[np.zeros(0, np.int32)] for _ in toks])
+    stats = lockstep(eng, ob, [[np.zeros(0, np.int32)] for _ in toks], Policy(window=8, m_min=3, k_fixed=0, k_max=4),
+                     max_steps=4)
+    assert stats["emitted"] == 4 * len(toks)
+    eng.close()
+
+
+def test_prefill_result_does_not_depend_on_chunking(toy):
+    """The cache after prefill is bit-identical for chunks of 1024 / 100 / 16 tokens, for one call or many, and when
+    the first part of a sequence was cached by an earlier prefill (resume from kv_done)."""
+    shape, w, rope = toy
+    rng = np.random.default_rng(7)
+    lens = [700, 130, 1024, 31]
+    toks = texts(rng, lens, shape.vocab)
+    caches = []
+    for chunk, max_rows in [(1024, 2000), (100, 2000), (16, 50), (512, 600)]:
+        eng, _ = run_prefill(shape, w, rope, toks, chunk, max_rows, pages_seed=9)
+        caches.append((np_of(eng.kc).copy(), np_of(eng.vc).copy()))
+        eng.close()
+    for kc, vc in caches[1:]:
+        assert (kc == caches[0][0]).all() and (vc == caches[0][1]).all()
+    # resume: the first 200 / 50 / 1000 / 0 positions come from a first engine pass with chunk 256, the rest from a
+    # second pass that starts at kv_done
+    from paper_2508_18588_amd.runtime import Engine
+    eng = Engine(shape, w, rope, max_batch=4, k_max=4, c_max=1, max_len=max(lens) + 16, shuffle_pages_seed=9,
+                 max_rows=2000)
+    part = [200, 50, 1000, 0]
+    eng.load_sequences([t[:p + 1] for t, p in zip(toks, part)], budgets=[8] * 4)
+    eng.prefill_chunked(256)
+    eng.load_sequences(toks, budgets=[8] * 4)
+    eng.prefill_chunked(300, kv_done=part)
+    torch.cuda.synchronize()
+    assert (np_of(eng.kc) == caches[0][0]).all() and (np_of(eng.vc) == caches[0][1]).all()
+    eng.close()
+
+
+def test_prefill_agrees_with_the_verify_path_prefill(toy):
+    """The older way to fill the cache (chains of a few tokens through hs_verify) and hs_prefill see the same text:
+    their caches agree within rounding (different attention partitioning), and tightly."""
+    from paper_2508_18588_amd.runtime import Engine
+    shape, w, rope = toy
+    rng = np.random.default_rng(11)
+    toks = texts(rng, [400, 90], shape.vocab)
+    a, _ = run_prefill(shape, w, rope, toks, 256, 600, pages_seed=None)
+    b = Engine(shape, w, rope, max_batch=2, k_max=4, c_max=1, max_len=416, max_rows=600)
+    b.load_sequences(toks, budgets=[8] * 2)
+    b.prefill(toks)
+    f = lambda t: (np_of(t).view(np.uint16).astype(np.uint32) << 16).view(np.float32)
+    assert np.abs(f(a.kc) - f(b.kc)).max() < 2e-2 and np.abs(f(a.vc) - f(b.vc)).max() < 2e-2
+    assert (np_of(a.kc) == np_of(b.kc)).mean() > 0.9       # layer 0 is identical, layer 1 differs by roundings
+    a.close()
+    b.close()
+
+
+def test_prefill_edge_cases(toy):
+    """Nothing to do (all sequences of length 1; kv_done already complete): no rows, no writes, no error.  A text
+    longer than the rotary table is flagged and left alone."""
+    from paper_2508_18588_amd import HsError, hs_prefill, hs_prefill_args
+    from paper_2508_18588_amd.runtime import Engine
+    shape, w, rope = toy
+    rng = np.random.default_rng(13)
+    toks = texts(rng, [1, 1, 1], shape.vocab)
+    eng, calls = run_prefill(shape, w, rope, toks, 64, 100)
+    assert calls == 0
+    args = hs_prefill_args(64, 0, eng.kv_done.data_ptr())
+    hs_prefill(eng.ctx, eng.c_cache, eng.c_seq, eng.c_step, args, eng.stream())     # a call with zero rows
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 0 and int(eng.st["row_off"][3]) == 0
+    assert not np_of(eng.kc).any() and not np_of(eng.vc).any()
+    for bad in (hs_prefill_args(0, 0, eng.kv_done.data_ptr()), hs_prefill_args(1025, 0, eng.kv_done.data_ptr()),
+                hs_prefill_args(64, 0, None)):
+        with pytest.raises(HsError):
+            hs_prefill(eng.ctx, eng.c_cache, eng.c_seq, eng.c_step, bad, eng.stream())
+    eng.close()
+    short_rope = rope_table(64, shape.head_dim)
+    toks = texts(rng, [40, 100], shape.vocab)
+    eng = Engine(shape, w, short_rope, max_batch=2, k_max=4, c_max=1, max_len=120, max_rows=300)
+    eng.load_sequences(toks, budgets=[8] * 2)
+    eng.prefill_chunked(512)
+    torch.cuda.synchronize()
+    assert eng.poll_error() & 2                      # position overflow
+    assert np_of(eng.kv_done)[:2].tolist() == [39, 0]
+    eng.close()
+
+
+def test_prefill_7b_shape_two_layers():
+    """Head dimension 128, 7 query heads per KV head (rows of a token spread over 7 lanes of a row tile), d_model
+    3584, at the size of two 7B layers: K/V of sampled positions against the oracle within the tolerance derived
+    for that depth and width."""
+    from gpu_common import derived_logit_tol
+    shape7 = CONFIG_SHAPES[3]
+    shape = ModelShape(n_layers=2, d_model=shape7.d_model, n_q_heads=shape7.n_q_heads, n_kv_heads=shape7.n_kv_heads,
+                       head_dim=shape7.head_dim, d_ffn=shape7.d_ffn, vocab=4096, rms_eps=shape7.rms_eps)
+    w = make_weights(shape, seed=21)
+    rope = rope_table(512, shape.head_dim)
+    rng = np.random.default_rng(21)
+    toks = texts(rng, [150, 41], shape.vocab)
+    eng, _ = run_prefill(shape, w, rope, toks, 128, 160)
+    model = oracle.Model(shape, w, rope)
+    ob = OracleBatch(model, toks, [8] * 2, 200)
+    tol = derived_logit_tol(shape, 2)
+    hkv, h = shape.n_kv_heads, shape.head_dim
+    kc = np_of(eng.kc).view(np.uint16).reshape(2, eng.n_blocks, hkv, 16, h)
+    vc = np_of(eng.vc).view(np.uint16).reshape(2, eng.n_blocks, hkv, h, 16)
+    bt = np_of(eng.block_table)
+    f = lambda bits: (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    worst = 0.0
+    for b, s in enumerate(ob.seqs):
+        for pos in range(0, len(s), 3):
+            for layer in range(2):
+                k, v = s.kv(layer, pos)
+                page, ip = bt[b, pos // 16], pos % 16
+                worst = max(worst, np.abs(f(kc[layer, page, :, ip, :]).reshape(-1) - k).max(),
+                            np.abs(f(vc[layer, page, :, :, ip]).reshape(-1) - v).max())
+    print("7B-shape prefill: max |dK|,|dV| =", worst, "tolerance", tol)
+    assert worst <= tol
+    eng.close()
