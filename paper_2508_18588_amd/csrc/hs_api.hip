@@ -46,6 +46,8 @@ void layout_workspace(hs_ctx* ctx) {
     w.gemm_part_bytes = M * part_cols * 4;
     w.gemm_part = take(w.gemm_part_bytes);
     w.pf_len = take((size_t)l.max_batch * 4);
+    w.att_work = take((size_t)(2 + 2 * d.n_layers) * 4);
+    w.att_list = take(2 * hs_attention_max_units(ctx) * 8);
     w.total = off;
 }
 
@@ -172,6 +174,13 @@ hs_status hs_create(const hs_model_desc* desc, const hs_weights* w, const hs_lim
     const long long max_keys = (long long)l.max_blocks_per_seq * 16;
     ctx->max_parts = (int)((max_keys + ctx->att_part - 1) / ctx->att_part);
     ctx->max_segs = (l.max_pos + 32 + HS_DRAFT_SEG - 1) / HS_DRAFT_SEG;
+    {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            ctx->n_cu = n;
+        (void)hipGetLastError();
+    }
     layout_workspace(ctx);
     *out = ctx;
     return HS_OK;
@@ -263,6 +272,7 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
 
     pr.begin(3);
     hs_launch_embed(ctx, step, seq->batch, x, st);
+    hs_launch_attention_worklist(ctx, seq, step, st);
     pr.end();
     // A projection run in the split execution leaves its chunk partials for the next kernel in line (RMSNorm for
     // the residual projections, rotary/KV write for QKV), which adds them up in chunk order: one launch fewer per

@@ -162,109 +162,115 @@ __device__ inline void store_partial(const f32x16 (&o)[HD / 32], float m_run, fl
     }
 }
 
-template <int HD, int RTW>
-__global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc, size_t layer_off,
-    const int32_t* __restrict__ seq_len, const int32_t* __restrict__ block_table, int max_blocks, int n_blocks,
-    const int32_t* __restrict__ row_off, const uint64_t* __restrict__ anc_mask, float* __restrict__ part_o,
-    float* __restrict__ part_ml, int max_parts, int part_keys, int hq, int hkv, float scale_log2) {
-    constexpr int KS = HD + 8;        // sK row stride (bf16)
-    constexpr int VS = 20;            // sV row stride (bf16): 16 tokens + pad, 40 bytes
-    constexpr int NKS = HD / 16;      // k-steps of the score product
-    constexpr int NDT = HD / 32;      // 32-wide tiles of the head dimension
-    // 128 keys of K and 8 pages of V^T: four private 32-key slices (wavefront-per-partition path) or tiles of 64
-    // keys shared by the workgroup (workgroup-per-partition path).
-    __shared__ __attribute__((aligned(16))) bf16_t sK[128 * KS];
-    __shared__ __attribute__((aligned(16))) bf16_t sV[8 * HD * VS];
+// Everything a unit of work needs besides its own (sequence, KV head, partition).
+struct AttnArgs {
+    const bf16_t* q;
+    const bf16_t* kc;     // already offset to the layer
+    const bf16_t* vc;
+    const int32_t* seq_len;
+    const int32_t* block_table;
+    const int32_t* row_off;
+    const uint64_t* anc_mask;
+    float* part_o;
+    float* part_ml;
+    int max_blocks, n_blocks, max_parts, part_keys, hq, hkv;
+    float scale_log2;
+};
 
-    const int j = blockIdx.y, b = blockIdx.z;
-    const int r0 = row_off[b];
-    const int nn = row_off[b + 1] - r0;
-    if (nn <= 0) return;
-    const int L = seq_len[b] - 1;
-    const int total = L + nn;
-    const int G = hq / hkv;
-    const int R = nn * G;
-    const int nrt = (R + 31) >> 5;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// One partition of one (sequence, KV head) by ONE WAVEFRONT (R <= 32 query rows): private 32-key LDS slice, one
+// sub-tile of register prefetch, no workgroup synchronisation (a wavefront's LDS operations execute in order).
+template <int HD>
+__device__ inline void attn_unit_wave(const AttnArgs& a, int b, int j, int part, bf16_t* sKw, bf16_t* sVw, int lane) {
+    constexpr int KS = HD + 8, VS = 20, NKS = HD / 16, NDT = HD / 32;
     const int half = lane >> 5, l32 = lane & 31;
-    const int32_t* bt = block_table + (size_t)b * max_blocks;
-    const bf16_t* kbase_ptr = kc + layer_off + (size_t)j * 16 * HD;   // + page * page_stride
-    const bf16_t* vbase_ptr = vc + layer_off + (size_t)j * HD * 16;   // + page * page_stride
-    const size_t page_stride = (size_t)hkv * 16 * HD;
+    const int r0 = a.row_off[b];
+    const int nn = a.row_off[b + 1] - r0;
+    const int L = a.seq_len[b] - 1;
+    const int total = L + nn;
+    const int G = a.hq / a.hkv;
+    const int R = nn * G;
+    const int k_begin = part * a.part_keys;
+    if (nn <= 0 || k_begin >= total) return;
+    const int k_end = min(total, k_begin + a.part_keys);
+    const int32_t* bt = a.block_table + (size_t)b * a.max_blocks;
+    const bf16_t* kbase_ptr = a.kc + (size_t)j * 16 * HD;   // + page * page_stride
+    const bf16_t* vbase_ptr = a.vc + (size_t)j * HD * 16;
+    const size_t page_stride = (size_t)a.hkv * 16 * HD;
 
-    if (nrt == 1) {
-        // ---------------- one wavefront per partition, no workgroup synchronisation ----------------
-        if (blockIdx.x & 3) return;
-        const int part = blockIdx.x + wave;
-        const int k_begin = part * part_keys;
-        if (k_begin >= total) return;
-        const int k_end = min(total, k_begin + part_keys);
-        bf16_t* sKw = sK + wave * 32 * KS;
-        bf16_t* sVw = sV + wave * 2 * HD * VS;
-
-        bf16x8 qf[NKS];
-        uint64_t anc;
-        load_query_tile<HD>(q, anc_mask, r0, 0, R, G, hq, j, half, l32, qf, anc);
-        f32x16 o[NDT];
+    bf16x8 qf[NKS];
+    uint64_t anc;
+    load_query_tile<HD>(a.q, a.anc_mask, r0, 0, R, G, a.hq, j, half, l32, qf, anc);
+    f32x16 o[NDT];
 #pragma unroll
-        for (int dt = 0; dt < NDT; dt++)
+    for (int dt = 0; dt < NDT; dt++)
 #pragma unroll
-            for (int e = 0; e < 16; e++) o[dt][e] = 0.f;
-        float m_run = -INFINITY, l_run = 0.f;
+        for (int e = 0; e < 16; e++) o[dt][e] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
 
-        // one 32-key sub-tile = two pages; a page's K block and V^T block are each 16*HD contiguous elements,
-        // copied as NCP 16-byte chunks per lane (chunk c = lane + 64*ii covers elements [8c, 8c+8))
-        constexpr int NCP = HD / 32;
-        u32x4 rk[2 * NCP], rv[2 * NCP];
-        // the partition's page numbers, fetched once: lane l holds the page of positions k_begin + 16 l .. + 15
-        // (a partition has at most 64 pages), handed out by readlane -- no table look-up sits between two tiles
-        const int my_page = safe_page_lane(bt, k_begin + 16 * lane, total, max_blocks, n_blocks);
+    // one 32-key sub-tile = two pages; a page's K block and V^T block are each 16*HD contiguous elements, copied as
+    // NCP 16-byte chunks per lane (chunk c = lane + 64*ii covers elements [8c, 8c+8))
+    constexpr int NCP = HD / 32;
+    u32x4 rk[2 * NCP], rv[2 * NCP];
+    // the partition's page numbers, fetched once: lane l holds the page of positions k_begin + 16 l .. + 15 (a
+    // partition has at most 64 pages), handed out by readlane -- no table look-up sits between two tiles
+    const int my_page = safe_page_lane(bt, k_begin + 16 * lane, total, a.max_blocks, a.n_blocks);
 #define HS_W_FETCH(KB)                                                                                            \
-        {                                                                                                         \
-            _Pragma("unroll") for (int pp = 0; pp < 2; pp++) {                                                    \
-                const size_t pofs = (size_t)__builtin_amdgcn_readlane(my_page, (((KB) - k_begin) >> 4) + pp) * page_stride; \
-                const bf16_t* kp_ = kbase_ptr + pofs + lane * 8;                                                  \
-                const bf16_t* vp_ = vbase_ptr + pofs + lane * 8;                                                  \
-                _Pragma("unroll") for (int ii = 0; ii < NCP; ii++) {                                              \
-                    rk[pp * NCP + ii] = *reinterpret_cast<const u32x4*>(kp_ + ii * 512);                          \
-                    rv[pp * NCP + ii] = *reinterpret_cast<const u32x4*>(vp_ + ii * 512);                          \
-                }                                                                                                 \
+    {                                                                                                             \
+        _Pragma("unroll") for (int pp = 0; pp < 2; pp++) {                                                        \
+            const size_t pofs = (size_t)__builtin_amdgcn_readlane(my_page, (((KB) - k_begin) >> 4) + pp) * page_stride; \
+            const bf16_t* kp_ = kbase_ptr + pofs + lane * 8;                                                      \
+            const bf16_t* vp_ = vbase_ptr + pofs + lane * 8;                                                      \
+            _Pragma("unroll") for (int ii = 0; ii < NCP; ii++) {                                                  \
+                rk[pp * NCP + ii] = *reinterpret_cast<const u32x4*>(kp_ + ii * 512);                              \
+                rv[pp * NCP + ii] = *reinterpret_cast<const u32x4*>(vp_ + ii * 512);                              \
             }                                                                                                     \
-        }
-        HS_W_FETCH(k_begin)
-        for (int kb = k_begin; kb < k_end; kb += 32) {
-            // a wavefront's LDS operations execute in order: the previous sub-tile's reads are done
-#pragma unroll
-            for (int pp = 0; pp < 2; pp++)
-#pragma unroll
-                for (int ii = 0; ii < NCP; ii++) {
-                    int c = lane + 64 * ii;
-                    int key = pp * 16 + c / (HD / 8), c16 = c % (HD / 8);
-                    *reinterpret_cast<u32x4*>(&sKw[key * KS + c16 * 8]) = rk[pp * NCP + ii];
-                    int dim = c >> 1, hf = c & 1;
-                    u32x2* dst = reinterpret_cast<u32x2*>(&sVw[(pp * HD + dim) * VS + hf * 8]);
-                    dst[0] = u32x2{rv[pp * NCP + ii].x, rv[pp * NCP + ii].y};
-                    dst[1] = u32x2{rv[pp * NCP + ii].z, rv[pp * NCP + ii].w};
-                }
-            if (kb + 32 < k_end) HS_W_FETCH(kb + 32)
-            attn_subtile<HD>(sKw, sVw, qf, o, m_run, l_run, anc, kb, L, total, scale_log2, half, l32);
-        }
-#undef HS_W_FETCH
-        store_partial<HD>(o, m_run, l_run, part_o, part_ml, r0, 0, R, G, hq, j, max_parts, part, half, l32);
-        return;
+        }                                                                                                         \
     }
+    HS_W_FETCH(k_begin)
+    for (int kb = k_begin; kb < k_end; kb += 32) {
+#pragma unroll
+        for (int pp = 0; pp < 2; pp++)
+#pragma unroll
+            for (int ii = 0; ii < NCP; ii++) {
+                int c = lane + 64 * ii;
+                int key = pp * 16 + c / (HD / 8), c16 = c % (HD / 8);
+                *reinterpret_cast<u32x4*>(&sKw[key * KS + c16 * 8]) = rk[pp * NCP + ii];
+                int dim = c >> 1, hf = c & 1;
+                u32x2* dst = reinterpret_cast<u32x2*>(&sVw[(pp * HD + dim) * VS + hf * 8]);
+                dst[0] = u32x2{rv[pp * NCP + ii].x, rv[pp * NCP + ii].y};
+                dst[1] = u32x2{rv[pp * NCP + ii].z, rv[pp * NCP + ii].w};
+            }
+        if (kb + 32 < k_end) HS_W_FETCH(kb + 32)
+        attn_subtile<HD>(sKw, sVw, qf, o, m_run, l_run, anc, kb, L, total, a.scale_log2, half, l32);
+    }
+#undef HS_W_FETCH
+    store_partial<HD>(o, m_run, l_run, a.part_o, a.part_ml, r0, 0, R, G, a.hq, j, a.max_parts, part, half, l32);
+}
 
-    // ------------ one workgroup per partition: shared 64-key tiles, row tiles dealt to the wavefronts ------------
+// One partition of one (sequence, KV head) by the WORKGROUP (R > 32): 64-key tiles shared by the four wavefronts,
+// 32-row tiles dealt to them round-robin (up to RTW each), one tile of register prefetch.
+template <int HD, int RTW>
+__device__ inline void attn_unit_wg(const AttnArgs& a, int b, int j, int part, bf16_t* sK, bf16_t* sV, int tid) {
+    constexpr int KS = HD + 8, VS = 20, NKS = HD / 16, NDT = HD / 32;
     constexpr int TILE = 64;
     constexpr int NCK = HD / 32;      // 16-byte K chunks per thread and tile
-    constexpr int NCV = NCK;
-    const int part = blockIdx.x;
-    const int k_begin = part * part_keys;
-    if (k_begin >= total) return;
-    const int k_end = min(total, k_begin + part_keys);
-    // row tiles start at a workgroup-dependent wavefront so that two-tile sequences do not all use the same SIMDs
+    const int lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int r0 = a.row_off[b];
+    const int nn = a.row_off[b + 1] - r0;
+    const int L = a.seq_len[b] - 1;
+    const int total = L + nn;
+    const int G = a.hq / a.hkv;
+    const int R = nn * G;
+    const int nrt = (R + 31) >> 5;
+    const int k_begin = part * a.part_keys;
+    if (nn <= 0 || k_begin >= total) return;     // uniform over the workgroup
+    const int k_end = min(total, k_begin + a.part_keys);
+    const int32_t* bt = a.block_table + (size_t)b * a.max_blocks;
+    const bf16_t* kbase_ptr = a.kc + (size_t)j * 16 * HD;
+    const bf16_t* vbase_ptr = a.vc + (size_t)j * HD * 16;
+    const size_t page_stride = (size_t)a.hkv * 16 * HD;
+    // row tiles start at a unit-dependent wavefront so that two-tile sequences do not all use the same SIMDs
     const int slot = (wave - (part + j + b)) & 3;
 
     bf16x8 qf[RTW][NKS];
@@ -276,7 +282,7 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
     for (int t = 0; t < RTW; t++) {
         int rt = slot + 4 * t;
         rt_on[t] = rt < nrt;
-        load_query_tile<HD>(q, anc_mask, r0, rt_on[t] ? rt : 0, rt_on[t] ? R : 0, G, hq, j, half, l32, qf[t], anc[t]);
+        load_query_tile<HD>(a.q, a.anc_mask, r0, rt_on[t] ? rt : 0, rt_on[t] ? R : 0, G, a.hq, j, half, l32, qf[t], anc[t]);
 #pragma unroll
         for (int dt = 0; dt < NDT; dt++)
 #pragma unroll
@@ -287,21 +293,21 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
 
     // a 64-key tile = four pages = 8*HD 16-byte chunks of K and of V^T; chunk c = tid + 256*i lies in page
     // c / (2*HD), which is uniform within a wavefront
-    u32x4 rk[NCK], rv[NCV];
+    u32x4 rk[NCK], rv[NCK];
     const int wave_c0 = tid & ~63;
 #define HS_G_FETCH(KB)                                                                                            \
     {                                                                                                             \
         _Pragma("unroll") for (int i = 0; i < NCK; i++) {                                                         \
             const int kk = (wave_c0 + 256 * i) / (2 * HD);                                                        \
             const int within = (tid + 256 * i) % (2 * HD);                                                        \
-            const size_t pofs = (size_t)safe_page(bt, (KB) + 16 * kk, total, max_blocks, n_blocks) * page_stride; \
+            const size_t pofs = (size_t)safe_page(bt, (KB) + 16 * kk, total, a.max_blocks, a.n_blocks) * page_stride; \
             rk[i] = *reinterpret_cast<const u32x4*>(kbase_ptr + pofs + within * 8);                               \
             rv[i] = *reinterpret_cast<const u32x4*>(vbase_ptr + pofs + within * 8);                               \
         }                                                                                                         \
     }
     HS_G_FETCH(k_begin)
     for (int kbase = k_begin; kbase < k_end; kbase += TILE) {
-        __syncthreads();  // previous tile fully consumed
+        __syncthreads();  // previous tile (or previous unit) fully consumed
 #pragma unroll
         for (int i = 0; i < NCK; i++) {
             const int kk = (wave_c0 + 256 * i) / (2 * HD);
@@ -323,7 +329,7 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
             for (int t = 0; t < RTW; t++) {
                 if (!rt_on[t]) continue;
                 attn_subtile<HD>(sK + sub * 32 * KS, sV + sub * 2 * HD * VS, qf[t], o[t], m_run[t], l_run[t], anc[t],
-                                 kb, L, total, scale_log2, half, l32);
+                                 kb, L, total, a.scale_log2, half, l32);
             }
         }
     }
@@ -331,8 +337,104 @@ __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(
 #pragma unroll
     for (int t = 0; t < RTW; t++) {
         if (!rt_on[t]) continue;
-        store_partial<HD>(o[t], m_run[t], l_run[t], part_o, part_ml, r0, slot + 4 * t, R, G, hq, j, max_parts, part,
-                          half, l32);
+        store_partial<HD>(o[t], m_run[t], l_run[t], a.part_o, a.part_ml, r0, slot + 4 * t, R, G, a.hq, j, a.max_parts,
+                          part, half, l32);
+    }
+}
+
+// The units of one step, built once per hs_verify call (the same for every layer): a unit = one partition of one
+// (sequence, KV head), numbered u = partition * hkv + head within its sequence.  List A: units of sequences with more
+// than 32 query rows per KV head (taken by whole workgroups), list B: the others (taken by single wavefronts).
+// work[0] = |A|, work[1] = |B|, work[2 + 2 l], work[3 + 2 l] = the two take-counters of layer l (zeroed here).
+__global__ __launch_bounds__(256) void attn_worklist_kernel(const int32_t* __restrict__ seq_len,
+                                                             const int32_t* __restrict__ row_off, int batch,
+                                                             int part_keys, int G, int hkv, int max_parts, int n_layers,
+                                                             int32_t* __restrict__ work, int2* __restrict__ list_a,
+                                                             int2* __restrict__ list_b) {
+    __shared__ int s_nu[256], s_off[256];
+    __shared__ int sw_a[4], sw_b[4];
+    __shared__ int carry_a, carry_b;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < 2 * n_layers; i += 256) work[2 + i] = 0;
+    if (tid == 0) { carry_a = 0; carry_b = 0; }
+    __syncthreads();
+    for (int b0 = 0; b0 < batch; b0 += 256) {
+        const int b = b0 + tid;
+        int nu = 0;
+        bool is_a = false;
+        if (b < batch) {
+            const int nn = row_off[b + 1] - row_off[b];
+            if (nn > 0) {
+                const int total = seq_len[b] - 1 + nn;
+                const int nparts = min(max_parts, (total + part_keys - 1) / part_keys);
+                nu = max(nparts, 0) * hkv;
+                is_a = nn * G > 32;
+            }
+        }
+        int ia = is_a ? nu : 0, ib = is_a ? 0 : nu;
+        const int va = ia, vb = ib;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            int ta = __shfl_up(ia, o), tb = __shfl_up(ib, o);
+            if (lane >= o) { ia += ta; ib += tb; }
+        }
+        if (lane == 63) { sw_a[wave] = ia; sw_b[wave] = ib; }
+        __syncthreads();
+        int ba = carry_a, bb = carry_b;
+        for (int w2 = 0; w2 < wave; w2++) { ba += sw_a[w2]; bb += sw_b[w2]; }
+        // sign of s_nu tells the list: positive = B, negative = A
+        s_nu[tid] = is_a ? -nu : nu;
+        s_off[tid] = is_a ? ba + ia - va : bb + ib - vb;
+        __syncthreads();
+        if (tid == 255) { carry_a = ba + ia; carry_b = bb + ib; }
+        const int nb = min(256, batch - b0);
+        for (int i = 0; i < nb; i++) {
+            const int n = s_nu[i], off = s_off[i];
+            int2* dst = (n < 0 ? list_a : list_b) + off;
+            const int cnt = n < 0 ? -n : n;
+            for (int u = tid; u < cnt; u += 256) dst[u] = make_int2(b0 + i, u);
+        }
+        __syncthreads();
+    }
+    if (tid == 0) { work[0] = carry_a; work[1] = carry_b; }
+}
+
+// Persistent launch: about as many workgroups as the chip holds at once; each takes units from the two lists through
+// atomic counters until both are empty (the counters only grow, so every wavefront reaches its exit).  No workgroup
+// is ever launched for work that does not exist, the four wavefronts of a workgroup are never idle while units are
+// left, and which workgroup computes a unit has no influence on the unit's result.
+template <int HD, int RTW>
+__global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(AttnArgs a, const int32_t* __restrict__ work,
+                                                                            int32_t* __restrict__ take,
+                                                                            const int2* __restrict__ list_a,
+                                                                            const int2* __restrict__ list_b) {
+    constexpr int KS = HD + 8;        // sK row stride (bf16)
+    constexpr int VS = 20;            // sV row stride (bf16): 16 tokens + pad, 40 bytes
+    // 128 keys of K and 8 pages of V^T: four private 32-key slices (wavefront units) or tiles of 64 keys shared by
+    // the workgroup (workgroup units)
+    __shared__ __attribute__((aligned(16))) bf16_t sK[128 * KS];
+    __shared__ __attribute__((aligned(16))) bf16_t sV[8 * HD * VS];
+    __shared__ int s_item;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_a = work[0], n_b = work[1];
+    for (;;) {
+        if (tid == 0) s_item = atomicAdd(&take[0], 1);
+        __syncthreads();
+        const int it = s_item;
+        __syncthreads();
+        if (it >= n_a) break;
+        const int2 e = list_a[it];
+        attn_unit_wg<HD, RTW>(a, e.x, e.y % a.hkv, e.y / a.hkv, sK, sV, tid);
+    }
+    bf16_t* sKw = sK + wave * 32 * KS;
+    bf16_t* sVw = sV + wave * 2 * HD * VS;
+    for (;;) {
+        int it = 0;
+        if (lane == 0) it = atomicAdd(&take[1], 1);
+        it = __builtin_amdgcn_readfirstlane(it);
+        if (it >= n_b) break;
+        const int2 e = list_b[it];
+        attn_unit_wave<HD>(a, e.x, e.y % a.hkv, e.y / a.hkv, sKw, sVw, lane);
     }
 }
 
@@ -541,17 +643,33 @@ __global__ __launch_bounds__(64) void attn_verify_plain(
 }
 
 template <int HD, int RTW>
-void launch_mfma(const hs_ctx* ctx, size_t layer_off, const hs_kv_cache* cache, const hs_seq_state* seq,
-                 const hs_step* step, const bf16_t* q, bf16_t* out, hipStream_t st) {
+void launch_mfma(const hs_ctx* ctx, int layer, size_t layer_off, const hs_kv_cache* cache, const hs_seq_state* seq,
+                 const hs_step* step, const bf16_t* q, hipStream_t st) {
     const hs_model_desc& d = ctx->desc;
-    float* part_o = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_o);
-    float* part_ml = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_ml);
-    float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
-    dim3 grid(ctx->max_parts, d.n_kv_heads, seq->batch);
-    hipLaunchKernelGGL((attn_verify_mfma<HD, RTW>), grid, dim3(256), 0, st, q, (const bf16_t*)cache->k,
-                       (const bf16_t*)cache->v, layer_off, seq->seq_len, seq->block_table,
-                       ctx->lim.max_blocks_per_seq, cache->n_blocks, step->row_off, step->anc_mask, part_o, part_ml,
-                       ctx->max_parts, ctx->att_part, d.n_q_heads, d.n_kv_heads, scale_log2);
+    AttnArgs a;
+    a.q = q;
+    a.kc = (const bf16_t*)cache->k + layer_off;
+    a.vc = (const bf16_t*)cache->v + layer_off;
+    a.seq_len = seq->seq_len;
+    a.block_table = seq->block_table;
+    a.row_off = step->row_off;
+    a.anc_mask = step->anc_mask;
+    a.part_o = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_o);
+    a.part_ml = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_ml);
+    a.max_blocks = ctx->lim.max_blocks_per_seq;
+    a.n_blocks = cache->n_blocks;
+    a.max_parts = ctx->max_parts;
+    a.part_keys = ctx->att_part;
+    a.hq = d.n_q_heads;
+    a.hkv = d.n_kv_heads;
+    a.scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
+    int32_t* work = reinterpret_cast<int32_t*>(ctx->ws + ctx->lay.att_work);
+    const int2* list_a = reinterpret_cast<const int2*>(ctx->ws + ctx->lay.att_list);
+    const int2* list_b = list_a + hs_attention_max_units(ctx);
+    // at least as many workgroups as can be resident at once (2-4 per compute unit with one row tile per wavefront,
+    // 1-2 with two); those that start after the lists have run dry leave at once
+    dim3 grid(ctx->n_cu * (RTW == 1 ? 4 : 2));
+    hipLaunchKernelGGL((attn_verify_mfma<HD, RTW>), grid, dim3(256), 0, st, a, work, work + 2 + 2 * layer, list_a, list_b);
 }
 
 }  // namespace
@@ -572,12 +690,27 @@ void hs_launch_attention(const hs_ctx* ctx, int layer, const hs_kv_cache* cache,
     int r_max = G * (1 + ctx->lim.c_max * ctx->lim.k_max);
     bool two = r_max > 128;
     if (d.head_dim == 128) {
-        if (two) launch_mfma<128, 2>(ctx, layer_off, cache, seq, step, q, out, st);
-        else launch_mfma<128, 1>(ctx, layer_off, cache, seq, step, q, out, st);
+        if (two) launch_mfma<128, 2>(ctx, layer, layer_off, cache, seq, step, q, st);
+        else launch_mfma<128, 1>(ctx, layer, layer_off, cache, seq, step, q, st);
     } else {
-        if (two) launch_mfma<64, 2>(ctx, layer_off, cache, seq, step, q, out, st);
-        else launch_mfma<64, 1>(ctx, layer_off, cache, seq, step, q, out, st);
+        if (two) launch_mfma<64, 2>(ctx, layer, layer_off, cache, seq, step, q, st);
+        else launch_mfma<64, 1>(ctx, layer, layer_off, cache, seq, step, q, st);
     }
+}
+
+size_t hs_attention_max_units(const hs_ctx* ctx) {
+    return (size_t)ctx->lim.max_batch * ctx->max_parts * ctx->desc.n_kv_heads;
+}
+
+void hs_launch_attention_worklist(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, hipStream_t st) {
+    if (ctx->flags & HS_FLAG_REFERENCE_KERNELS) return;
+    const hs_model_desc& d = ctx->desc;
+    int32_t* work = reinterpret_cast<int32_t*>(ctx->ws + ctx->lay.att_work);
+    int2* list_a = reinterpret_cast<int2*>(ctx->ws + ctx->lay.att_list);
+    int2* list_b = list_a + hs_attention_max_units(ctx);
+    hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(256), 0, st, seq->seq_len, step->row_off, seq->batch,
+                       ctx->att_part, d.n_q_heads / d.n_kv_heads, d.n_kv_heads, ctx->max_parts, d.n_layers, work, list_a,
+                       list_b);
 }
 
 void hs_launch_attention_prefill(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,

@@ -18,7 +18,7 @@ constexpr int HS_DRAFT_SEG = 4096;
 constexpr int HS_MAX_NODES = 64;  // ancestor masks are 64-bit
 
 struct hs_workspace_layout {
-    size_t x, xn, qkv, q, attn, act, part_o, part_ml, logits, draft_best, gemm_part, gemm_part_bytes, err, pf_len, total;
+    size_t x, xn, qkv, q, attn, act, part_o, part_ml, logits, draft_best, gemm_part, gemm_part_bytes, err, pf_len, att_work, att_list, total;
 };
 
 struct hs_ctx {
@@ -35,6 +35,7 @@ struct hs_ctx {
     int att_part = HS_ATT_PART_DEFAULT;
     int max_parts = 0;
     int max_segs = 0;
+    int n_cu = 256;  // compute units of the device the context was created on
     std::string err;
     // profiling
     int profile = 0;
@@ -92,6 +93,9 @@ void hs_launch_prefill_rows(const hs_ctx* ctx, const hs_seq_state* seq, int32_t*
 void hs_launch_attention_prefill(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
                                  const int32_t* len_plus1, const hs_step* step, const bf16_t* q, bf16_t* out, int chunk,
                                  hipStream_t st);
+// Unit lists of the verify attention (one per hs_verify call, before the first layer) and their capacity.
+void hs_launch_attention_worklist(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, hipStream_t st);
+size_t hs_attention_max_units(const hs_ctx* ctx);
 void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, bf16_t* out,
                                hipStream_t st);
 void hs_launch_argmax(const hs_ctx* ctx, const float* logits, int32_t* argmax, const int32_t* m_dev,

@@ -40,11 +40,13 @@ def test_7b_shape_two_layers_lockstep():
     tol = derived_logit_tol(shape, L)
     old = gpu_common.LOGIT_TOL
     import test_gpu_decode
-    test_gpu_decode.LOGIT_TOL = tol          # lockstep() reads the module-level tolerance
+    test_gpu_decode.LOGIT_TOL = tol          # lockstep() and check_cache() read the module-level tolerance
+    gpu_common.LOGIT_TOL = tol
     try:
         stats = lockstep(eng, ob, cands, pol, max_steps=20, check_kv_layers=(1,))
     finally:
         test_gpu_decode.LOGIT_TOL = old
+        gpu_common.LOGIT_TOL = old
     eng.close()
     print("7B-shape 2 layers:", stats, "tolerance", tol)
     assert stats["emitted"] == 24 and stats["max_logit_err"] <= tol
