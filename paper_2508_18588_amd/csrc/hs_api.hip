@@ -46,8 +46,8 @@ void layout_workspace(hs_ctx* ctx) {
     w.gemm_part_bytes = M * part_cols * 4;
     w.gemm_part = take(w.gemm_part_bytes);
     w.pf_len = take((size_t)l.max_batch * 4);
-    w.att_work = take((size_t)(2 + 2 * d.n_layers) * 4);
-    w.att_list = take(2 * hs_attention_max_units(ctx) * 8);
+    w.att_work = take((size_t)(2 + d.n_layers) * 4);
+    w.att_list = take(2 * hs_attention_max_units(ctx) * 32);
     w.total = off;
 }
 

@@ -177,57 +177,84 @@ struct AttnArgs {
     float scale_log2;
 };
 
-// One partition of one (sequence, KV head) by ONE WAVEFRONT (R <= 32 query rows): private 32-key LDS slice, one
-// sub-tile of register prefetch, no workgroup synchronisation (a wavefront's LDS operations execute in order).
+// A unit of work: one partition of one (sequence, KV head), with the sequence's row range and cached length, as the
+// list kernel wrote it (two int4 per unit).
+struct AttnUnit { int b, j, part, r0, nn, L; };
+
+__device__ inline AttnUnit attn_unit_from(const int4& p, const int4& q) {
+    AttnUnit u;
+    u.b = __builtin_amdgcn_readfirstlane(p.x);
+    u.j = __builtin_amdgcn_readfirstlane(p.y);
+    u.part = __builtin_amdgcn_readfirstlane(p.z);
+    u.r0 = __builtin_amdgcn_readfirstlane(p.w);
+    u.nn = __builtin_amdgcn_readfirstlane(q.x);
+    u.L = __builtin_amdgcn_readfirstlane(q.y);
+    return u;
+}
+
+// Units with at most 32 query rows, taken by ONE WAVEFRONT each: the wavefront walks its units (first, first + stride,
+// ...) as one uninterrupted stream of 32-key sub-tiles through a private LDS slice, always with the next sub-tile's
+// K/V in flight in registers -- also across a unit boundary: the next unit's list entry is read during the current
+// unit's first sub-tile, its page numbers during the second, its first sub-tile during the current unit's last.
+// There is no workgroup synchronisation (a wavefront's LDS operations execute in order) and no atomic: a load or an
+// atomic that returns late holds back every later load of its wavefront.
 template <int HD>
-__device__ inline void attn_unit_wave(const AttnArgs& a, int b, int j, int part, bf16_t* sKw, bf16_t* sVw, int lane) {
+__device__ inline void attn_wave_stream(const AttnArgs& a, const int4* __restrict__ list, int n_units, int first,
+                                        int stride, bf16_t* sKw, bf16_t* sVw, int lane) {
     constexpr int KS = HD + 8, VS = 20, NKS = HD / 16, NDT = HD / 32;
+    if (first >= n_units) return;
     const int half = lane >> 5, l32 = lane & 31;
-    const int r0 = a.row_off[b];
-    const int nn = a.row_off[b + 1] - r0;
-    const int L = a.seq_len[b] - 1;
-    const int total = L + nn;
     const int G = a.hq / a.hkv;
-    const int R = nn * G;
-    const int k_begin = part * a.part_keys;
-    if (nn <= 0 || k_begin >= total) return;
-    const int k_end = min(total, k_begin + a.part_keys);
-    const int32_t* bt = a.block_table + (size_t)b * a.max_blocks;
-    const bf16_t* kbase_ptr = a.kc + (size_t)j * 16 * HD;   // + page * page_stride
-    const bf16_t* vbase_ptr = a.vc + (size_t)j * HD * 16;
     const size_t page_stride = (size_t)a.hkv * 16 * HD;
+
+    AttnUnit cu = attn_unit_from(list[2 * first], list[2 * first + 1]);
+    int total = cu.L + cu.nn;
+    int k_begin = cu.part * a.part_keys;
+    int k_end = min(total, k_begin + a.part_keys);
+    const bf16_t* kbase_ptr = a.kc + (size_t)cu.j * 16 * HD;   // + page * page_stride
+    const bf16_t* vbase_ptr = a.vc + (size_t)cu.j * HD * 16;
+    // the unit's page numbers, fetched once: lane l holds the page of positions k_begin + 16 l .. + 15 (a partition
+    // has at most 64 pages), handed out by readlane -- no table look-up sits between two sub-tiles
+    int my_page = safe_page_lane(a.block_table + (size_t)cu.b * a.max_blocks, k_begin + 16 * lane, total, a.max_blocks,
+                                 a.n_blocks);
+
+    int it_n = first + stride;
+    bool have_n = it_n < n_units;
+    int4 en0 = list[2 * (have_n ? it_n : first)], en1 = list[2 * (have_n ? it_n : first) + 1];
+    bool n_ready = false;
+    AttnUnit nu = cu;
+    int total_n = total, k_begin_n = k_begin, k_end_n = k_end, my_page_n = my_page;
+    const bf16_t *kbase_n = kbase_ptr, *vbase_n = vbase_ptr;
 
     bf16x8 qf[NKS];
     uint64_t anc;
-    load_query_tile<HD>(a.q, a.anc_mask, r0, 0, R, G, a.hq, j, half, l32, qf, anc);
     f32x16 o[NDT];
+    float m_run = -INFINITY, l_run = 0.f;
+    load_query_tile<HD>(a.q, a.anc_mask, cu.r0, 0, cu.nn * G, G, a.hq, cu.j, half, l32, qf, anc);
 #pragma unroll
     for (int dt = 0; dt < NDT; dt++)
 #pragma unroll
         for (int e = 0; e < 16; e++) o[dt][e] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
 
     // one 32-key sub-tile = two pages; a page's K block and V^T block are each 16*HD contiguous elements, copied as
     // NCP 16-byte chunks per lane (chunk c = lane + 64*ii covers elements [8c, 8c+8))
     constexpr int NCP = HD / 32;
     u32x4 rk[2 * NCP], rv[2 * NCP];
-    // the partition's page numbers, fetched once: lane l holds the page of positions k_begin + 16 l .. + 15 (a
-    // partition has at most 64 pages), handed out by readlane -- no table look-up sits between two tiles
-    const int my_page = safe_page_lane(bt, k_begin + 16 * lane, total, a.max_blocks, a.n_blocks);
-#define HS_W_FETCH(KB)                                                                                            \
+#define HS_W_FETCH(PAGES, KPTR, VPTR, PAGE0)                                                                      \
     {                                                                                                             \
         _Pragma("unroll") for (int pp = 0; pp < 2; pp++) {                                                        \
-            const size_t pofs = (size_t)__builtin_amdgcn_readlane(my_page, (((KB) - k_begin) >> 4) + pp) * page_stride; \
-            const bf16_t* kp_ = kbase_ptr + pofs + lane * 8;                                                      \
-            const bf16_t* vp_ = vbase_ptr + pofs + lane * 8;                                                      \
+            const size_t pofs = (size_t)__builtin_amdgcn_readlane(PAGES, (PAGE0) + pp) * page_stride;             \
+            const bf16_t* kp_ = (KPTR) + pofs + lane * 8;                                                         \
+            const bf16_t* vp_ = (VPTR) + pofs + lane * 8;                                                         \
             _Pragma("unroll") for (int ii = 0; ii < NCP; ii++) {                                                  \
                 rk[pp * NCP + ii] = *reinterpret_cast<const u32x4*>(kp_ + ii * 512);                              \
                 rv[pp * NCP + ii] = *reinterpret_cast<const u32x4*>(vp_ + ii * 512);                              \
             }                                                                                                     \
         }                                                                                                         \
     }
-    HS_W_FETCH(k_begin)
-    for (int kb = k_begin; kb < k_end; kb += 32) {
+    HS_W_FETCH(my_page, kbase_ptr, vbase_ptr, 0)
+    int kb = k_begin;
+    for (;;) {
 #pragma unroll
         for (int pp = 0; pp < 2; pp++)
 #pragma unroll
@@ -240,25 +267,59 @@ __device__ inline void attn_unit_wave(const AttnArgs& a, int b, int j, int part,
                 dst[0] = u32x2{rv[pp * NCP + ii].x, rv[pp * NCP + ii].y};
                 dst[1] = u32x2{rv[pp * NCP + ii].z, rv[pp * NCP + ii].w};
             }
-        if (kb + 32 < k_end) HS_W_FETCH(kb + 32)
-        attn_subtile<HD>(sKw, sVw, qf, o, m_run, l_run, anc, kb, L, total, a.scale_log2, half, l32);
+        const bool last = kb + 32 >= k_end;
+        if (have_n && !n_ready && (kb > k_begin || last)) {
+            nu = attn_unit_from(en0, en1);
+            total_n = nu.L + nu.nn;
+            k_begin_n = nu.part * a.part_keys;
+            k_end_n = min(total_n, k_begin_n + a.part_keys);
+            kbase_n = a.kc + (size_t)nu.j * 16 * HD;
+            vbase_n = a.vc + (size_t)nu.j * HD * 16;
+            my_page_n = safe_page_lane(a.block_table + (size_t)nu.b * a.max_blocks, k_begin_n + 16 * lane, total_n,
+                                       a.max_blocks, a.n_blocks);
+            n_ready = true;
+        }
+        if (!last) HS_W_FETCH(my_page, kbase_ptr, vbase_ptr, (kb + 32 - k_begin) >> 4)
+        else if (have_n) HS_W_FETCH(my_page_n, kbase_n, vbase_n, 0)
+        attn_subtile<HD>(sKw, sVw, qf, o, m_run, l_run, anc, kb, cu.L, total, a.scale_log2, half, l32);
+        kb += 32;
+        if (last) {
+            store_partial<HD>(o, m_run, l_run, a.part_o, a.part_ml, cu.r0, 0, cu.nn * G, G, a.hq, cu.j, a.max_parts, cu.part,
+                              half, l32);
+            if (!have_n) break;
+            cu = nu;
+            total = total_n; k_begin = k_begin_n; k_end = k_end_n; my_page = my_page_n;
+            kbase_ptr = kbase_n; vbase_ptr = vbase_n;
+            kb = k_begin;
+            it_n += stride;
+            have_n = it_n < n_units;
+            n_ready = false;
+            en0 = list[2 * (have_n ? it_n : first)];
+            en1 = list[2 * (have_n ? it_n : first) + 1];
+            load_query_tile<HD>(a.q, a.anc_mask, cu.r0, 0, cu.nn * G, G, a.hq, cu.j, half, l32, qf, anc);
+#pragma unroll
+            for (int dt = 0; dt < NDT; dt++)
+#pragma unroll
+                for (int e = 0; e < 16; e++) o[dt][e] = 0.f;
+            m_run = -INFINITY;
+            l_run = 0.f;
+        }
     }
 #undef HS_W_FETCH
-    store_partial<HD>(o, m_run, l_run, a.part_o, a.part_ml, r0, 0, R, G, a.hq, j, a.max_parts, part, half, l32);
 }
 
-// One partition of one (sequence, KV head) by the WORKGROUP (R > 32): 64-key tiles shared by the four wavefronts,
+// One partition of one (sequence, KV head) by the WORKGROUP (R > 32): 64- or 128-key tiles shared by the four wavefronts,
 // 32-row tiles dealt to them round-robin (up to RTW each), one tile of register prefetch.
 template <int HD, int RTW>
-__device__ inline void attn_unit_wg(const AttnArgs& a, int b, int j, int part, bf16_t* sK, bf16_t* sV, int tid) {
+__device__ inline void attn_unit_wg(const AttnArgs& a, const AttnUnit& un, bf16_t* sK, bf16_t* sV, int tid) {
     constexpr int KS = HD + 8, VS = 20, NKS = HD / 16, NDT = HD / 32;
-    constexpr int TILE = 64;
-    constexpr int NCK = HD / 32;      // 16-byte K chunks per thread and tile
+    // keys per shared tile: with one row tile per wavefront there are registers for a 128-key tile in flight (twice
+    // the bytes on their way per workgroup), with two only for 64
+    constexpr int TILE = RTW == 1 ? 128 : 64;
+    constexpr int NCK = TILE * HD / 2048;   // 16-byte K chunks per thread and tile
     const int lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int r0 = a.row_off[b];
-    const int nn = a.row_off[b + 1] - r0;
-    const int L = a.seq_len[b] - 1;
+    const int b = un.b, j = un.j, part = un.part, r0 = un.r0, nn = un.nn, L = un.L;
     const int total = L + nn;
     const int G = a.hq / a.hkv;
     const int R = nn * G;
@@ -291,8 +352,8 @@ __device__ inline void attn_unit_wg(const AttnArgs& a, int b, int j, int part, b
         l_run[t] = 0.f;
     }
 
-    // a 64-key tile = four pages = 8*HD 16-byte chunks of K and of V^T; chunk c = tid + 256*i lies in page
-    // c / (2*HD), which is uniform within a wavefront
+    // a tile of TILE keys = TILE/16 pages = TILE*HD/8 16-byte chunks of K and of V^T; chunk c = tid + 256*i lies in
+    // page c / (2*HD), which is uniform within a wavefront
     u32x4 rk[NCK], rv[NCK];
     const int wave_c0 = tid & ~63;
 #define HS_G_FETCH(KB)                                                                                            \
@@ -322,7 +383,7 @@ __device__ inline void attn_unit_wg(const AttnArgs& a, int b, int j, int part, b
         __syncthreads();
         if (kbase + TILE < k_end) HS_G_FETCH(kbase + TILE)
 #pragma unroll
-        for (int sub = 0; sub < 2; sub++) {
+        for (int sub = 0; sub < TILE / 32; sub++) {
             const int kb = kbase + 32 * sub;
             if (kb >= k_end) break;
 #pragma unroll
@@ -343,31 +404,33 @@ __device__ inline void attn_unit_wg(const AttnArgs& a, int b, int j, int part, b
 }
 
 // The units of one step, built once per hs_verify call (the same for every layer): a unit = one partition of one
-// (sequence, KV head), numbered u = partition * hkv + head within its sequence.  List A: units of sequences with more
-// than 32 query rows per KV head (taken by whole workgroups), list B: the others (taken by single wavefronts).
-// work[0] = |A|, work[1] = |B|, work[2 + 2 l], work[3 + 2 l] = the two take-counters of layer l (zeroed here).
+// (sequence, KV head), in (sequence, partition, head) order.  List A: units of sequences with more than 32 query rows
+// per KV head (taken by whole workgroups), list B: the others (taken by single wavefronts).  An entry is two int4:
+// (sequence, head, partition, first row) (rows, cached length, 0, 0).  work[0] = |A|, work[1] = |B|, work[2 + l] = the
+// counter through which layer l's launch hands out list A (zeroed here).
 __global__ __launch_bounds__(256) void attn_worklist_kernel(const int32_t* __restrict__ seq_len,
                                                              const int32_t* __restrict__ row_off, int batch,
                                                              int part_keys, int G, int hkv, int max_parts, int n_layers,
-                                                             int32_t* __restrict__ work, int2* __restrict__ list_a,
-                                                             int2* __restrict__ list_b) {
-    __shared__ int s_nu[256], s_off[256];
+                                                             int32_t* __restrict__ work, int4* __restrict__ list_a,
+                                                             int4* __restrict__ list_b) {
+    __shared__ int s_nu[256], s_off[256], s_r0[256], s_nn[256], s_len[256];
     __shared__ int sw_a[4], sw_b[4];
     __shared__ int carry_a, carry_b;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < 2 * n_layers; i += 256) work[2 + i] = 0;
+    for (int i = tid; i < n_layers; i += 256) work[2 + i] = 0;
     if (tid == 0) { carry_a = 0; carry_b = 0; }
     __syncthreads();
     for (int b0 = 0; b0 < batch; b0 += 256) {
         const int b = b0 + tid;
-        int nu = 0;
+        int nu = 0, r0 = 0, nn = 0, L = 0;
         bool is_a = false;
         if (b < batch) {
-            const int nn = row_off[b + 1] - row_off[b];
-            if (nn > 0) {
-                const int total = seq_len[b] - 1 + nn;
-                const int nparts = min(max_parts, (total + part_keys - 1) / part_keys);
-                nu = max(nparts, 0) * hkv;
+            r0 = row_off[b];
+            nn = row_off[b + 1] - r0;
+            L = seq_len[b] - 1;
+            if (nn > 0 && L >= 0) {
+                const int nparts = min(max_parts, (L + nn + part_keys - 1) / part_keys);
+                nu = nparts * hkv;
                 is_a = nn * G > 32;
             }
         }
@@ -382,59 +445,63 @@ __global__ __launch_bounds__(256) void attn_worklist_kernel(const int32_t* __res
         __syncthreads();
         int ba = carry_a, bb = carry_b;
         for (int w2 = 0; w2 < wave; w2++) { ba += sw_a[w2]; bb += sw_b[w2]; }
-        // sign of s_nu tells the list: positive = B, negative = A
+        // the sign of s_nu tells the list: positive = B, negative = A
         s_nu[tid] = is_a ? -nu : nu;
         s_off[tid] = is_a ? ba + ia - va : bb + ib - vb;
+        s_r0[tid] = r0;
+        s_nn[tid] = nn;
+        s_len[tid] = L;
         __syncthreads();
         if (tid == 255) { carry_a = ba + ia; carry_b = bb + ib; }
         const int nb = min(256, batch - b0);
         for (int i = 0; i < nb; i++) {
-            const int n = s_nu[i], off = s_off[i];
-            int2* dst = (n < 0 ? list_a : list_b) + off;
+            const int n = s_nu[i];
+            int4* dst = (n < 0 ? list_a : list_b) + 2 * (size_t)s_off[i];
             const int cnt = n < 0 ? -n : n;
-            for (int u = tid; u < cnt; u += 256) dst[u] = make_int2(b0 + i, u);
+            for (int u = tid; u < cnt; u += 256) {
+                dst[2 * u] = make_int4(b0 + i, u % hkv, u / hkv, s_r0[i]);
+                dst[2 * u + 1] = make_int4(s_nn[i], s_len[i], 0, 0);
+            }
         }
         __syncthreads();
     }
     if (tid == 0) { work[0] = carry_a; work[1] = carry_b; }
 }
 
-// Persistent launch: about as many workgroups as the chip holds at once; each takes units from the two lists through
-// atomic counters until both are empty (the counters only grow, so every wavefront reaches its exit).  No workgroup
-// is ever launched for work that does not exist, the four wavefronts of a workgroup are never idle while units are
-// left, and which workgroup computes a unit has no influence on the unit's result.
+// Persistent launch: exactly as many workgroups as the chip holds at once.  First every wavefront streams its share
+// of the wavefront units (wavefront w of workgroup g: units 4 g + w, 4 g + w + 4 gridDim.x, ... -- dealt out
+// statically, so that nothing but K/V tiles is ever waited for); then the workgroups take the workgroup units one by
+// one through a counter (`take`, zeroed by the list kernel).  These are short -- four wavefronts share one partition
+// -- and fill the ragged end of the first phase: a workgroup that had less to stream takes more of them.  The claim
+// for the next unit is issued before the current one is computed.  No workgroup is launched for work that does not
+// exist, and which workgroup computes a unit has no influence on the unit's result.
 template <int HD, int RTW>
 __global__ __launch_bounds__(256, (RTW == 1 ? 2 : 1)) void attn_verify_mfma(AttnArgs a, const int32_t* __restrict__ work,
                                                                             int32_t* __restrict__ take,
-                                                                            const int2* __restrict__ list_a,
-                                                                            const int2* __restrict__ list_b) {
+                                                                            const int4* __restrict__ list_a,
+                                                                            const int4* __restrict__ list_b) {
     constexpr int KS = HD + 8;        // sK row stride (bf16)
     constexpr int VS = 20;            // sV row stride (bf16): 16 tokens + pad, 40 bytes
     // 128 keys of K and 8 pages of V^T: four private 32-key slices (wavefront units) or tiles of 64 keys shared by
     // the workgroup (workgroup units)
     __shared__ __attribute__((aligned(16))) bf16_t sK[128 * KS];
     __shared__ __attribute__((aligned(16))) bf16_t sV[8 * HD * VS];
-    __shared__ int s_item;
+    __shared__ int s_item[2];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n_a = work[0], n_b = work[1];
-    for (;;) {
-        if (tid == 0) s_item = atomicAdd(&take[0], 1);
+    attn_wave_stream<HD>(a, list_b, n_b, blockIdx.x * 4 + wave, gridDim.x * 4, sK + wave * 32 * KS,
+                         sV + wave * 2 * HD * VS, lane);
+    if (n_a == 0) return;
+    if (tid == 0) s_item[0] = atomicAdd(take, 1);
+    __syncthreads();   // also: every private slice is consumed before shared tiles are written
+    int it = s_item[0], slot = 0;
+    while (it < n_a) {
+        if (tid == 0) s_item[slot ^ 1] = atomicAdd(take, 1);
+        const AttnUnit un = attn_unit_from(list_a[2 * it], list_a[2 * it + 1]);
+        attn_unit_wg<HD, RTW>(a, un, sK, sV, tid);
         __syncthreads();
-        const int it = s_item;
-        __syncthreads();
-        if (it >= n_a) break;
-        const int2 e = list_a[it];
-        attn_unit_wg<HD, RTW>(a, e.x, e.y % a.hkv, e.y / a.hkv, sK, sV, tid);
-    }
-    bf16_t* sKw = sK + wave * 32 * KS;
-    bf16_t* sVw = sV + wave * 2 * HD * VS;
-    for (;;) {
-        int it = 0;
-        if (lane == 0) it = atomicAdd(&take[1], 1);
-        it = __builtin_amdgcn_readfirstlane(it);
-        if (it >= n_b) break;
-        const int2 e = list_b[it];
-        attn_unit_wave<HD>(a, e.x, e.y % a.hkv, e.y / a.hkv, sKw, sVw, lane);
+        slot ^= 1;
+        it = s_item[slot];
     }
 }
 
@@ -664,12 +731,19 @@ void launch_mfma(const hs_ctx* ctx, int layer, size_t layer_off, const hs_kv_cac
     a.hkv = d.n_kv_heads;
     a.scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
     int32_t* work = reinterpret_cast<int32_t*>(ctx->ws + ctx->lay.att_work);
-    const int2* list_a = reinterpret_cast<const int2*>(ctx->ws + ctx->lay.att_list);
-    const int2* list_b = list_a + hs_attention_max_units(ctx);
-    // at least as many workgroups as can be resident at once (2-4 per compute unit with one row tile per wavefront,
-    // 1-2 with two); those that start after the lists have run dry leave at once
-    dim3 grid(ctx->n_cu * (RTW == 1 ? 4 : 2));
-    hipLaunchKernelGGL((attn_verify_mfma<HD, RTW>), grid, dim3(256), 0, st, a, work, work + 2 + 2 * layer, list_a, list_b);
+    const int4* list_a = reinterpret_cast<const int4*>(ctx->ws + ctx->lay.att_list);
+    const int4* list_b = list_a + 2 * hs_attention_max_units(ctx);
+    // the wavefront units are dealt out statically: the grid is what is resident at once, no more
+    static int per_cu = 0;
+    if (per_cu == 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void*)attn_verify_mfma<HD, RTW>, 256, 0) != hipSuccess ||
+            n < 1)
+            n = 1;
+        per_cu = n;
+    }
+    dim3 grid(ctx->n_cu * per_cu);
+    hipLaunchKernelGGL((attn_verify_mfma<HD, RTW>), grid, dim3(256), 0, st, a, work, work + 2 + layer, list_a, list_b);
 }
 
 }  // namespace
@@ -706,8 +780,8 @@ void hs_launch_attention_worklist(const hs_ctx* ctx, const hs_seq_state* seq, co
     if (ctx->flags & HS_FLAG_REFERENCE_KERNELS) return;
     const hs_model_desc& d = ctx->desc;
     int32_t* work = reinterpret_cast<int32_t*>(ctx->ws + ctx->lay.att_work);
-    int2* list_a = reinterpret_cast<int2*>(ctx->ws + ctx->lay.att_list);
-    int2* list_b = list_a + hs_attention_max_units(ctx);
+    int4* list_a = reinterpret_cast<int4*>(ctx->ws + ctx->lay.att_list);
+    int4* list_b = list_a + 2 * hs_attention_max_units(ctx);
     hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(256), 0, st, seq->seq_len, step->row_off, seq->batch,
                        ctx->att_part, d.n_q_heads / d.n_kv_heads, d.n_kv_heads, ctx->max_parts, d.n_layers, work, list_a,
                        list_b);
