@@ -58,6 +58,8 @@ def lib():
         L.orc_gate_step.argtypes = [i32p, C.c_int, C.c_uint32, C.c_uint32]
         L.orc_gate_table.argtypes = [C.POINTER(C.c_float), i32p, C.c_int, C.c_double, C.c_int, i32p]
         L.orc_gate_table.restype = None
+        L.orc_plan_allocation.argtypes = [f64p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, i32p,
+                                          f64p]
         L.orc_draft_len.argtypes = [C.c_int] * 4
         L.orc_aimd.argtypes = [C.c_int] * 6
         L.orc_build_tree.argtypes = [C.c_int, C.POINTER(i32p), intp, C.c_int32, C.c_int, i32p, i32p, i32p, u64p,
@@ -147,6 +149,20 @@ def gate_table(ms, rows, k_bar: float, b_max: int) -> np.ndarray:
     lib().orc_gate_table(m.ctypes.data_as(C.POINTER(C.c_float)), rp, len(m), float(k_bar), b_max,
                          out.ctypes.data_as(C.POINTER(C.c_int32)))
     return out
+
+
+def plan_allocation(tau, min_wks: int, max_wks: int, wks: int, t_train: float, p: float = 1.0):
+    """Tier-2 planner (Sec. 6.2): tau[i][k - min_wks] = time of ranking group i on k workers.  Returns
+    (plan int32[N], d) or None if the cluster cannot meet any gradient in the search interval."""
+    t = np.ascontiguousarray(tau, dtype=np.float64)
+    n, k = t.shape
+    assert k == max_wks - min_wks + 1
+    plan = np.zeros(n, np.int32)
+    d = np.zeros(1, np.float64)
+    ok = lib().orc_plan_allocation(t.ctypes.data_as(C.POINTER(C.c_double)), n, min_wks, max_wks, wks, float(t_train),
+                                   float(p), plan.ctypes.data_as(C.POINTER(C.c_int32)),
+                                   d.ctypes.data_as(C.POINTER(C.c_double)))
+    return (plan, float(d[0])) if ok else None
 
 
 def k_policy(mode, k_fixed, k_state, match_len, k_max) -> int:

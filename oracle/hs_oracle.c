@@ -30,6 +30,11 @@
  *                          monitored and speculation is switched off while the
  *                          batch is larger than the largest batch at which it
  *                          still pays at that rate (a pre-profiled table).
+ *   orc_plan_workers,
+ *   orc_plan_allocation    Sec. 6.2, figure "Tier-2 scheduling algorithm": workers
+ *                          per ranking group such that the groups' finish times
+ *                          rise linearly with the smallest gradient the cluster
+ *                          can afford (binary search).
  *   orc_seq_*              Sec. 2.2: the target model's forward pass (a
  *                          standard pre-norm decoder; shape from the
  *                          benchmark configurations).
@@ -45,6 +50,71 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+
+/* ------------------------------------------------- Tier-2 planner (HistoPipe) */
+
+/*
+ * Sec. 6.2, figure "Tier-2 scheduling algorithm", in its notation.  N ranking
+ * groups in ascending order of representative length; tau[i * K + (k - MIN_WKS)]
+ * = tau(lens[i], k), the pre-profiled time of group i on k workers, K = MAX_WKS
+ * - MIN_WKS + 1.  The target time of group i is t0 + i d.
+ *
+ * calWks: for each group the fewest workers k in [MIN_WKS, MAX_WKS] whose time
+ * meets the group's target; -1 if some group cannot meet it at all, else the sum.
+ */
+long orc_plan_workers(const double* tau, int N, int MIN_WKS, int MAX_WKS, double d, double t0, int32_t* plan) {
+    int K = MAX_WKS - MIN_WKS + 1;
+    long wks_needed = 0;
+    for (int i = 0; i < N; i++) {
+        double target_t = t0 + i * d;
+        int group_wks = -1;
+        for (int k = MIN_WKS; k <= MAX_WKS; k++) {
+            double exec_t = tau[(size_t)i * K + (k - MIN_WKS)];
+            if (exec_t <= target_t) { group_wks = k; break; }
+        }
+        if (group_wks == -1) return -1;
+        wks_needed += group_wks;
+        plan[i] = group_wks;
+    }
+    return wks_needed;
+}
+
+/*
+ * planAllocation: t0 = max(tau(lens[0], MAX_WKS), t_train); the gradient d is
+ * searched in [0, (tau(lens[N-1], MIN_WKS) - t0) / (N - 1)] by bisection down to
+ * precision p; a d whose plan needs more than wks workers raises the lower end,
+ * a feasible one becomes the best plan and lowers the upper end.
+ * Readings where the figure is silent: the upper end itself is tried first (if
+ * even that needs more than wks workers no d in the interval is feasible and 0 is
+ * returned; it also defines the plan when the interval is already narrower than
+ * p); N = 1 has no gradient: the plan is the fewest workers that meet t0.
+ * Returns 1 and fills plan[N], *d_out (the gradient the plan was computed for).
+ */
+int orc_plan_allocation(const double* tau, int N, int MIN_WKS, int MAX_WKS, int wks, double t_train, double p,
+                        int32_t* plan, double* d_out) {
+    int K = MAX_WKS - MIN_WKS + 1;
+    double t0 = tau[K - 1] > t_train ? tau[K - 1] : t_train;
+    int32_t* cand = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    double d_min = 0.0;
+    double d_max = N > 1 ? (tau[(size_t)(N - 1) * K] - t0) / (N - 1) : 0.0;
+    if (d_max < 0.0) d_max = 0.0;
+    long need = orc_plan_workers(tau, N, MIN_WKS, MAX_WKS, d_max, t0, cand);
+    if (need < 0 || need > wks) { free(cand); return 0; }
+    memcpy(plan, cand, sizeof(int32_t) * (size_t)N);
+    while (d_max - d_min > p) {
+        double d_mid = (d_max + d_min) / 2;
+        need = orc_plan_workers(tau, N, MIN_WKS, MAX_WKS, d_mid, t0, cand);
+        if (need < 0 || need > wks) {
+            d_min = d_mid;
+        } else {
+            memcpy(plan, cand, sizeof(int32_t) * (size_t)N);
+            d_max = d_mid;
+        }
+    }
+    *d_out = d_max;
+    free(cand);
+    return 1;
+}
 
 /* ------------------------------------------------- speculation on / off */
 
