@@ -282,6 +282,19 @@ hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size
 hs_status hs_gate_table_build(const float* ms, const int32_t* rows, int32_t n_points, float k_bar, int32_t b_max,
                               int32_t* table17);
 
+/* HOST: Tier-2 planner of the hybrid rollout pipeline (Sec. 6.2, figure "Tier-2 scheduling algorithm"): how many
+ * rollout workers each ranking group gets so that the groups' finish times rise linearly, t(i) = t0 + i d, with the
+ * smallest gradient d the cluster can afford.  n_groups ranking groups in ascending order of representative length;
+ * tau[i * K + (k - min_wks)], K = max_wks - min_wks + 1, = pre-profiled time of group i on k data-parallel workers
+ * (the caller evaluates its profile tau(l, dp), speculation included, at the groups' lengths).  t0 =
+ * max(tau(group 0, max_wks), t_train); d is bisected in [0, (tau(last group, min_wks) - t0) / (n_groups - 1)] down
+ * to `precision`; for a given d a group takes the fewest workers that meet its target time.  Writes plan[n_groups]
+ * and *d_out (the gradient the plan was computed for).  HS_ERR_CAPACITY: even the upper end of the interval needs
+ * more than `wks` workers (plan untouched).  No device work; one GPU machine never runs it for more than one worker --
+ * it pairs with the sequence-sharded layout described for several GPUs. */
+hs_status hs_plan_allocation(const double* tau, int32_t n_groups, int32_t min_wks, int32_t max_wks, int32_t wks,
+                             double t_train, double precision, int32_t* plan, double* d_out);
+
 /* One projection on its own, through the same launcher hs_verify uses (unit-level parity tests and timing):
  * C[m, n] (+)= A[m, k] . W[n, k]^T with bf16 operands, K-contiguous, fp32 accumulation in the shape's fixed K
  * order.  epi 0: C f32 = product; 1: C f32 += product; 2: SwiGLU, C bf16 [m][n] = silu(A.W^T) * (A.W2^T).

@@ -119,7 +119,7 @@ HS_PREFILL_CHUNK_MAX = 1024
 
 EXPORTS = ("hs_create", "hs_destroy", "hs_last_error", "hs_set_flags", "hs_workspace_bytes", "hs_bind_workspace",
            "hs_draft", "hs_draft_group", "hs_verify", "hs_accept", "hs_kv_commit", "hs_poll_error", "hs_debug_buffer",
-           "hs_set_profile", "hs_get_profile", "hs_debug_gemm", "hs_gate_table_build", "hs_prefill")
+           "hs_set_profile", "hs_get_profile", "hs_debug_gemm", "hs_gate_table_build", "hs_prefill", "hs_plan_allocation")
 
 _lib = None
 
@@ -160,6 +160,8 @@ def lib():
         L.hs_get_profile.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         L.hs_gate_table_build.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int32), C.c_int32, C.c_float, C.c_int32,
                                           C.POINTER(C.c_int32)]
+        L.hs_plan_allocation.argtypes = [C.POINTER(C.c_double), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_double,
+                                         C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         L.hs_debug_gemm.argtypes = [vp, C.c_int32, vp, vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp]
         _lib = L
     return _lib
@@ -258,6 +260,20 @@ def hs_gate_table_build(ms, rows, k_bar: float, b_max: int):
     if st != HS_OK:
         raise HsError(st, "hs_gate_table_build rejected the profile")
     return list(out)
+
+
+def hs_plan_allocation(tau, min_wks: int, max_wks: int, wks: int, t_train: float, precision: float = 1.0):
+    """Tier-2 planner: tau[i][k - min_wks] = time of ranking group i on k workers -> (plan, d); raises HsError
+    (HS_ERR_CAPACITY) if the cluster cannot meet any gradient of the search interval.  Host arithmetic only."""
+    n = len(tau)
+    vals = [float(x) for row in tau for x in row]
+    flat = (C.c_double * max(1, len(vals)))(*vals)
+    plan = (C.c_int32 * max(1, n))()
+    d = C.c_double()
+    st = lib().hs_plan_allocation(flat, n, min_wks, max_wks, wks, float(t_train), float(precision), plan, C.byref(d))
+    if st != HS_OK:
+        raise HsError(st, "hs_plan_allocation: no feasible plan" if st == HS_ERR_CAPACITY else "hs_plan_allocation")
+    return list(plan), d.value
 
 
 def hs_get_profile(ctx):

@@ -461,6 +461,47 @@ hs_status hs_gate_table_build(const float* ms, const int32_t* rows, int32_t n_po
     return HS_OK;
 }
 
+hs_status hs_plan_allocation(const double* tau, int32_t n_groups, int32_t min_wks, int32_t max_wks, int32_t wks,
+                             double t_train, double precision, int32_t* plan, double* d_out) {
+    if (!tau || !plan || !d_out || n_groups < 1 || min_wks < 1 || max_wks < min_wks || wks < 1 || !(precision > 0.0))
+        return HS_ERR_INVALID_ARG;
+    const int width = max_wks - min_wks + 1;
+    const double t0 = std::max(tau[width - 1], t_train);
+    std::vector<int32_t> trial((size_t)n_groups);
+    // workers needed at gradient d (the fewest per group that meet t0 + i d), -1 if a group cannot meet its target
+    auto workers_at = [&](double d) -> long {
+        long total = 0;
+        for (int i = 0; i < n_groups; i++) {
+            const double* row = tau + (size_t)i * width;
+            const double target = t0 + i * d;
+            int k = 0;
+            while (k < width && !(row[k] <= target)) k++;
+            if (k == width) return -1;
+            trial[i] = min_wks + k;
+            total += trial[i];
+        }
+        return total;
+    };
+    double lo = 0.0;
+    double hi = n_groups > 1 ? (tau[(size_t)(n_groups - 1) * width] - t0) / (n_groups - 1) : 0.0;
+    if (hi < 0.0) hi = 0.0;
+    long need = workers_at(hi);
+    if (need < 0 || need > wks) return HS_ERR_CAPACITY;
+    std::copy(trial.begin(), trial.end(), plan);
+    while (hi - lo > precision) {
+        const double mid = (hi + lo) / 2;
+        need = workers_at(mid);
+        if (need < 0 || need > wks) {
+            lo = mid;
+        } else {
+            std::copy(trial.begin(), trial.end(), plan);
+            hi = mid;
+        }
+    }
+    *d_out = hi;
+    return HS_OK;
+}
+
 hs_status hs_debug_gemm(hs_ctx* ctx, int32_t epi, const void* a, const void* w, const void* w2, void* c,
                         const int32_t* m_dev, int32_t m_max, int32_t n, int32_t k, int32_t rows_hint,
                         hs_stream stream) {

@@ -149,3 +149,34 @@ def test_gate_table_host_helper_equals_the_oracle():
         hs.hs_gate_table_build([1.0], [4], 2.0, 8)
     with pytest.raises(hs.HsError):
         hs.hs_gate_table_build([1.0, 2.0, 3.0], [4, 4, 9], 2.0, 8)
+
+
+def test_planner_host_function_equals_the_oracle():
+    """hs_plan_allocation is host arithmetic: plan and gradient must be the oracle's on random instances (same
+    bisection, so exactly), infeasible instances report HS_ERR_CAPACITY, bad arguments HS_ERR_INVALID_ARG."""
+    import numpy as np
+    import oracle
+    rng = np.random.default_rng(17)
+    n_none = 0
+    for trial in range(200):
+        n, width, min_wks = int(rng.integers(1, 17)), int(rng.integers(1, 9)), int(rng.integers(1, 4))
+        max_wks = min_wks + width - 1
+        lens = np.sort(rng.uniform(200, 16000, n)) * np.where(np.arange(n) == n - 1, rng.uniform(1, 4), 1.0)
+        tau = lens[:, None] * (0.2 + 0.8 / np.arange(min_wks, max_wks + 1)[None, :])
+        wks = int(rng.integers(n * min_wks, n * max_wks + 2))
+        t_train = float(rng.choice([0.0, rng.uniform(0, tau[0, 0] * 1.5)]))
+        p = float(rng.choice([1.0, 25.0, 0.05]))
+        want = oracle.plan_allocation(tau, min_wks, max_wks, wks, t_train, p)
+        if want is None:
+            n_none += 1
+            with pytest.raises(hs.HsError) as e:
+                hs.hs_plan_allocation(tau, min_wks, max_wks, wks, t_train, p)
+            assert e.value.status == hs.HS_ERR_CAPACITY
+        else:
+            plan, d = hs.hs_plan_allocation(tau, min_wks, max_wks, wks, t_train, p)
+            assert plan == want[0].tolist() and d == want[1], (trial, plan, want)
+    assert 5 < n_none < 150
+    for bad in ((0, 2, 4, 1.0), (3, 2, 4, 1.0), (1, 2, 0, 1.0), (1, 2, 4, 0.0)):
+        with pytest.raises(hs.HsError) as e:
+            hs.hs_plan_allocation([[3.0, 2.0][:max(0, bad[1] - bad[0] + 1)] or [1.0]], bad[0], bad[1], bad[2], 0.0, bad[3])
+        assert e.value.status == hs.HS_ERR_INVALID_ARG
