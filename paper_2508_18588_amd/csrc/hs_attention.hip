@@ -652,12 +652,25 @@ __global__ __launch_bounds__(256) void attn_merge(const float* __restrict__ part
             ll = part_ml[(prow + p0 + lane) * 2 + 1];
         }
         const int n = min(64, nparts - p0);
-        for (int p = 0; p < n; p++) {     // partition order
-            float w = __shfl(wl, p);
-            den += w * __shfl(ll, p);
-            const float* po = part_o + (prow + p0 + p) * HD;
+        // partition order; the values of eight partitions are fetched before the first is added, so that the loop
+        // waits for memory once per eight partitions instead of once per partition
+        for (int pb = 0; pb < n; pb += 8) {
+            float v[8][HD / 64];
 #pragma unroll
-            for (int i = 0; i < HD / 64; i++) acc[i] += w * po[lane + 64 * i];
+            for (int q = 0; q < 8; q++) {
+                const float* po = part_o + (prow + p0 + min(pb + q, n - 1)) * HD;
+#pragma unroll
+                for (int i = 0; i < HD / 64; i++) v[q][i] = po[lane + 64 * i];
+            }
+#pragma unroll
+            for (int q = 0; q < 8; q++) {
+                if (pb + q < n) {
+                    float w = __shfl(wl, pb + q);
+                    den += w * __shfl(ll, pb + q);
+#pragma unroll
+                    for (int i = 0; i < HD / 64; i++) acc[i] += w * v[q][i];
+                }
+            }
         }
     }
 #pragma unroll
