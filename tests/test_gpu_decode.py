@@ -301,6 +301,44 @@ def test_gqa_head_dim_128_small_model():
     assert stats["emitted"] == 240 and stats["accepted"] > 60 and stats["flagged"] <= 6
 
 
+def test_batch_of_300_ragged_sequences_mixed_unit_kinds():
+    """More sequences than one block of the device-side list builders handles at once (256), three KV heads (the
+    wavefronts of a workgroup then straddle partitions), contexts of 2..700 tokens (1..3 partitions of 256 keys),
+    finished sequences in between, and drafts of up to 12 tokens next to sequences that draft nothing: units for
+    single wavefronts and units for workgroups in one launch.  The cache comes from hs_prefill (its row builder also
+    walks the batch in blocks).  Three decode steps in lock-step with the oracle."""
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    shape = ModelShape(n_layers=2, d_model=384, n_q_heads=9, n_kv_heads=3, head_dim=64, d_ffn=512, vocab=512)
+    w = make_weights(shape, 51, norm_jitter=0.1)
+    rope = rope_table(1024, shape.head_dim)
+    model = oracle.Model(shape, w, rope)
+    rng = np.random.default_rng(52)
+    B = 300
+    lens = rng.integers(2, 701, B)
+    toks = [rng.integers(0, shape.vocab, int(n)).astype(np.int32) for n in lens]
+    budgets = [0 if b % 7 == 3 else 20 for b in range(B)]
+    # history: for two sequences in three the true continuation is not known (no match -> one row); for the others
+    # a planted copy of the text's last tokens followed by 12 tokens makes hs_draft take a 12-token draft
+    cands = []
+    for b in range(B):
+        if b % 3 == 0:
+            cands.append([np.concatenate([toks[b][-6:], rng.integers(0, shape.vocab, 12)]).astype(np.int32)])
+        else:
+            cands.append([np.zeros(0, np.int32)])
+    pol = Policy(window=6, m_min=3, k_fixed=12, k_max=12)
+    eng = Engine(shape, w, rope, max_batch=B, k_max=12, c_max=1, max_len=int(lens.max()) + 24, shuffle_pages_seed=53)
+    eng.load_sequences(toks, budgets=budgets)
+    eng.set_history(cands)
+    eng.prefill_chunked(64)
+    ob = OracleBatch(model, toks, budgets, int(lens.max()) + 40)
+    stats = lockstep(eng, ob, cands, pol, max_steps=3)
+    eng.close()
+    print("batch300", stats)
+    live = sum(b > 0 for b in budgets)
+    assert stats["steps"] == 3 and stats["emitted"] >= 3 * live
+    assert stats["rows"] > 3 * live + 900          # the planted drafts were taken (12 extra rows each, first step)
+
+
 def test_split_and_serial_gemm_execution_agree_bitwise():
     """The narrow projections cut K into a fixed number of chunks; with few rows each chunk runs in its own
     workgroup and an ordered reduce adds them, with many rows one workgroup folds the chunks itself.  Both must
