@@ -237,7 +237,9 @@ __device__ inline void attn_wave_stream(const AttnArgs& a, const int4* __restric
         for (int e = 0; e < 16; e++) o[dt][e] = 0.f;
 
     // one 32-key sub-tile = two pages; a page's K block and V^T block are each 16*HD contiguous elements, copied as
-    // NCP 16-byte chunks per lane (chunk c = lane + 64*ii covers elements [8c, 8c+8))
+    // NCP 16-byte chunks per lane (chunk c = lane + 64*ii covers elements [8c, 8c+8)).  The loads are non-temporal:
+    // K/V is read once per launch, and kept out of the caches it leaves the queries and the partial results (which
+    // the merge kernel reads right after) there -- 10 % of the launch
     constexpr int NCP = HD / 32;
     u32x4 rk[2 * NCP], rv[2 * NCP];
 #define HS_W_FETCH(PAGES, KPTR, VPTR, PAGE0)                                                                      \
@@ -247,8 +249,8 @@ __device__ inline void attn_wave_stream(const AttnArgs& a, const int4* __restric
             const bf16_t* kp_ = (KPTR) + pofs + lane * 8;                                                         \
             const bf16_t* vp_ = (VPTR) + pofs + lane * 8;                                                         \
             _Pragma("unroll") for (int ii = 0; ii < NCP; ii++) {                                                  \
-                rk[pp * NCP + ii] = *reinterpret_cast<const u32x4*>(kp_ + ii * 512);                              \
-                rv[pp * NCP + ii] = *reinterpret_cast<const u32x4*>(vp_ + ii * 512);                              \
+                rk[pp * NCP + ii] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp_ + ii * 512));                           \
+                rv[pp * NCP + ii] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vp_ + ii * 512));                           \
             }                                                                                                     \
         }                                                                                                         \
     }
@@ -362,8 +364,8 @@ __device__ inline void attn_unit_wg(const AttnArgs& a, const AttnUnit& un, bf16_
             const int kk = (wave_c0 + 256 * i) / (2 * HD);                                                        \
             const int within = (tid + 256 * i) % (2 * HD);                                                        \
             const size_t pofs = (size_t)safe_page(bt, (KB) + 16 * kk, total, a.max_blocks, a.n_blocks) * page_stride; \
-            rk[i] = *reinterpret_cast<const u32x4*>(kbase_ptr + pofs + within * 8);                               \
-            rv[i] = *reinterpret_cast<const u32x4*>(vbase_ptr + pofs + within * 8);                               \
+            rk[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kbase_ptr + pofs + within * 8));                           \
+            rv[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vbase_ptr + pofs + within * 8));                           \
         }                                                                                                         \
     }
     HS_G_FETCH(k_begin)
