@@ -33,6 +33,15 @@ __device__ __forceinline__ void load_to_lds_16(const unsigned char* base, unsign
                  : "memory", "m0");
 }
 
+// The same for data that is read once per launch (the weight stream): non-temporal, so that it does not evict the
+// activation tile that every workgroup re-reads from L2.
+__device__ __forceinline__ void load_to_lds_16_stream(const unsigned char* base, unsigned off, unsigned lds_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                 :
+                 : "s"(lds_off), "v"(off), "s"(base)
+                 : "memory", "m0");
+}
+
 }  // namespace hs_gemm_detail
 
 // The MFMA kernel (defined in hs_gemm_stream.hip).  `chunks`/`tpc` are the K chunking of

@@ -55,6 +55,7 @@ struct stream_args {
     void* Cout;
     float* part;
     int M, m_max, N, K, n0, m0, kt0, kt1, chunk;
+    int w_once;  // the launch reads every weight byte once (one row pass): non-temporal weight loads
 };
 
 // One K chunk of one row pass for a wavefront that owns NMI live row tiles (0 = loads and barriers only).
@@ -97,7 +98,10 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
         const unsigned dst = smem_off + W_RING + (kt % SW) * W_STAGE + wave * 1024;
         const unsigned char* base = w_mine + (size_t)kt * ROW_BYTES;
 #pragma unroll
-        for (int j = 0; j < NLW; j++) load_to_lds_16(base, w_off[j], dst + j * 4096);
+        for (int j = 0; j < NLW; j++) {
+            if (p.w_once) load_to_lds_16_stream(base, w_off[j], dst + j * 4096);
+            else load_to_lds_16(base, w_off[j], dst + j * 4096);
+        }
     };
     // Hand-over number h (h < kt0 before the loop, then in the middle of tile h): first the activation tile h+SA,
     // then the weight tile h+SW.  The issue order fixes the wait counts below.
@@ -110,8 +114,10 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
                                smem_off + ((h + SA) % SA) * A_STAGE + wave * 1024 + l * 4096);
             }
         } else if (h + SW < p.kt1) {
-            load_to_lds_16(w_mine + (size_t)(h + SW) * ROW_BYTES, w_off[l - 4 * MT],
-                           smem_off + W_RING + ((h + SW) % SW) * W_STAGE + wave * 1024 + (l - 4 * MT) * 4096);
+            const unsigned char* wsrc = w_mine + (size_t)(h + SW) * ROW_BYTES;
+            const unsigned wdst = smem_off + W_RING + ((h + SW) % SW) * W_STAGE + wave * 1024 + (l - 4 * MT) * 4096;
+            if (p.w_once) load_to_lds_16_stream(wsrc, w_off[l - 4 * MT], wdst);
+            else load_to_lds_16(wsrc, w_off[l - 4 * MT], wdst);
         }
     };
     auto issue_for = [&](int h) {
@@ -316,6 +322,7 @@ __global__ __launch_bounds__(256) void hs_gemm_stream(const bf16_t* __restrict__
     if (group >= n_groups) return;
     p.n0 = group * NCOLS;
     p.chunk = blockIdx.y;
+    p.w_once = n_pass == 1;
     const int nk = K / BK;
     p.kt0 = blockIdx.y * tpc;
     p.kt1 = min(nk, p.kt0 + tpc);
