@@ -95,10 +95,14 @@ void launch(const hs_ctx* ctx, const bf16_t* a, const bf16_t* w, const bf16_t* w
 }  // namespace
 
 // Number of K chunks of a projection: a function of the shape alone.  Narrow outputs get as many chunks as put
-// about one workgroup of the weight-streaming execution (128 weight rows each) on every one of the 256 compute
-// units; every chunk keeps at least 4 k-tiles.
+// about one workgroup of the weight-streaming execution on every one of the 256 compute units; every chunk keeps at
+// least 4 k-tiles.  A workgroup takes 128 weight rows, or 64 when the reduction is short (hs_gemm_narrow_groups):
+// with half as many chunks the projection writes -- and the kernel after it reads -- half the partial sums, and
+// with K < 8192 the activation tile that every workgroup re-reads is small enough for that to pay.
+bool hs_gemm_narrow_groups(int k) { return k < 8192; }
+
 int hs_gemm_chunks(int n, int k) {
-    const int groups = (n + 127) / 128;
+    const int groups = hs_gemm_narrow_groups(k) ? (n + 63) / 64 : (n + 127) / 128;
     int chunks = 256 / groups;
     const int nk = k / BK;
     if (chunks > nk / 4) chunks = nk / 4;

@@ -44,6 +44,9 @@ __device__ __forceinline__ void load_to_lds_16_stream(const unsigned char* base,
 
 }  // namespace hs_gemm_detail
 
+// Split-K projections with a short reduction run in groups of 64 weight rows (see hs_gemm_chunks).
+bool hs_gemm_narrow_groups(int k);
+
 // The MFMA kernel (defined in hs_gemm_stream.hip).  `chunks`/`tpc` are the K chunking of
 // the shape (chunks > 1: chunk sums go to `part`, laid out [chunk][m_max][n], for the ordered reduce).
 void hs_launch_gemm_stream(int epi, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, float* part,

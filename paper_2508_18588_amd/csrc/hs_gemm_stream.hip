@@ -403,7 +403,10 @@ void launch_stream_shape(const bf16_t* a, const bf16_t* w, const bf16_t* w2, voi
     // not pay a second pass over the weights.  Row tiles that do not exist cost nothing in either shape.
     const bool tall = rows_hint > 160;
 #define HS_ARGS a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st
-    if (nu == 5) {
+    if (PARTIAL && chunks > 1 && hs_gemm_narrow_groups(k)) {
+        if (tall) launch_stream<EPI, PARTIAL, 2, 3, 2, 6>(HS_ARGS);
+        else launch_stream<EPI, PARTIAL, 2, 2, 2, 8>(HS_ARGS);
+    } else if (nu == 5) {
         if (tall) launch_stream<EPI, PARTIAL, 5, 3, 2, 3>(HS_ARGS);
         else launch_stream<EPI, PARTIAL, 5, 2, 2, 4>(HS_ARGS);
     } else {
