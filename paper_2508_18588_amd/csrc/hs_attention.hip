@@ -14,16 +14,22 @@
 // product O^T = V^T . P^T needs as its B operand.  V is stored in the cache with the token index fastest so V^T
 // tiles are plain 8-byte LDS reads.
 //
-// Two ways to run a partition, chosen per sequence by its number of query rows R = G * nn:
-//   R <= 32 (one-token decoding and short drafts): one WAVEFRONT per partition.  The 4 wavefronts of a workgroup
-//     take 4 consecutive partitions and never synchronise: each stages its own sub-tiles in a private LDS slice.
-//     With a single 32-row tile the softmax arithmetic of a partition is one instruction stream; giving every
-//     wavefront its own stream keeps all four SIMDs of a compute unit busy and the KV stream bandwidth-bound.
-//   R > 32: one WORKGROUP per partition; K/V tiles of 64 keys are staged once and shared, the row tiles are
+// Two ways to run a unit (= one partition of one (sequence, KV head)), chosen per sequence by its number of query
+// rows R = G * nn:
+//   R <= 32 (one-token decoding and short drafts): one WAVEFRONT per unit.  A wavefront streams its units one after
+//     the other through a private LDS slice and never synchronises with the others.  With a single 32-row tile the
+//     softmax arithmetic of a partition is one instruction stream; giving every wavefront its own stream keeps all
+//     four SIMDs of a compute unit busy and the KV stream bandwidth-bound.
+//   R > 32: one WORKGROUP per unit; K/V tiles of 64 or 128 keys are staged once and shared, the row tiles are
 //     dealt to the 4 wavefronts.
 // Both run the identical per-row arithmetic on the identical partitions: masked keys contribute exact zeros and
 // partitions merge in index order, so a row's result is bit-identical whether it is verified next to other draft
 // rows or decoded alone.
+//
+// Launch.  The units of a step are listed on the device once per verify call (attn_worklist_kernel) and a
+// persistent grid -- exactly the workgroups that are resident at once -- works the lists off: wavefront units by a
+// static deal, workgroup units through a counter (see attn_verify_mfma).  K and V are read with non-temporal loads.
+// A second entry, attn_prefill_mfma, runs the same sub-tile routine causally over a chunk of consecutive tokens.
 #include "hs_internal.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
