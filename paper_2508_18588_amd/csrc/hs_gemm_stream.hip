@@ -313,7 +313,18 @@ __global__ __launch_bounds__(256) void hs_gemm_stream(const bf16_t* __restrict__
     // weight slab meet in one L2.
     // (With a single pass the id is the group: no padding of the grid, a workgroup that only exits still has to
     // wait for a compute unit with this kernel's LDS free.)
-    int group = blockIdx.x, pass = 0;
+    int group = blockIdx.x, pass = 0, chunk = blockIdx.y;
+    if (n_pass == 1 && gridDim.y > 1) {
+        // Split-K, one pass: the workgroups that land on one XCD (ids congruent mod 8) take consecutive
+        // (chunk, group) pairs, i.e. one or two K chunks -- the slice of the activations they re-read then fits
+        // that XCD's L2 (all chunks together, e.g. 8 MB for the down projection at 220 rows, do not).
+        const int total = gridDim.x * gridDim.y, id = blockIdx.x + gridDim.x * blockIdx.y;
+        const int xcd = id & 7, slot = id >> 3;
+        const int full = total >> 3, extra = total & 7;          // XCDs 0 .. extra-1 hold one workgroup more
+        const int w = xcd * full + min(xcd, extra) + slot;
+        chunk = w / (int)gridDim.x;
+        group = w - chunk * (int)gridDim.x;
+    }
     if (n_pass > 1) {
         const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
         group = (local / n_pass) * 8 + xcd;
@@ -321,10 +332,10 @@ __global__ __launch_bounds__(256) void hs_gemm_stream(const bf16_t* __restrict__
     }
     if (group >= n_groups) return;
     p.n0 = group * NCOLS;
-    p.chunk = blockIdx.y;
+    p.chunk = chunk;
     p.w_once = n_pass == 1;
     const int nk = K / BK;
-    p.kt0 = blockIdx.y * tpc;
+    p.kt0 = chunk * tpc;
     p.kt1 = min(nk, p.kt0 + tpc);
 
     // Weight loader geometry: instruction j of wavefront w fills the 1 KB block (w + 4j) of a tile = rows 8w..8w+7
