@@ -36,7 +36,7 @@ void layout_workspace(hs_ctx* ctx) {
     w.q = take(M * qh * 2);
     w.attn = take(M * qh * 2);
     w.act = take(M * (size_t)d.d_ffn * 2);
-    w.part_o = take(M * d.n_q_heads * (size_t)ctx->max_parts * d.head_dim * 4);
+    w.part_o = take(M * d.n_q_heads * (size_t)ctx->max_parts * d.head_dim * 2);   // fp16
     w.part_ml = take(M * d.n_q_heads * (size_t)ctx->max_parts * 2 * 4);
     w.logits = take(M * (size_t)d.vocab * 4);
     w.draft_best = take((size_t)l.max_batch * std::max(l.c_max, l.g_max) * ctx->max_segs * 8);

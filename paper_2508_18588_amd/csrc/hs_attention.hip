@@ -145,22 +145,29 @@ __device__ inline void load_query_tile(const bf16_t* q, const uint64_t* anc_mask
     }
 }
 
-// Partial result of one partition for the lane's row: unnormalised O, running max (log2 domain) and sum.
+// Partial result of one partition for the lane's row: running max (log2 domain) and sum in fp32, and the partition's
+// own normalised output O / l in fp16 -- a convex combination of V rows, so within fp16's range whenever V is, and
+// rounded 8 times finer than the bf16 result of the merge.  Half the bytes of an fp32 partial: the partial results
+// are the one write stream of the launch, and writes in the middle of the K/V read stream are dear.
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+
 template <int HD>
-__device__ inline void store_partial(const f32x16 (&o)[HD / 32], float m_run, float l_run, float* part_o,
+__device__ inline void store_partial(const f32x16 (&o)[HD / 32], float m_run, float l_run, _Float16* part_o,
                                      float* part_ml, int r0, int rt, int R, int G, int hq, int j, int max_parts,
                                      int part, int half, int l32) {
     int rho = rt * 32 + l32;
     if (rho >= R) return;
     int node = rho / G, g = rho - node * G;
     size_t prow = ((size_t)(r0 + node) * hq + j * G + g) * max_parts + part;
-    float* po = part_o + prow * HD;
+    _Float16* po = part_o + prow * HD;
+    const float inv = l_run > 0.f ? 1.f / l_run : 0.f;   // a partition in which the row sees no key: all zero
 #pragma unroll
     for (int dt = 0; dt < HD / 32; dt++)
 #pragma unroll
         for (int g4 = 0; g4 < 4; g4++) {
-            float4 v = make_float4(o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]);
-            *reinterpret_cast<float4*>(po + dt * 32 + 8 * g4 + 4 * half) = v;
+            f16x4 v = {(_Float16)(o[dt][4 * g4] * inv), (_Float16)(o[dt][4 * g4 + 1] * inv),
+                       (_Float16)(o[dt][4 * g4 + 2] * inv), (_Float16)(o[dt][4 * g4 + 3] * inv)};
+            *reinterpret_cast<f16x4*>(po + dt * 32 + 8 * g4 + 4 * half) = v;
         }
     if (half == 0) {
         part_ml[prow * 2] = m_run;
@@ -177,7 +184,7 @@ struct AttnArgs {
     const int32_t* block_table;
     const int32_t* row_off;
     const uint64_t* anc_mask;
-    float* part_o;
+    _Float16* part_o;
     float* part_ml;
     int max_blocks, n_blocks, max_parts, part_keys, hq, hkv;
     float scale_log2;
@@ -633,7 +640,7 @@ __global__ __launch_bounds__(256, 1) void attn_prefill_mfma(
 // Combine the partitions of one (row, query head) in partition order: one wavefront per (row, head), four per
 // workgroup.  Lane p holds partition p's (max, sum); weights are broadcast from there.
 template <int HD>
-__global__ __launch_bounds__(256) void attn_merge(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+__global__ __launch_bounds__(256) void attn_merge(const _Float16* __restrict__ part_o, const float* __restrict__ part_ml,
                                                    const int32_t* __restrict__ row2seq, const int32_t* __restrict__ row_off,
                                                    const int32_t* __restrict__ seq_len, int batch, int max_parts,
                                                    int part_keys, int hq, bf16_t* __restrict__ out) {
@@ -663,20 +670,21 @@ __global__ __launch_bounds__(256) void attn_merge(const float* __restrict__ part
         // partition order; the values of eight partitions are fetched before the first is added, so that the loop
         // waits for memory once per eight partitions instead of once per partition
         for (int pb = 0; pb < n; pb += 8) {
-            float v[8][HD / 64];
+            _Float16 v[8][HD / 64];
 #pragma unroll
             for (int q = 0; q < 8; q++) {
-                const float* po = part_o + (prow + p0 + min(pb + q, n - 1)) * HD;
+                const _Float16* po = part_o + (prow + p0 + min(pb + q, n - 1)) * HD;
 #pragma unroll
                 for (int i = 0; i < HD / 64; i++) v[q][i] = po[lane + 64 * i];
             }
 #pragma unroll
             for (int q = 0; q < 8; q++) {
                 if (pb + q < n) {
-                    float w = __shfl(wl, pb + q);
-                    den += w * __shfl(ll, pb + q);
+                    // the partition's weight in the whole: exp2(m_p - m) l_p; its output is stored normalised
+                    const float w = __shfl(wl, pb + q) * __shfl(ll, pb + q);
+                    den += w;
 #pragma unroll
-                    for (int i = 0; i < HD / 64; i++) acc[i] += w * v[q][i];
+                    for (int i = 0; i < HD / 64; i++) acc[i] += w * (float)v[q][i];
                 }
             }
         }
@@ -742,7 +750,7 @@ void launch_mfma(const hs_ctx* ctx, int layer, size_t layer_off, const hs_kv_cac
     a.block_table = seq->block_table;
     a.row_off = step->row_off;
     a.anc_mask = step->anc_mask;
-    a.part_o = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_o);
+    a.part_o = reinterpret_cast<_Float16*>(ctx->ws + ctx->lay.part_o);
     a.part_ml = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_ml);
     a.max_blocks = ctx->lim.max_blocks_per_seq;
     a.n_blocks = cache->n_blocks;
@@ -832,7 +840,7 @@ void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const
                                hipStream_t st) {
     if (ctx->flags & HS_FLAG_REFERENCE_KERNELS) return;  // the plain kernel writes the final output itself
     const hs_model_desc& d = ctx->desc;
-    float* part_o = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_o);
+    const _Float16* part_o = reinterpret_cast<const _Float16*>(ctx->ws + ctx->lay.part_o);
     float* part_ml = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_ml);
     dim3 grid(ctx->lim.max_rows, (d.n_q_heads + 3) / 4);
     if (d.head_dim == 128)
