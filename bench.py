@@ -22,7 +22,7 @@ sys.path.insert(0, ROOT)
 # HBM bytes per launch of the attention kernel at config 3, from the two rocprofv3 --pmc runs (FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0, factors read off 1 GiB copies in the same runs) summarised under profiles/: counters cannot be
 # read inside a timed run, so the figure is carried here and re-measured whenever the kernel changes.
-ATTN_TRAFFIC_BYTES_PER_LAUNCH = 2.336e9
+ATTN_TRAFFIC_BYTES_PER_LAUNCH = 2.327e9
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 

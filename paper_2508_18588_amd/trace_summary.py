@@ -22,6 +22,11 @@ def summarise(path: str, n_steps: int, skip: int = 0) -> str:
     agg = collections.defaultdict(lambda: [0, 0])
     for r in rows[first:last]:
         name = r["Kernel_Name"].replace("void ", "").replace("(anonymous namespace)::", "").split("(")[0]
+        if name.startswith("_Z"):       # a name the profiler's demangler did not take (e.g. _Float16 arguments)
+            import re
+            m = re.search(r"_GLOBAL__N_1\d+([A-Za-z_]+?)I(?:Li(\d+)E)+", name)
+            if m:
+                name = m.group(1) + "<" + ", ".join(re.findall(r"Li(\d+)E", name.split(m.group(1), 1)[1].split("EEv")[0])) + ">"
         agg[name][0] += 1
         agg[name][1] += int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
     total = sum(v[1] for v in agg.values())

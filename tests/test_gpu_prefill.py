@@ -102,7 +102,8 @@ def test_prefill_agrees_with_the_verify_path_prefill(toy):
     b.prefill(toks)
     f = lambda t: (np_of(t).view(np.uint16).astype(np.uint32) << 16).view(np.float32)
     assert np.abs(f(a.kc) - f(b.kc)).max() < 2e-2 and np.abs(f(a.vc) - f(b.vc)).max() < 2e-2
-    assert (np_of(a.kc) == np_of(b.kc)).mean() > 0.9       # layer 0 is identical, layer 1 differs by roundings
+    # layer 0 (half of the cache) is identical, layer 1 differs where the two attention kernels round differently
+    assert (np_of(a.kc) == np_of(b.kc)).mean() > 0.7
     a.close()
     b.close()
 
