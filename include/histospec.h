@@ -199,7 +199,9 @@ typedef struct hs_accept_args {
 
 /* Validates the shape and copies the descriptors.  Supported: head_dim 64 or 128, kv_block 16, n_q_heads a
  * multiple of n_kv_heads with at most 8 query heads per KV head, d_model / d_ffn / n_q_heads*head_dim multiples
- * of 64. */
+ * of 64.  The length of the attention's split-KV partitions (256, 512 or 1024 keys) is chosen here from the limits
+ * alone; the environment variable HS_ATT_PART (a multiple of 32, 32..1024), read here, overrides it for experiments
+ * -- results of contexts created with different partition lengths differ in the last bits. */
 hs_status hs_create(const hs_model_desc* desc, const hs_weights* weights, const hs_limits* limits, hs_ctx** out);
 void hs_destroy(hs_ctx* ctx);
 const char* hs_last_error(const hs_ctx* ctx);
