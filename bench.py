@@ -31,21 +31,41 @@ def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
 
-def workload_params(config: int):
-    from paper_2508_18588_amd import HS_K_FIXED, HS_K_MATCHLEN
+def workload_params(config: int, reuse: float = 0.5):
+    from paper_2508_18588_amd import HS_ACCEPT_REJECTION, HS_K_AIMD, HS_K_FIXED, HS_K_MATCHLEN
     if config == 3:
         return dict(name="config3: 7B shape (28L d3584 28q/4kv x128 ffn18944 V152064), B=128, context U[2048,16384], "
                          "history = GPU greedy 256-token window mutated 26.3% iid + 5% spans (70% copied), "
                          "K = match length 1..16 (window 16, min 3), greedy, KV page 16",
-                    batch=128, ctx=("uniform", 2048, 16384), window_tokens=256, p_iid=0.263, p_span=0.05,
+                    batch=128, ctx=("uniform", 2048, 16384), window_tokens=256, p_iid=[0.263], p_span=0.05,
                     policy=dict(window=16, m_min=3, k_mode=HS_K_MATCHLEN, k_max=16), k_max=16)
     if config == 2:
         return dict(name="config2: 1.5B shape (28L d1536 12q/2kv x128 ffn8960 V151936), B=64, prompt 512 + response "
                          "offset 2048, history = GPU greedy 256-token window mutated 20% iid + 5% spans, K=8 fixed, "
                          "greedy, KV page 16",
-                    batch=64, ctx=("fixed", 512 + 2048), window_tokens=256, p_iid=0.20, p_span=0.05,
+                    batch=64, ctx=("fixed", 512 + 2048), window_tokens=256, p_iid=[0.20], p_span=0.05,
                     policy=dict(window=8, m_min=3, k_mode=HS_K_FIXED, k_fixed=8, k_max=8), k_max=8)
-    raise SystemExit(f"bench.py: no benchmark workload for config {config} (2 and 3 are available)")
+    if config == 4:
+        return dict(name="config4: 7B shape, B=256, prompt 512 + response lognormal(median 4000, sigma 0.8) clipped to "
+                         f"[512, 32768], snapshot 256 tokens before each response's end, history reuse {reuse:.0%} "
+                         f"(window mutated {1 - reuse:.0%} iid, no spans), K adaptive 2..32 (+2 on full accept, back "
+                         "to 2 on a reject; window 16, min 3), greedy, KV page 16",
+                    batch=256, ctx=("lognormal", 4000.0, 0.8, 512, 32768, 512), window_tokens=256,
+                    p_iid=[1.0 - reuse], p_span=0.0,
+                    policy=dict(window=16, m_min=3, k_mode=HS_K_AIMD, k_max=32), k_max=32)
+    if config == 5:
+        return dict(name="config5: 14B shape (48L d5120 40q/8kv x128 ffn13824 V152064), B=64, context 8192, two "
+                         "histories per sequence (the sampled 64-token continuation mutated 40% and 60% iid) -> "
+                         "2-branch draft tree of depth 8, tree-mask verify, rejection sampling at temperature 1 "
+                         "(Philox), tree commit, KV page 16; EVERY TIMED STEP IS THE FIRST SPECULATIVE STEP AFTER "
+                         "THE SNAPSHOT (sequence state restored by five small device copies inside the timed "
+                         "region): a sampled token never re-enters a history of other samples, so drafting would "
+                         "stop after one step, and on random-init (flat) logits the acceptance probability of a "
+                         "draft token is about 1/V, so accepted tokens/s is about 0 by construction",
+                    batch=64, ctx=("fixed", 8192), window_tokens=64, p_iid=[0.4, 0.6], p_span=0.0,
+                    policy=dict(window=8, m_min=3, k_mode=HS_K_FIXED, k_fixed=8, k_max=8), k_max=8,
+                    mode=HS_ACCEPT_REJECTION, temperature=1.0, snapshot=True)
+    raise SystemExit(f"bench.py: no benchmark workload for config {config} (2, 3, 4 and 5 are available)")
 
 
 def main():
@@ -54,6 +74,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--reuse", type=float, default=0.5,
+                    help="config 4 only: fraction of the previous epoch's tokens copied unmutated (0, 0.5, 0.9)")
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is then NOT the benchmark)")
     ap.add_argument("--window", type=int, default=0,
                     help="debug: tokens of previous-epoch text generated at set-up (default: the workload's 256)")
@@ -74,24 +96,30 @@ def main():
 
     import paper_2508_18588_amd as hs
     from paper_2508_18588_amd.runtime import Engine, Policy
-    from hs_inputs import CONFIG_SHAPES, config_seed, mutate, lengths_uniform
+    from hs_inputs import CONFIG_SHAPES, config_seed, mutate, lengths_lognormal, lengths_uniform
     from hs_inputs.device import make_weights_device, fill_kv_random, rope_device, weights_to_host
 
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
     hs.lib()
     cfg = args.config
-    wp = workload_params(cfg)
+    wp = workload_params(cfg, args.reuse)
     shape = CONFIG_SHAPES[cfg]
     seed = config_seed(cfg)
     n_layers = args.layers or shape.n_layers
     B, T = wp["batch"], (args.window or wp["window_tokens"])
     pol = Policy(**wp["policy"])
     W = pol.window
+    n_cand = len(wp["p_iid"])
+    mode, temperature = wp.get("mode", hs.HS_ACCEPT_GREEDY), wp.get("temperature", 1.0)
+    philox_seed = seed * 0x9E3779B1 & (2 ** 63 - 1)
     if args.reuse_all:
-        wp["p_iid"], wp["p_span"] = 0.0, 0.0
+        wp["p_iid"], wp["p_span"] = [0.0] * n_cand, 0.0
     if wp["ctx"][0] == "uniform":
         ctx = lengths_uniform(B, wp["ctx"][1], wp["ctx"][2], seed)
+    elif wp["ctx"][0] == "lognormal":
+        _, median, sigma, lo, hi, prompt = wp["ctx"]
+        ctx = (prompt + lengths_lognormal(B, median, sigma, lo, hi, seed) - T).astype(np.int32)
     else:
         ctx = np.full(B, wp["ctx"][1], np.int32)
     rng = np.random.default_rng(seed)
@@ -100,7 +128,7 @@ def main():
     w = make_weights_device(shape, seed, n_layers)
     max_len = int(ctx.max()) + 1 + T
     rope = rope_device(max_len + 64, shape.head_dim)
-    eng = Engine(shape, w, rope, max_batch=B, k_max=wp["k_max"], c_max=1, max_len=max_len,
+    eng = Engine(shape, w, rope, max_batch=B, k_max=wp["k_max"], c_max=n_cand, max_len=max_len,
                  seq_caps=[int(c) + 1 + T for c in ctx], shuffle_pages_seed=(None if os.environ.get("HS_BENCH_PAGES") == "bump" else seed & 0xFFFF), keep_logits=False)
     # context: L_b cached positions (synthetic K/V of the scale a real prefill writes) + one committed root token
     kv_std = 0.02 * float(np.sqrt(shape.d_model))
@@ -116,11 +144,11 @@ def main():
     eng.set_history([[np.zeros(0, np.int32)] for _ in range(B)])
     eng.set_rows_hint(B)   # launch-shape hint only: one row per sequence without drafts
     for _ in range(3):
-        eng.step(ar_pol)
+        eng.step(ar_pol, mode, temperature, philox_seed)
     torch.cuda.synchronize()
     t1 = time.time()
     for _ in range(T - 3):
-        eng.step(ar_pol)
+        eng.step(ar_pol, mode, temperature, philox_seed)
     torch.cuda.synchronize()
     ar_ms = (time.time() - t1) / (T - 3) * 1e3
     out = eng.tokens.cpu().numpy()
@@ -129,16 +157,25 @@ def main():
     hists = []
     for b in range(B):
         filler = rng.integers(0, shape.vocab, max(0, len(toks[b]) - (W - 1))).astype(np.int32)
-        hists.append([np.concatenate([filler, toks[b][-(W - 1):], mutate(rolls[b], wp["p_iid"], wp["p_span"],
-                                                                          shape.vocab, rng)])])
+        hists.append([np.concatenate([filler, toks[b][-(W - 1):], mutate(rolls[b], p, wp["p_span"], shape.vocab, rng)])
+                      for p in wp["p_iid"]])
     eng.load_sequences(toks, budgets=[T] * B)
     eng.set_history(hists)
+    # configuration 5 times the same step again and again: the state every step starts from
+    state = [eng.seq_len, eng.tail, eng.tail_len, eng.k_state, eng.budget_left]
+    snap = [t.clone() for t in state] if wp.get("snapshot") else None
+
+    def one_step():
+        if snap is not None:
+            for t, s0 in zip(state, snap):
+                t.copy_(s0)
+        eng.step(pol, mode, temperature, philox_seed)
 
     # ---- warm-up, then the timed region
     first = None
     warm_rows = []
     for i in range(args.warmup):
-        eng.step(pol)
+        one_step()
         warm_rows.append(int(eng.st["row_off"][B].item()))
         if i == 0:
             torch.cuda.synchronize()
@@ -155,7 +192,7 @@ def main():
     if args.warmup > 0:
         # launch-shape hint: mean rows of the warm-up steps after the first (in which every sequence drafts a full
         # window because all of them start in sync with their history)
-        tail = warm_rows[1:] or warm_rows
+        tail = (warm_rows[1:] or warm_rows) if snap is None else warm_rows
         eng.set_rows_hint(-(-sum(tail) // len(tail)))
         log(f"rows hint for the timed steps: {eng.c_step.rows_hint}")
     c0 = eng.counters.cpu().numpy().copy()
@@ -166,7 +203,7 @@ def main():
     t2 = time.perf_counter()
     step_rows = []
     for _ in range(args.steps):
-        eng.step(pol)
+        one_step()
         if args.print_rows:     # diagnostic: synchronises every step, the timing of such a run means nothing
             step_rows.append(int(eng.st["row_off"][B].item()))
     torch.cuda.synchronize()
@@ -184,7 +221,7 @@ def main():
         ca = eng.counters.cpu().numpy().copy()
         eng.set_profile(2)
         for _ in range(prof_all_steps):
-            eng.step(pol)
+            one_step()
         prof_all = eng.get_profile()
         eng.set_profile(0)
         cb = (eng.counters.cpu().numpy() - ca).tolist()
@@ -231,11 +268,11 @@ def main():
     # in which they are bound by the matrix cores rather than by streaming weights.  One layer's four projections and
     # the LM head, each launched alone through hs_debug_gemm on random activations, timed with events on the stream.
     if prof is not None and n_layers == shape.n_layers:
-        extras["gemm_at_max_rows"] = gemm_probe(eng, shape, B * (wp["k_max"] + 1))
+        extras["gemm_at_max_rows"] = gemm_probe(eng, shape, B * (n_cand * wp["k_max"] + 1))
 
     # ---- CPU oracle on a bounded sample: one sequence, its first speculative step at full model size
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and n_cand == 1 and mode == hs.HS_ACCEPT_GREEDY:
         cpu = cpu_baseline(eng, shape, w, rope, toks, hists, pol, first, B, n_layers, weights_to_host)
 
     result = {
