@@ -247,18 +247,25 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
         for (int mi = 0; mi < NMI; mi++) {
             const int row0 = p.m0 + 32 * (wave + 4 * mi) + lr;
             if (EPI == HS_EPI_SWIGLU_BF16) {
+                // Lanes c (gate) and c+16 (up) hold the two pre-activations of output column c.  Elements are taken
+                // in pairs: after one exchange the gate lanes finish the row of element e and the up lanes the row
+                // of element e+1, so every lane computes an output.  (32-bit element offsets: the host checks that
+                // the output stays below 4 GiB.)
                 bf16_t* C = reinterpret_cast<bf16_t*>(p.Cout);
+                const bool up_lane = (lc & 16) != 0;
+                const int rbase = row0 + (up_lane ? 1 : 0);
 #pragma unroll
                 for (int ni = 0; ni < NU; ni++) {
                     const int col = p.n0 + 16 * ni + (lc & 15);
 #pragma unroll
-                    for (int e = 0; e < 16; e++) {
-                        const float own = acc[mi][ni][e];
-                        const float other = __shfl_xor(own, 16);  // lanes c and c+16: gate and up of column c
-                        const int row = row0 + 8 * (e >> 2) + (e & 3);
-                        if (lc < 16 && col < p.N && row < p.M) {
-                            const float s = own / (1.f + __expf(-own));
-                            C[(size_t)row * p.N + col] = f32_to_bf16(s * other);
+                    for (int e = 0; e < 16; e += 2) {
+                        const float a0 = acc[mi][ni][e], a1 = acc[mi][ni][e + 1];
+                        const float got = __shfl_xor(up_lane ? a0 : a1, 16);
+                        const float gate = up_lane ? got : a0, up = up_lane ? a1 : got;
+                        const int row = rbase + 8 * (e >> 2) + (e & 3);
+                        if (col < p.N && row < p.M) {
+                            const float s = gate * __builtin_amdgcn_rcpf(1.f + __expf(-gate));
+                            C[(unsigned)row * (unsigned)p.N + (unsigned)col] = f32_to_bf16(s * up);
                         }
                     }
                 }
