@@ -105,21 +105,6 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
     };
     // Hand-over number h (h < kt0 before the loop, then in the middle of tile h): first the activation tile h+SA,
     // then the weight tile h+SW.  The issue order fixes the wait counts below.
-    // load number l of hand-over h, in issue order: the activation blocks, then the weight blocks
-    auto load_one = [&](int h, int l) {
-        if (l < 4 * MT) {
-            if (l < n_a && h + SA < p.kt1) {
-                const unsigned off = (unsigned)min(a_row + 32 * l, p.M - 1) * row_pitch + a_chunk;
-                load_to_lds_16(p.A + (size_t)(h + SA) * ROW_BYTES, off,
-                               smem_off + ((h + SA) % SA) * A_STAGE + wave * 1024 + l * 4096);
-            }
-        } else if (h + SW < p.kt1) {
-            const unsigned char* wsrc = w_mine + (size_t)(h + SW) * ROW_BYTES;
-            const unsigned wdst = smem_off + W_RING + ((h + SW) % SW) * W_STAGE + wave * 1024 + (l - 4 * MT) * 4096;
-            if (p.w_once) load_to_lds_16_stream(wsrc, w_off[l - 4 * MT], wdst);
-            else load_to_lds_16(wsrc, w_off[l - 4 * MT], wdst);
-        }
-    };
     auto issue_for = [&](int h) {
         if (h + SA >= p.kt0 && h + SA < p.kt1) issue_a(h + SA);
         if (h + SW >= p.kt0 && h + SW < p.kt1) issue_w(h + SW);
@@ -147,19 +132,36 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-    // prologue: the hand-overs a longer-running loop would have made before tile kt0, the last one as in the loop
+    // prologue: the hand-overs a longer-running loop would have made before tile kt0; of the last one only the
+    // activation part (a multiplying wavefront issues its weight part during the first half of tile kt0, see below)
 #pragma unroll
     for (int h = -SW; h < -1; h++) issue_for(p.kt0 + h);
     wait_tile(p.kt0);
     __builtin_amdgcn_s_barrier();
-    issue_for(p.kt0 - 1);
+    if (NMI == 0) issue_for(p.kt0 - 1);
+    else if (p.kt0 - 1 + SA < p.kt1) issue_a(p.kt0 - 1 + SA);
+
+    // Ring positions, kept incrementally: a wavefront issues one instruction at a time and nothing else while it does,
+    // so every scalar instruction between two MFMAs (a modulo, a guard, an address) is time the matrix pipe may
+    // idle -- with more than about four of them per MFMA it does.
+    int a_cur = (int)((unsigned)p.kt0 % SA) * A_STAGE;                   // stage of tile kt ...
+    int a_nxt = a_cur + A_STAGE == SA * A_STAGE ? 0 : a_cur + A_STAGE;   // ... and of tile kt+1
+    int w_cur = (int)((unsigned)p.kt0 % SW) * W_STAGE;
+    int w_nxt = w_cur + W_STAGE == SW * W_STAGE ? 0 : w_cur + W_STAGE;
+    int w_prv = w_cur == 0 ? (SW - 1) * W_STAGE : w_cur - W_STAGE;       // stage of tile kt-1 = of tile kt-1+SW
+    const unsigned char* a_src = p.A + (size_t)(p.kt0 + SA) * ROW_BYTES;          // activation tile of hand-over kt
+    const unsigned char* w_src = w_mine + (size_t)(p.kt0 - 1 + SW) * ROW_BYTES;   // weight tile of hand-over kt-1
+    unsigned a_off[4 * MT];
+#pragma unroll
+    for (int l = 0; l < 4 * MT; l++) a_off[l] = (unsigned)min(a_row + 32 * l, p.M - 1) * row_pitch + a_chunk;
 
     bf16x8 fa[BK / 16][NM], fb[BK / 16][NU];
-    // fragments of k-step KS of tile KT: lane l reads tile row l%32, k-chunk 2*KS + l/32, at its swizzled position
-#define HS_FRAGS(KT, KS)                                                                                         \
+    // fragments of k-step KS of the tile whose stages start at A_ / W_: lane l reads tile row l%32, k-chunk
+    // 2*KS + l/32, at its swizzled position
+#define HS_FRAGS(A_, W_, KS)                                                                                     \
     if (NMI > 0) {                                                                                               \
-        const unsigned char* sta_ = smem + ((KT) % SA) * A_STAGE + wave * TILE_BYTES + frag_row;                 \
-        const unsigned char* stw_ = smem + W_RING + ((KT) % SW) * W_STAGE + frag_row;                            \
+        const unsigned char* sta_ = smem + (A_) + wave * TILE_BYTES + frag_row;                                  \
+        const unsigned char* stw_ = smem + W_RING + (W_) + frag_row;                                             \
         const int pos_ = ((2 * (KS) + g) ^ fl) << 4;                                                             \
         _Pragma("unroll") for (int ni = 0; ni < NU; ni++)                                                        \
             fb[KS][ni] = *reinterpret_cast<const bf16x8*>(stw_ + ni * TILE_BYTES + pos_);                        \
@@ -177,20 +179,77 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                       \
     }                                                                                                            \
     __builtin_amdgcn_sched_group_barrier(0x008, NMI * NU - (NMI + NU) > 0 ? NMI * NU - (NMI + NU) : 0, 0);
+    // Half a tile in a pinned order: k-steps KS0 and KS0+1 are multiplied; behind each MFMA come its share of the
+    // fragment reads of k-steps (KS0+2)%4 and (KS0+3)%4 from the stages A_ / W_, and its share of the NLD loads
+    // that LOAD(l) issues -- one after the other, because a wavefront that issues a dozen loads back to back
+    // stalls on the address path while its matrix pipe runs dry.
+#define HS_HALF(KS0, A_, W_, NLD, LOAD)                                                                          \
+    {                                                                                                            \
+        const unsigned char* sta_ = smem + (A_) + wave * TILE_BYTES + frag_row;                                  \
+        const unsigned char* stw_ = smem + W_RING + (W_) + frag_row;                                             \
+        constexpr int NMF = 2 * NM * NU;                                                                         \
+        _Pragma("unroll") for (int q = 0; q < NMF; q++) {                                                        \
+            const int ks = (KS0) + q / (NM * NU), kr = (ks + 2) % 4, mi = (q % (NM * NU)) / NU, ni = q % NU;     \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][mi], fb[ks][ni], acc[mi][ni], 0, 0, 0); \
+            const int pos_ = ((2 * kr + g) ^ fl) << 4;                                                           \
+            _Pragma("unroll") for (int r = (q % (NM * NU)) * (NU + NM) / (NM * NU);                              \
+                                   r < (q % (NM * NU) + 1) * (NU + NM) / (NM * NU); r++) {                       \
+                if (r < NU) fb[kr][r] = *reinterpret_cast<const bf16x8*>(stw_ + r * TILE_BYTES + pos_);          \
+                else fa[kr][r - NU] = *reinterpret_cast<const bf16x8*>(sta_ + (r - NU) * 4 * TILE_BYTES + pos_); \
+            }                                                                                                    \
+            _Pragma("unroll") for (int l = q * (NLD) / NMF; l < (q + 1) * (NLD) / NMF; l++) { LOAD(l) }          \
+            __builtin_amdgcn_sched_barrier(0);                                                                   \
+        }                                                                                                        \
+    }
+    // the loads of a tile go out in two parts: the activation blocks of hand-over kt in the second half of tile kt,
+    // the weight blocks of the same hand-over in the first half of tile kt+1 (same order as issue_for: the wait
+    // counts do not change), so that they reach the address path evenly
+#define HS_LOAD_A(l)                                                                                             \
+    if ((l) < na_eff) load_to_lds_16(a_src, a_off[l], a_dst + (l) * 4096);
+#define HS_LOAD_W_ONCE(l)                                                                                        \
+    if (w_on) load_to_lds_16_stream(w_src, w_off[l], w_dst + (l) * 4096);
+#define HS_LOAD_W_KEEP(l)                                                                                        \
+    if (w_on) load_to_lds_16(w_src, w_off[l], w_dst + (l) * 4096);
 
-    HS_FRAGS(p.kt0, 0)
-    HS_FRAGS(p.kt0, 1)
+    HS_FRAGS(a_cur, w_cur, 0)
+    HS_FRAGS(a_cur, w_cur, 1)
     int kt = p.kt0;
     for (; kt + 1 < p.kt1; kt++) {
         __builtin_amdgcn_sched_barrier(0);
-        HS_FRAGS(kt, 2)
-        HS_MFMAS(0)
-        HS_INTERLEAVE()
-        __builtin_amdgcn_sched_barrier(0);
-        HS_FRAGS(kt, 3)
-        HS_MFMAS(1)
-        HS_INTERLEAVE()
-        __builtin_amdgcn_sched_barrier(0);
+        // First half of tile kt: k-steps 0 and 1, the fragments of k-steps 2 and 3 of the same tile, and the weight
+        // blocks of hand-over kt-1 (tile kt-1+SW, into the stage that tile kt-1 left).
+        if (NMI > 0) {
+            const bool w_on = kt - 1 + SW < p.kt1;
+            const unsigned w_dst = smem_off + W_RING + w_prv + wave * 1024;
+            HS_FRAGS(a_cur, w_cur, 2)
+            HS_MFMAS(0)
+            HS_INTERLEAVE()
+            __builtin_amdgcn_sched_barrier(0);
+            if (w_on) {
+                if (p.w_once) {
+#pragma unroll
+                    for (int l = 0; l < NLW / 2; l++) load_to_lds_16_stream(w_src, w_off[l], w_dst + l * 4096);
+                } else {
+#pragma unroll
+                    for (int l = 0; l < NLW / 2; l++) load_to_lds_16(w_src, w_off[l], w_dst + l * 4096);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            HS_FRAGS(a_cur, w_cur, 3)
+            HS_MFMAS(1)
+            HS_INTERLEAVE()
+            __builtin_amdgcn_sched_barrier(0);
+            if (w_on) {
+                if (p.w_once) {
+#pragma unroll
+                    for (int l = NLW / 2; l < NLW; l++) load_to_lds_16_stream(w_src, w_off[l], w_dst + l * 4096);
+                } else {
+#pragma unroll
+                    for (int l = NLW / 2; l < NLW; l++) load_to_lds_16(w_src, w_off[l], w_dst + l * 4096);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
         // Hand-over: every fragment read of tile kt has been issued; once they have returned (lgkmcnt) and all
         // wavefronts have met, the slots of tile kt are free to be refilled.  Tile kt+1 must have landed: each
         // wavefront waits for its own part before the barrier (a bare barrier: a fenced one would wait for the
@@ -198,39 +257,31 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
         wait_tile(kt + 1);
         __builtin_amdgcn_s_waitcnt((63 & 15) | ((63 >> 4) << 14) | (7 << 4) | (0 << 8));  // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
-        // Second half of tile kt: k-steps 2 and 3, the first two fragment sets of tile kt+1, and the loads of this
-        // hand-over -- one after the other behind single MFMAs in a pinned order, because a wavefront that issues a
-        // dozen loads back to back stalls on the address path while its matrix pipe runs dry.
+        // Second half of tile kt: k-steps 2 and 3, the first two fragment sets of tile kt+1, and the activation
+        // blocks of this hand-over (tile kt+SA, into the stage of tile kt).
         if (NMI == 0) {
             issue_for(kt);
         } else {
-            const unsigned char* sta_ = smem + ((kt + 1) % SA) * A_STAGE + wave * TILE_BYTES + frag_row;
-            const unsigned char* stw_ = smem + W_RING + ((kt + 1) % SW) * W_STAGE + frag_row;
-            constexpr int NMF = 2 * NM * NU, TL = 4 * MT + NU;
-#pragma unroll
-            for (int q = 0; q < NMF; q++) {
-                const int ks = 2 + q / (NM * NU), mi = (q % (NM * NU)) / NU, ni = q % NU;
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][mi], fb[ks][ni], acc[mi][ni], 0, 0, 0);
-                // this MFMA's share of the k-step's NU + NM fragment reads
-                const int pos_ = ((2 * (ks - 2) + g) ^ fl) << 4;
-#pragma unroll
-                for (int r = (q % (NM * NU)) * (NU + NM) / (NM * NU); r < (q % (NM * NU) + 1) * (NU + NM) / (NM * NU); r++) {
-                    if (r < NU) fb[ks - 2][r] = *reinterpret_cast<const bf16x8*>(stw_ + r * TILE_BYTES + pos_);
-                    else fa[ks - 2][r - NU] = *reinterpret_cast<const bf16x8*>(sta_ + (r - NU) * 4 * TILE_BYTES + pos_);
-                }
-#pragma unroll
-                for (int l = q * TL / NMF; l < (q + 1) * TL / NMF; l++) load_one(kt, l);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            int na_eff = kt + SA < p.kt1 ? n_a : 0;
+            asm volatile("" : "+s"(na_eff));  // one scalar compare per slot below, not a mask expression
+            const unsigned a_dst = smem_off + a_cur + wave * 1024;
+            HS_HALF(2, a_nxt, w_nxt, 4 * MT, HS_LOAD_A)
         }
+        a_cur = a_nxt;
+        a_nxt = a_nxt + A_STAGE == SA * A_STAGE ? 0 : a_nxt + A_STAGE;
+        w_prv = w_cur;
+        w_cur = w_nxt;
+        w_nxt = w_nxt + W_STAGE == SW * W_STAGE ? 0 : w_nxt + W_STAGE;
+        a_src += ROW_BYTES;
+        w_src += ROW_BYTES;
     }
     // last tile of the chunk: nothing follows it
     __builtin_amdgcn_sched_barrier(0);
-    HS_FRAGS(kt, 2)
+    HS_FRAGS(a_cur, w_cur, 2)
     HS_MFMAS(0)
     HS_INTERLEAVE()
     __builtin_amdgcn_sched_barrier(0);
-    HS_FRAGS(kt, 3)
+    HS_FRAGS(a_cur, w_cur, 3)
     HS_MFMAS(1)
     HS_INTERLEAVE()
     __builtin_amdgcn_sched_barrier(0);
@@ -239,6 +290,10 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
 #undef HS_FRAGS
 #undef HS_MFMAS
 #undef HS_INTERLEAVE
+#undef HS_HALF
+#undef HS_LOAD_A
+#undef HS_LOAD_W_ONCE
+#undef HS_LOAD_W_KEEP
 
     // Epilogue.  Accumulator element e of a 32x32 tile: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
     if (NMI > 0) {
