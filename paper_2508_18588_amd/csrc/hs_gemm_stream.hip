@@ -214,67 +214,74 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
     HS_FRAGS(a_cur, w_cur, 0)
     HS_FRAGS(a_cur, w_cur, 1)
     int kt = p.kt0;
-    for (; kt + 1 < p.kt1; kt++) {
-        __builtin_amdgcn_sched_barrier(0);
-        // First half of tile kt: k-steps 0 and 1, the fragments of k-steps 2 and 3 of the same tile, and the weight
-        // blocks of hand-over kt-1 (tile kt-1+SW, into the stage that tile kt-1 left).
-        if (NMI > 0) {
-            const bool w_on = kt - 1 + SW < p.kt1;
-            const unsigned w_dst = smem_off + W_RING + w_prv + wave * 1024;
-            HS_FRAGS(a_cur, w_cur, 2)
-            HS_MFMAS(0)
-            HS_INTERLEAVE()
-            __builtin_amdgcn_sched_barrier(0);
-            if (w_on) {
-                if (p.w_once) {
-#pragma unroll
-                    for (int l = 0; l < NLW / 2; l++) load_to_lds_16_stream(w_src, w_off[l], w_dst + l * 4096);
-                } else {
-#pragma unroll
-                    for (int l = 0; l < NLW / 2; l++) load_to_lds_16(w_src, w_off[l], w_dst + l * 4096);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            HS_FRAGS(a_cur, w_cur, 3)
-            HS_MFMAS(1)
-            HS_INTERLEAVE()
-            __builtin_amdgcn_sched_barrier(0);
-            if (w_on) {
-                if (p.w_once) {
-#pragma unroll
-                    for (int l = NLW / 2; l < NLW; l++) load_to_lds_16_stream(w_src, w_off[l], w_dst + l * 4096);
-                } else {
-#pragma unroll
-                    for (int l = NLW / 2; l < NLW; l++) load_to_lds_16(w_src, w_off[l], w_dst + l * 4096);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // Hand-over: every fragment read of tile kt has been issued; once they have returned (lgkmcnt) and all
-        // wavefronts have met, the slots of tile kt are free to be refilled.  Tile kt+1 must have landed: each
-        // wavefront waits for its own part before the barrier (a bare barrier: a fenced one would wait for the
-        // tiles in flight as well).
-        wait_tile(kt + 1);
-        __builtin_amdgcn_s_waitcnt((63 & 15) | ((63 >> 4) << 14) | (7 << 4) | (0 << 8));  // lgkmcnt(0)
-        __builtin_amdgcn_s_barrier();
-        // Second half of tile kt: k-steps 2 and 3, the first two fragment sets of tile kt+1, and the activation
-        // blocks of this hand-over (tile kt+SA, into the stage of tile kt).
-        if (NMI == 0) {
-            issue_for(kt);
-        } else {
-            int na_eff = kt + SA < p.kt1 ? n_a : 0;
-            asm volatile("" : "+s"(na_eff));  // one scalar compare per slot below, not a mask expression
-            const unsigned a_dst = smem_off + a_cur + wave * 1024;
-            HS_HALF(2, a_nxt, w_nxt, 4 * MT, HS_LOAD_A)
-        }
-        a_cur = a_nxt;
-        a_nxt = a_nxt + A_STAGE == SA * A_STAGE ? 0 : a_nxt + A_STAGE;
-        w_prv = w_cur;
-        w_cur = w_nxt;
-        w_nxt = w_nxt + W_STAGE == SW * W_STAGE ? 0 : w_nxt + W_STAGE;
-        a_src += ROW_BYTES;
-        w_src += ROW_BYTES;
+    // One tile of the k-loop.  A compare and a branch in front of a load cost the matrix pipe about 17 clocks, so
+    // the steady state (kt + SW < kt1: every load of both parts exists, the wait count is a constant) comes in two
+    // forms: G = 0 for a wavefront whose activation slots are all live (no guard at all), G = 2 with one guard per
+    // activation slot (issuing the dead slots anyway, re-reading row M-1, costs more than the guards).  G = 1: the
+    // last SW-1 tiles before the final one, with every load guarded.
+    // First half of tile kt: k-steps 0 and 1, the fragments of k-steps 2 and 3 of the same tile, and the weight
+    // blocks of hand-over kt-1 (tile kt-1+SW, into the stage that tile kt-1 left), in two bursts.
+    // Hand-over: every fragment read of tile kt has been issued; once they have returned (lgkmcnt) and all
+    // wavefronts have met, the slots of tile kt are free to be refilled.  Tile kt+1 must have landed: each
+    // wavefront waits for its own part before the barrier (a bare barrier: a fenced one would wait for the
+    // tiles in flight as well).
+    // Second half of tile kt: k-steps 2 and 3, the first two fragment sets of tile kt+1, and the activation
+    // blocks of this hand-over (tile kt+SA, into the stage of tile kt).
+#define HS_W_BURST(L0, L1)                                                                                       \
+    if (w_on) {                                                                                                  \
+        if (p.w_once) {                                                                                          \
+            _Pragma("unroll") for (int l = (L0); l < (L1); l++)                                                  \
+                load_to_lds_16_stream(w_src, w_off[l], w_dst + l * 4096);                                        \
+        } else {                                                                                                 \
+            _Pragma("unroll") for (int l = (L0); l < (L1); l++) load_to_lds_16(w_src, w_off[l], w_dst + l * 4096); \
+        }                                                                                                        \
     }
+#define HS_TILE(G)                                                                                               \
+    {                                                                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                                                       \
+        if (NMI > 0) {                                                                                           \
+            const bool w_on = (G) == 1 ? kt - 1 + SW < p.kt1 : true;                                             \
+            const unsigned w_dst = smem_off + W_RING + w_prv + wave * 1024;                                      \
+            HS_FRAGS(a_cur, w_cur, 2)                                                                            \
+            HS_MFMAS(0)                                                                                          \
+            HS_INTERLEAVE()                                                                                      \
+            __builtin_amdgcn_sched_barrier(0);                                                                   \
+            HS_W_BURST(0, NLW / 2)                                                                               \
+            __builtin_amdgcn_sched_barrier(0);                                                                   \
+            HS_FRAGS(a_cur, w_cur, 3)                                                                            \
+            HS_MFMAS(1)                                                                                          \
+            HS_INTERLEAVE()                                                                                      \
+            __builtin_amdgcn_sched_barrier(0);                                                                   \
+            HS_W_BURST(NLW / 2, NLW)                                                                             \
+            __builtin_amdgcn_sched_barrier(0);                                                                   \
+        }                                                                                                        \
+        if ((G) == 1) wait_tile(kt + 1);                                                                         \
+        else HS_WAIT_VMCNT(SW > SA ? NLW : 0);                                                                   \
+        __builtin_amdgcn_s_waitcnt((63 & 15) | ((63 >> 4) << 14) | (7 << 4) | (0 << 8)); /* lgkmcnt(0) */        \
+        __builtin_amdgcn_s_barrier();                                                                            \
+        if (NMI == 0) {                                                                                          \
+            issue_for(kt);                                                                                       \
+        } else {                                                                                                 \
+            int na_eff = (G) == 0 ? 4 * MT : (G) == 2 ? n_a : (kt + SA < p.kt1 ? n_a : 0);                       \
+            if (G) asm volatile("" : "+s"(na_eff)); /* one scalar compare per slot, not a mask expression */     \
+            const unsigned a_dst = smem_off + a_cur + wave * 1024;                                               \
+            HS_HALF(2, a_nxt, w_nxt, 4 * MT, HS_LOAD_A)                                                          \
+        }                                                                                                        \
+        a_cur = a_nxt;                                                                                           \
+        a_nxt = a_nxt + A_STAGE == SA * A_STAGE ? 0 : a_nxt + A_STAGE;                                           \
+        w_prv = w_cur;                                                                                           \
+        w_cur = w_nxt;                                                                                           \
+        w_nxt = w_nxt + W_STAGE == SW * W_STAGE ? 0 : w_nxt + W_STAGE;                                           \
+        a_src += ROW_BYTES;                                                                                      \
+        w_src += ROW_BYTES;                                                                                      \
+    }
+    static_assert(SA == 2, "the constant wait count of the steady state is written for a two-stage activation ring");
+    if (n_a == 4 * MT) {
+        for (; kt + SW < p.kt1; kt++) HS_TILE(0)
+    } else {
+        for (; kt + SW < p.kt1; kt++) HS_TILE(2)
+    }
+    for (; kt + 1 < p.kt1; kt++) HS_TILE(1)
     // last tile of the chunk: nothing follows it
     __builtin_amdgcn_sched_barrier(0);
     HS_FRAGS(a_cur, w_cur, 2)
@@ -291,6 +298,8 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
 #undef HS_MFMAS
 #undef HS_INTERLEAVE
 #undef HS_HALF
+#undef HS_TILE
+#undef HS_W_BURST
 #undef HS_LOAD_A
 #undef HS_LOAD_W_ONCE
 #undef HS_LOAD_W_KEEP
