@@ -335,17 +335,36 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
                 }
             } else {
                 float* C = PARTIAL ? p.part + (size_t)p.chunk * p.m_max * p.N : reinterpret_cast<float*>(p.Cout);
+                // A row tile that lies wholly below M (all but the last one of a pass) is stored without row checks,
+                // through a wavefront-uniform row pointer plus a 32-bit lane offset.
+                const int tile_row = p.m0 + 32 * (wave + 4 * mi);
+                unsigned char* tile = reinterpret_cast<unsigned char*>(C + (size_t)tile_row * p.N);
+                const unsigned lane_bytes = ((unsigned)lr * (unsigned)p.N + (unsigned)(p.n0 + lc)) * 4u;
+                if (tile_row + 32 <= p.M) {
 #pragma unroll
-                for (int ni = 0; ni < NU; ni++) {
-                    const int col = p.n0 + 32 * ni + lc;
-                    if (col >= p.N) continue;
+                    for (int ni = 0; ni < NU; ni++) {
+                        if (p.n0 + 32 * ni + lc >= p.N) continue;
 #pragma unroll
-                    for (int e = 0; e < 16; e++) {
-                        const int row = row0 + 8 * (e >> 2) + (e & 3);
-                        if (row < p.M) {
-                            float* dst = &C[(size_t)row * p.N + col];
+                        for (int e = 0; e < 16; e++) {
+                            unsigned char* rowp = tile + (size_t)(8 * (e >> 2) + (e & 3)) * p.N * 4;
+                            float* dst = reinterpret_cast<float*>(rowp + (lane_bytes + 128u * ni));
                             if (!PARTIAL && EPI == HS_EPI_ADD_F32) *dst += acc[mi][ni][e];
                             else *dst = acc[mi][ni][e];
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int ni = 0; ni < NU; ni++) {
+                        const int col = p.n0 + 32 * ni + lc;
+                        if (col >= p.N) continue;
+#pragma unroll
+                        for (int e = 0; e < 16; e++) {
+                            const int row = row0 + 8 * (e >> 2) + (e & 3);
+                            if (row < p.M) {
+                                float* dst = &C[(size_t)row * p.N + col];
+                                if (!PARTIAL && EPI == HS_EPI_ADD_F32) *dst += acc[mi][ni][e];
+                                else *dst = acc[mi][ni][e];
+                            }
                         }
                     }
                 }
