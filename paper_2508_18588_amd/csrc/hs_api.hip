@@ -40,9 +40,12 @@ void layout_workspace(hs_ctx* ctx) {
     w.part_ml = take(M * d.n_q_heads * (size_t)ctx->max_parts * 2 * 4);
     w.logits = take(M * (size_t)d.vocab * 4);
     w.draft_best = take((size_t)l.max_batch * std::max(l.c_max, l.g_max) * ctx->max_segs * 8);
+    // (the LM head splits K only when the vocabulary is small; it then writes partial sums like the others)
+    const int lm_chunks = hs_gemm_chunks(d.vocab, d.d_model);
     size_t part_cols = std::max({(size_t)hs_gemm_chunks((int)nqkv, d.d_model) * nqkv,
                                  (size_t)hs_gemm_chunks(d.d_model, (int)qh) * d.d_model,
-                                 (size_t)hs_gemm_chunks(d.d_model, d.d_ffn) * d.d_model});
+                                 (size_t)hs_gemm_chunks(d.d_model, d.d_ffn) * d.d_model,
+                                 lm_chunks > 1 ? (size_t)lm_chunks * d.vocab : (size_t)0});
     w.gemm_part_bytes = M * part_cols * 4;
     w.gemm_part = take(w.gemm_part_bytes);
     w.pf_len = take((size_t)l.max_batch * 4);
