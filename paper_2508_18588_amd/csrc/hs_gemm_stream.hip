@@ -1,23 +1,23 @@
-// Weight-streaming bf16 MFMA GEMM for the row counts of a verify step (up to a few hundred draft-tree rows):
-//   C[M,N] (+)= A[M,K] . W[N,K]^T  with the same arithmetic, in the same order, as the tile-grid kernel.
+// The bf16 MFMA GEMM of the projections:  C[M,N] (+)= A[M,K] . W[N,K]^T,  built for the row counts of a verify
+// step (a few hundred draft-tree rows) and run in row passes for more (prefill, wide drafts).
 //
-// At these row counts a projection is bound by streaming its weights from HBM exactly once, with the matrix cores
-// needed at roughly half their rate just to keep up (220 rows: 220 flop per weight byte).  The kernel is laid out
-// around the weight stream:
-//   * One workgroup per (group of NU 32-row weight units, K chunk); unit and chunk counts are chosen by the host
-//     so that one round of workgroups covers the 256 compute units.  A workgroup holds ALL rows (up to 128*MT)
-//     against its weight slab, so every weight byte is fetched once.
+// At a verify step's row count a projection is bound by streaming its weights from HBM exactly once, with the
+// matrix cores needed at roughly half their rate just to keep up (220 rows: 220 flop per weight byte).  The kernel
+// is laid out around the weight stream:
+//   * One workgroup per (group of NU 32-row weight units, K chunk, row pass); unit and chunk counts are chosen by
+//     the host so that one round of workgroups covers the 256 compute units.  A workgroup holds all rows of its
+//     pass (up to 128*MT) against its weight slab, so with one pass every weight byte is fetched once.
 //   * Row tile t (32 rows) belongs to wavefront t % 4.  A wavefront multiplies only the row tiles that exist
 //     (M is read on the device) against all NU weight units; its accumulators stay in registers for the whole chunk.
 //   * Tiles (64 deep in K) travel from global memory straight into LDS (global_load_lds_dwordx4) through an
 //     SA-stage activation ring and an SW-stage weight ring.
-//   * One instruction stream per SIMD: a wavefront issues in order, so a fragment read that waits its turn at the
-//     LDS (four wavefronts share it) keeps the next MFMA from issuing.  The loop is therefore software-pipelined
-//     over k-steps of 16 -- the fragments of step s+2 are read while step s is multiplied, across tile boundaries --
-//     and the reads are interleaved one by one with the MFMAs (sched_group_barrier), so that the matrix pipe always
-//     has its next instruction while the wavefront negotiates the LDS.  The tile hand-over (wait for the loads of
-//     the next tile, workgroup barrier, issue of new loads) sits in the middle of a tile, after the last fragment
-//     read of the current one has been issued.
+//   * One instruction stream per SIMD: a wavefront issues one instruction at a time, so a fragment read that waits
+//     its turn at the LDS, or scalar bookkeeping between two MFMAs, keeps the next MFMA from issuing.  The loop is
+//     therefore software-pipelined over k-steps of 16 -- the fragments of step s+2 are read while step s is
+//     multiplied, across tile boundaries -- the reads and loads are placed one by one behind single MFMAs, and
+//     the steady state of the loop carries no modulo arithmetic and as few guards as possible.  The tile hand-over
+//     (wait for the loads of the next tile, workgroup barrier, issue of new loads) sits in the middle of a tile,
+//     after the last fragment read of the current one has been issued.
 // SwiGLU pairs the gate and up rows of 16 output columns in one 32-row weight unit, so that both pre-activations of
 // a column meet in one MFMA tile (lanes c and c+16).
 #include "hs_gemm_common.h"
