@@ -5,6 +5,8 @@ A "step" is one pass of the whole path -- hs_draft, hs_verify, hs_accept, hs_kv_
 in-flight batch.  The default workload is benchmark configuration 3 (7B-shaped decoder, batch 128, contexts
 uniform 2k..16k, 70 % history similarity, draft length set by the match length, greedy acceptance); all inputs
 are synthetic and seeded (see the design doc for the recipe) and resident in HBM before the timed region starts.
+`--config 2`, `--config 4 --reuse R` and `--config 5` run the other benchmark configurations (5 repeats its first
+speculative step, see its workload string).
 
 Prints ONE JSON line: accepted tokens/s over the timed steps, the roofline of the dominant kernel (verify
 attention, HBM-bound) measured with HIP events on the launching stream, and the CPU oracle timed on a bounded
