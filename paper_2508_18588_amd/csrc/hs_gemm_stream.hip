@@ -312,9 +312,11 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
             const int row0 = p.m0 + 32 * (wave + 4 * mi) + lr;
             if (EPI == HS_EPI_SWIGLU_BF16) {
                 // Lanes c (gate) and c+16 (up) hold the two pre-activations of output column c.  Elements are taken
-                // in pairs: after one exchange the gate lanes finish the row of element e and the up lanes the row
-                // of element e+1, so every lane computes an output.  (32-bit element offsets: the host checks that
-                // the output stays below 4 GiB.)
+                // in pairs: the gate lanes finish the row of element e and the up lanes the row of element e+1, so
+                // every lane computes an output.  One v_permlane16_swap does the exchange: it swaps the odd
+                // 16-lane rows of its first operand (element e: the up values) with the even rows of its second
+                // (element e+1: the gate values), after which the first holds every lane's gate and the second
+                // every lane's up.  (32-bit element offsets: the host checks that the output stays below 4 GiB.)
                 bf16_t* C = reinterpret_cast<bf16_t*>(p.Cout);
                 const bool up_lane = (lc & 16) != 0;
                 const int rbase = row0 + (up_lane ? 1 : 0);
@@ -323,9 +325,9 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
                     const int col = p.n0 + 16 * ni + (lc & 15);
 #pragma unroll
                     for (int e = 0; e < 16; e += 2) {
-                        const float a0 = acc[mi][ni][e], a1 = acc[mi][ni][e + 1];
-                        const float got = __shfl_xor(up_lane ? a0 : a1, 16);
-                        const float gate = up_lane ? got : a0, up = up_lane ? a1 : got;
+                        const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(acc[mi][ni][e]),
+                                                                         __float_as_uint(acc[mi][ni][e + 1]), false, false);
+                        const float gate = __uint_as_float(sw[0]), up = __uint_as_float(sw[1]);
                         const int row = rbase + 8 * (e >> 2) + (e & 3);
                         if (col < p.N && row < p.M) {
                             const float s = gate * __builtin_amdgcn_rcpf(1.f + __expf(-gate));
