@@ -72,7 +72,13 @@ __device__ inline void attn_subtile(const bf16_t* sK, const bf16_t* sV, const bf
     float tmax = s[0];
 #pragma unroll
     for (int e = 1; e < 16; e++) tmax = fmaxf(tmax, s[e]);
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * scale_log2;   // scale > 0: the maximum commutes with it
+    // lanes l and l+32 hold the two halves of a query row: v_permlane32_swap puts the upper half of its first
+    // operand and the lower half of its second in each other's place, so the two results are, in some order, a
+    // lane's own value and its partner's -- enough for a maximum and for a sum, with no trip through the LDS
+    {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+        tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * scale_log2;   // scale > 0: commutes with max
+    }
     float m_new = fmaxf(m_run, tmax);
     float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
     float alpha = fast_exp2(m_run - m_safe);
@@ -84,7 +90,10 @@ __device__ inline void attn_subtile(const bf16_t* sK, const bf16_t* sV, const bf
         psum += p;
         pb[e >> 3][e & 7] = (__bf16)p;
     }
-    psum += __shfl_xor(psum, 32);
+    {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(psum), __float_as_uint(psum), false, false);
+        psum = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
     l_run = l_run * alpha + psum;
     m_run = m_new;
     // the running maximum rarely moves after the first tiles: multiplying by exactly 1 is skipped
