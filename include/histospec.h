@@ -58,7 +58,14 @@ enum { HS_DEV_BLOCK_TABLE_OVERFLOW = 1, HS_DEV_POSITION_OVERFLOW = 2, HS_DEV_ROW
 
 enum { HS_K_FIXED = 0, HS_K_MATCHLEN = 1, HS_K_AIMD = 2 }; /* hs_policy.k_mode */
 enum { HS_ACCEPT_GREEDY = 0, HS_ACCEPT_REJECTION = 1 };    /* hs_accept_args.mode */
-enum { HS_FLAG_REFERENCE_KERNELS = 1 };                    /* hs_set_flags: plain (slow) GEMM/attention kernels */
+/* hs_set_flags.  HS_FLAG_REFERENCE_KERNELS: hs_verify runs plain (slow) GEMM and attention kernels on the same bf16
+ * activation buffers and cache.  HS_FLAG_FP32_ACTIVATIONS: the precise mode -- the plain kernels, with every
+ * activation kept in fp32 between operations (normed input, queries, attention output, feed-forward activation),
+ * sums carried in fp64, and the KV cache holding fp32 values: hs_kv_cache.k / .v then point at float arrays of the
+ * same index layout (twice the bytes), for hs_verify and hs_kv_commit alike.  Only the bf16 weights are rounded, as in
+ * the definition of the model, so logits agree with an fp64 evaluation to fp32 rounding (about 1e-5 of a row's
+ * largest logit at 28 layers).  Slow; meant for checking the fast path's rounding, not for serving. */
+enum { HS_FLAG_REFERENCE_KERNELS = 1, HS_FLAG_FP32_ACTIVATIONS = 2 };
 
 /* Pre-norm decoder: RMSNorm, rotary embedding (pairs i, i + head_dim/2), grouped-query attention with scale
  * 1/sqrt(head_dim), SwiGLU feed-forward, untied LM head, no biases. */
@@ -205,6 +212,8 @@ typedef struct hs_accept_args {
 hs_status hs_create(const hs_model_desc* desc, const hs_weights* weights, const hs_limits* limits, hs_ctx** out);
 void hs_destroy(hs_ctx* ctx);
 const char* hs_last_error(const hs_ctx* ctx);
+/* Changing HS_FLAG_FP32_ACTIVATIONS changes hs_workspace_bytes; a bound workspace that is too small for the new
+ * layout is unbound (bind a larger one before the next call).  hs_prefill supports neither flag. */
 hs_status hs_set_flags(hs_ctx* ctx, uint32_t flags);
 
 /* Scratch the kernels need (activations, split-KV partials, logits).  The caller allocates at least
@@ -273,8 +282,22 @@ hs_status hs_poll_error(hs_ctx* ctx, hs_stream stream, uint32_t* error_bits);
 
 /* Debug view of workspace buffers, valid after hs_verify: 0 final hidden state bf16 [max_rows][d_model]
  * (after the last RMSNorm), 1 last layer's queries bf16 [max_rows][n_q_heads*head_dim] (after rotation),
- * 2 last layer's attention output bf16 (same shape), 3 logits f32 [max_rows][vocab]. */
+ * 2 last layer's attention output bf16 (same shape), 3 logits f32 [max_rows][vocab], 4 residual stream after the
+ * last layer f32 [max_rows][d_model], 5 last layer's feed-forward activation silu(gate)*up bf16 [max_rows][d_ffn].
+ * With HS_FLAG_FP32_ACTIVATIONS buffers 0, 1, 2 and 5 hold floats. */
 hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size_t* bytes);
+
+/* Snapshots of what the LAST layer's projections read, for checking each projection of a real forward pass against
+ * its definition.  With a DEVICE buffer of hs_debug_capture_bytes(ctx) bytes set (NULL switches it off), every
+ * hs_verify copies into four consecutive slots of max_rows * d_model * 4 bytes each:
+ *   0 the normed input of the QKV projection (bf16, or float in the fp32-activation mode: the slot's first bytes),
+ *   1 the residual stream at that point, f32 (the output of every earlier projection summed in),
+ *   2 the normed input of the gate/up projection, 3 the residual stream at that point, f32.
+ * Together with hs_debug_buffer 1, 2, 4, 5 and the cache rows written by the step this pins: QKV (slot 0 -> queries
+ * and K/V), O (attention output -> slot 3 minus slot 1), gate/up (slot 2 -> activation) and down (activation ->
+ * residual after the layer minus slot 3).  The copies are device-to-device on the call's stream. */
+size_t hs_debug_capture_bytes(const hs_ctx* ctx);
+hs_status hs_debug_capture(hs_ctx* ctx, void* dev_ptr, size_t bytes);
 
 /* HOST helper: the table of the speculation gate from a profiled step time.  ms[i] = duration of one decode step
  * (all four calls) at rows[i] rows, rows ascending, n_points >= 2 (straight lines between neighbours, the outer
@@ -296,6 +319,11 @@ hs_status hs_gate_table_build(const float* ms, const int32_t* rows, int32_t n_po
  * it pairs with the sequence-sharded layout described for several GPUs. */
 hs_status hs_plan_allocation(const double* tau, int32_t n_groups, int32_t min_wks, int32_t max_wks, int32_t wks,
                              double t_train, double precision, int32_t* plan, double* d_out);
+
+/* The random generator of hs_accept on its own (Philox-4x32-10, Salmon et al., SC'11; key = (seed lo, seed hi)):
+ * out[i][0..3] = the four output words of counter ctr[i][0..3], i < n.  ctr and out are DEVICE arrays of 4 n words.
+ * hs_accept uses word 0 of counter (position, draw kind, seq_id lo, seq_id hi): u = (word >> 8) / 2^24. */
+hs_status hs_debug_philox(const uint32_t* ctr, uint64_t seed, uint32_t* out, int32_t n, hs_stream stream);
 
 /* One projection on its own, through the same launcher hs_verify uses (unit-level parity tests and timing):
  * C[m, n] (+)= A[m, k] . W[n, k]^T with bf16 operands, K-contiguous, fp32 accumulation in the shape's fixed K

@@ -58,8 +58,7 @@ def lib():
         L.orc_gate_step.argtypes = [i32p, C.c_int, C.c_uint32, C.c_uint32]
         L.orc_gate_table.argtypes = [C.POINTER(C.c_float), i32p, C.c_int, C.c_double, C.c_int, i32p]
         L.orc_gate_table.restype = None
-        L.orc_plan_allocation.argtypes = [f64p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, i32p,
-                                          f64p]
+        L.orc_plan_allocation.argtypes = [f64p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, i32p, f64p]
         L.orc_draft_len.argtypes = [C.c_int] * 4
         L.orc_aimd.argtypes = [C.c_int] * 6
         L.orc_build_tree.argtypes = [C.c_int, C.POINTER(i32p), intp, C.c_int32, C.c_int, i32p, i32p, i32p, u64p,
@@ -77,11 +76,17 @@ def lib():
         L.orc_seq_kv.argtypes = [C.c_void_p, C.c_int, C.c_int, f64p, f64p]
         L.orc_seq_load_kv.argtypes = [C.c_void_p, C.c_int, f64p, f64p]
         L.orc_seq_push.argtypes = [C.c_void_p, C.c_int32, f64p]
+        L.orc_seq_set_trace.argtypes = [C.c_void_p, f64p]
+        L.orc_seq_set_trace.restype = None
         L.orc_argmax.argtypes = [f64p, C.c_int]
         L.orc_tree_logits.argtypes = [C.c_void_p, C.c_int, i32p, i32p, f64p]
+        L.orc_tree_logits_shared.argtypes = [C.c_void_p, C.c_int, i32p, i32p, f64p]
+        L.orc_accept_greedy_bruteforce.argtypes = [C.c_void_p, C.c_int, i32p, i32p, i32p, i32p]
         L.orc_accept_greedy.argtypes = [C.c_int, i32p, i32p, i32p, i32p, i32p]
         L.orc_philox4x32_10.argtypes = [C.POINTER(C.c_uint32)] * 3
         L.orc_philox4x32_10.restype = None
+        L.orc_philox_batch.argtypes = [C.c_int, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+        L.orc_philox_batch.restype = None
         L.orc_uniform.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32]
         L.orc_uniform.restype = C.c_double
         L.orc_accept_stochastic.argtypes = [C.c_int, C.c_int, i32p, i32p, i32p, f64p, C.c_double, C.c_uint64,
@@ -151,16 +156,17 @@ def gate_table(ms, rows, k_bar: float, b_max: int) -> np.ndarray:
     return out
 
 
-def plan_allocation(tau, min_wks: int, max_wks: int, wks: int, t_train: float, p: float = 1.0):
-    """Tier-2 planner (Sec. 6.2): tau[i][k - min_wks] = time of ranking group i on k workers.  Returns
-    (plan int32[N], d) or None if the cluster cannot meet any gradient in the search interval."""
+def plan_allocation(tau, min_wks: int, max_wks: int, wks: int, t_train: float):
+    """Tier-2 planning problem (Sec. 6.2): tau[i][k - min_wks] = time of ranking group i on k workers.  Returns
+    (plan int32[N], d) with d the exact smallest feasible gradient, or None if the cluster cannot meet any gradient
+    in the search interval."""
     t = np.ascontiguousarray(tau, dtype=np.float64)
     n, k = t.shape
     assert k == max_wks - min_wks + 1
     plan = np.zeros(n, np.int32)
     d = np.zeros(1, np.float64)
     ok = lib().orc_plan_allocation(t.ctypes.data_as(C.POINTER(C.c_double)), n, min_wks, max_wks, wks, float(t_train),
-                                   float(p), plan.ctypes.data_as(C.POINTER(C.c_int32)),
+                                   plan.ctypes.data_as(C.POINTER(C.c_int32)),
                                    d.ctypes.data_as(C.POINTER(C.c_double)))
     return (plan, float(d[0])) if ok else None
 
@@ -265,6 +271,17 @@ class Seq:
             raise ValueError("orc_seq_push failed (capacity / token range)")
         return out
 
+    def push_traced(self, token: int):
+        """Push one token; returns (logits, h) with h[(n_layers+1), d_model] the residual stream of that token after
+        the embedding (row 0) and after every layer."""
+        h = np.empty((self.model.n_layers + 1, self.model.shape.d_model), np.float64)
+        lib().orc_seq_set_trace(self.h, h.ctypes.data_as(C.POINTER(C.c_double)))
+        try:
+            out = self.push(token)
+        finally:
+            lib().orc_seq_set_trace(self.h, None)
+        return out, h
+
     def extend(self, tokens):
         """Push tokens, return the logits after the last one (None if empty)."""
         out = None
@@ -290,13 +307,30 @@ class Seq:
         if lib().orc_seq_load_kv(self.h, k.shape[1], k.ctypes.data_as(f64p), v.ctypes.data_as(f64p)) != 0:
             raise IndexError("load_kv")
 
-    def tree_logits(self, tok, parent) -> np.ndarray:
+    def tree_logits(self, tok, parent, plain: bool = False) -> np.ndarray:
+        """Logits of every tree node.  plain=True: the definition (every node's whole path pushed from the cached
+        prefix); default: the shared-prefix walk, pinned equal to it bit for bit and n/2 times cheaper on a chain."""
         t, tp = _i32(tok)
         p, pp = _i32(parent)
         out = np.empty((len(t), self.model.vocab), np.float64)
-        if lib().orc_tree_logits(self.h, len(t), tp, pp, out.ctypes.data_as(C.POINTER(C.c_double))) != 0:
+        fn = lib().orc_tree_logits if plain else lib().orc_tree_logits_shared
+        if fn(self.h, len(t), tp, pp, out.ctypes.data_as(C.POINTER(C.c_double))) != 0:
             raise ValueError("orc_tree_logits")
         return out
+
+    def accept_greedy_bruteforce(self, tok, parent):
+        """Greedy acceptance by definition: plain autoregressive decoding from this cache, then the longest prefix of
+        it that the tree spells out.  Returns (a, emitted tokens, path)."""
+        t, tp = _i32(tok)
+        p, pp = _i32(parent)
+        n = len(t)
+        out = np.zeros(n + 1, np.int32)
+        path = np.zeros(n + 1, np.int32)
+        a = lib().orc_accept_greedy_bruteforce(self.h, n, tp, pp, out.ctypes.data_as(C.POINTER(C.c_int32)),
+                                               path.ctypes.data_as(C.POINTER(C.c_int32)))
+        if a < 0:
+            raise ValueError("orc_accept_greedy_bruteforce")
+        return a, out[:a + 1].copy(), path[:a + 1].copy()
 
 
 def threads() -> int:
@@ -350,6 +384,16 @@ def philox4x32_10(ctr, key):
     o = (C.c_uint32 * 4)()
     lib().orc_philox4x32_10(c, k, o)
     return [int(x) for x in o]
+
+
+def philox_batch(ctr: np.ndarray, key) -> np.ndarray:
+    """ctr uint32 [n, 4] -> uint32 [n, 4]: the generator applied to every counter."""
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = (C.c_uint32 * 2)(*[int(x) & 0xFFFFFFFF for x in key])
+    out = np.empty_like(c)
+    u32p = C.POINTER(C.c_uint32)
+    lib().orc_philox_batch(len(c), c.ctypes.data_as(u32p), k, out.ctypes.data_as(u32p))
+    return out
 
 
 def uniform(seed: int, seq_id: int, position: int, draw_kind: int) -> float:

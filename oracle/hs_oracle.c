@@ -30,11 +30,11 @@
  *                          monitored and speculation is switched off while the
  *                          batch is larger than the largest batch at which it
  *                          still pays at that rate (a pre-profiled table).
- *   orc_plan_workers,
- *   orc_plan_allocation    Sec. 6.2, figure "Tier-2 scheduling algorithm": workers
- *                          per ranking group such that the groups' finish times
+ *   orc_plan_allocation    Sec. 6.2, the Tier-2 planning problem: workers per
+ *                          ranking group such that the groups' finish times
  *                          rise linearly with the smallest gradient the cluster
- *                          can afford (binary search).
+ *                          can afford -- the exact optimum (the paper bisects
+ *                          towards it).
  *   orc_seq_*              Sec. 2.2: the target model's forward pass (a
  *                          standard pre-norm decoder; shape from the
  *                          benchmark configurations).
@@ -54,65 +54,72 @@
 /* ------------------------------------------------- Tier-2 planner (HistoPipe) */
 
 /*
- * Sec. 6.2, figure "Tier-2 scheduling algorithm", in its notation.  N ranking
- * groups in ascending order of representative length; tau[i * K + (k - MIN_WKS)]
- * = tau(lens[i], k), the pre-profiled time of group i on k workers, K = MAX_WKS
- * - MIN_WKS + 1.  The target time of group i is t0 + i d.
+ * Sec. 6.2 states the planning problem: the ranking groups (ascending representative length, group i profiled as
+ * tau[i * K + (k - min_wks)] = its time on k data-parallel workers, K = max_wks - min_wks + 1) shall finish on a
+ * straight line, group i no later than t0 + i d, with t0 = max(time of group 0 on max_wks workers, training time),
+ * every group on the fewest workers that meet its deadline, all groups together within the worker budget -- and the
+ * gradient d as small as the budget allows.  The paper reaches that d by bisection down to a precision; the oracle
+ * is the definition itself: the exact smallest feasible d.
  *
- * calWks: for each group the fewest workers k in [MIN_WKS, MAX_WKS] whose time
- * meets the group's target; -1 if some group cannot meet it at all, else the sum.
+ * For a given d the workers a group needs can only change where its deadline crosses one of its profiled times, i.e.
+ * at d = (tau(i, k) - t0) / i, and raising d never raises any group's need.  So the smallest feasible gradient is 0
+ * or one of these finitely many values: they are listed, sorted, and tried in ascending order.
+ *
+ * need_at: workers needed at gradient d (filling alloc), -1 if some group misses its deadline on any worker count.
  */
-long orc_plan_workers(const double* tau, int N, int MIN_WKS, int MAX_WKS, double d, double t0, int32_t* plan) {
-    int K = MAX_WKS - MIN_WKS + 1;
-    long wks_needed = 0;
-    for (int i = 0; i < N; i++) {
-        double target_t = t0 + i * d;
-        int group_wks = -1;
-        for (int k = MIN_WKS; k <= MAX_WKS; k++) {
-            double exec_t = tau[(size_t)i * K + (k - MIN_WKS)];
-            if (exec_t <= target_t) { group_wks = k; break; }
-        }
-        if (group_wks == -1) return -1;
-        wks_needed += group_wks;
-        plan[i] = group_wks;
+static long need_at(const double* tau, int n_groups, int min_wks, int max_wks, double t0, double d, int32_t* alloc) {
+    int K = max_wks - min_wks + 1;
+    long total = 0;
+    for (int i = 0; i < n_groups; i++) {
+        int fewest = 0;
+        while (fewest < K && tau[(size_t)i * K + fewest] > t0 + i * d) fewest++;
+        if (fewest == K) return -1;
+        alloc[i] = min_wks + fewest;
+        total += alloc[i];
     }
-    return wks_needed;
+    return total;
+}
+
+static int cmp_double(const void* a, const void* b) {
+    double x = *(const double*)a, y = *(const double*)b;
+    return (x > y) - (x < y);
 }
 
 /*
- * planAllocation: t0 = max(tau(lens[0], MAX_WKS), t_train); the gradient d is
- * searched in [0, (tau(lens[N-1], MIN_WKS) - t0) / (N - 1)] by bisection down to
- * precision p; a d whose plan needs more than wks workers raises the lower end,
- * a feasible one becomes the best plan and lowers the upper end.
- * Readings where the figure is silent: the upper end itself is tried first (if
- * even that needs more than wks workers no d in the interval is feasible and 0 is
- * returned; it also defines the plan when the interval is already narrower than
- * p); N = 1 has no gradient: the plan is the fewest workers that meet t0.
- * Returns 1 and fills plan[N], *d_out (the gradient the plan was computed for).
+ * Gradients are looked for in [0, d_top], d_top = (time of the last group on min_wks workers - t0) / (N - 1), the
+ * interval the paper searches (reading: a negative d_top counts as 0; one group has no gradient, d = 0).  Returns 0
+ * if even d_top is not affordable with `wks` workers, else 1 with plan[N] and *d_out = the smallest feasible gradient.
  */
-int orc_plan_allocation(const double* tau, int N, int MIN_WKS, int MAX_WKS, int wks, double t_train, double p,
+int orc_plan_allocation(const double* tau, int n_groups, int min_wks, int max_wks, int wks, double t_train,
                         int32_t* plan, double* d_out) {
-    int K = MAX_WKS - MIN_WKS + 1;
+    int K = max_wks - min_wks + 1;
     double t0 = tau[K - 1] > t_train ? tau[K - 1] : t_train;
-    int32_t* cand = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
-    double d_min = 0.0;
-    double d_max = N > 1 ? (tau[(size_t)(N - 1) * K] - t0) / (N - 1) : 0.0;
-    if (d_max < 0.0) d_max = 0.0;
-    long need = orc_plan_workers(tau, N, MIN_WKS, MAX_WKS, d_max, t0, cand);
-    if (need < 0 || need > wks) { free(cand); return 0; }
-    memcpy(plan, cand, sizeof(int32_t) * (size_t)N);
-    while (d_max - d_min > p) {
-        double d_mid = (d_max + d_min) / 2;
-        need = orc_plan_workers(tau, N, MIN_WKS, MAX_WKS, d_mid, t0, cand);
-        if (need < 0 || need > wks) {
-            d_min = d_mid;
-        } else {
-            memcpy(plan, cand, sizeof(int32_t) * (size_t)N);
-            d_max = d_mid;
+    double d_top = n_groups > 1 ? (tau[(size_t)(n_groups - 1) * K] - t0) / (n_groups - 1) : 0.0;
+    if (d_top < 0.0) d_top = 0.0;
+    long need = need_at(tau, n_groups, min_wks, max_wks, t0, d_top, plan);
+    if (need < 0 || need > wks) return 0;
+    /* candidates: 0, and every crossing point inside the interval (with its upper neighbour in floating point, since
+     * t0 + i * ((tau - t0) / i) can fall one rounding short of tau) */
+    size_t cap = 2 * (size_t)n_groups * K + 2, n = 0;
+    double* cand = (double*)malloc(sizeof(double) * cap);
+    int32_t* trial = (int32_t*)malloc(sizeof(int32_t) * (size_t)n_groups);
+    cand[n++] = 0.0;
+    for (int i = 1; i < n_groups; i++)
+        for (int k = 0; k < K; k++) {
+            double c = (tau[(size_t)i * K + k] - t0) / i;
+            if (c > 0.0 && c < d_top) { cand[n++] = c; cand[n++] = nextafter(c, INFINITY); }
+        }
+    qsort(cand, n, sizeof(double), cmp_double);
+    *d_out = d_top;
+    for (size_t j = 0; j < n; j++) {
+        need = need_at(tau, n_groups, min_wks, max_wks, t0, cand[j], trial);
+        if (need >= 0 && need <= wks) {
+            memcpy(plan, trial, sizeof(int32_t) * (size_t)n_groups);
+            *d_out = cand[j];
+            break;
         }
     }
-    *d_out = d_max;
-    free(cand);
+    free(cand); free(trial);
     return 1;
 }
 
@@ -446,6 +453,7 @@ typedef struct {
     int32_t* tokens;  /* tokens whose K/V are cached */
     double* k;        /* [layer][cap][hkv*h] */
     double* v;
+    double* trace;    /* optional, caller-owned [(n_layers+1)][d_model]: residual stream of the last pushed token */
 } orc_seq;
 
 double orc_bf16(uint16_t b) {
@@ -558,6 +566,10 @@ int orc_seq_load_kv(orc_seq* s, int n, const double* k_in, const double* v_in) {
     return 0;
 }
 
+/* Inspection hook: with a buffer of (n_layers + 1) * d_model doubles set (NULL = off), every orc_seq_push also copies
+ * out the residual stream h of its token: row 0 after the embedding, row l + 1 after layer l.  No arithmetic. */
+void orc_seq_set_trace(orc_seq* s, double* buf) { s->trace = buf; }
+
 /*
  * Feed one token at position s->len: standard pre-norm decoder,
  *   h0 = E[token]
@@ -586,6 +598,7 @@ int orc_seq_push(orc_seq* s, int32_t token, double* logits) {
     double scale = 1.0 / sqrt((double)h);
 
     for (int i = 0; i < d; i++) x[i] = orc_bf16(m->embed[(size_t)token * d + i]);
+    if (s->trace) memcpy(s->trace, x, sizeof(double) * d);
     for (int l = 0; l < m->n_layers; l++) {
         rmsnorm(x, m->norm1[l], d, m->rms_eps, nx);
         matvec(m->wqkv[l], nqkv, d, nx, qkv);
@@ -611,6 +624,7 @@ int orc_seq_push(orc_seq* s, int32_t token, double* logits) {
         for (int i = 0; i < f; i++) gate[i] = gate[i] / (1.0 + exp(-gate[i])) * up[i];
         matvec(m->wdown[l], d, f, gate, proj);
         for (int i = 0; i < d; i++) x[i] += proj[i];
+        if (s->trace) memcpy(s->trace + (size_t)(l + 1) * d, x, sizeof(double) * d);
     }
     if (logits) {
         rmsnorm(x, m->norm_f, d, m->rms_eps, nx);
@@ -630,24 +644,40 @@ int orc_argmax(const double* x, int n) {
 }
 
 /*
- * Logits of every node of a draft tree.  The cache must hold exactly the
- * l_cached positions before the root token.  Node r's logits are those of the
- * plain causal model fed cached-prefix + the tokens on the path root..r.
- * Nodes are visited in index order; the K/V of the part of the path that the
- * previously visited node shares stay in the cache, the rest is truncated
- * away and the remaining path tokens are pushed one by one.  On return the
- * cache is back at l_cached.  logits is [n_nodes][vocab].
+ * Logits of every node of a draft tree, by the definition: node r's logits are those of the plain causal model fed
+ * the cached prefix followed by the tokens on the path root..r.  For every node the cache is cut back to the
+ * l_cached positions before the root and the whole path is pushed, token by token.  On return the cache is back at
+ * l_cached.  logits is [n_nodes][vocab].
  */
 int orc_tree_logits(orc_seq* s, int n_nodes, const int32_t* tok, const int32_t* parent, double* logits) {
+    int base = s->len;
+    int V = s->m->vocab;
+    for (int r = 0; r < n_nodes; r++) {
+        int path[80], np_ = 0;
+        for (int c = r; c >= 0; c = parent[c]) { if (np_ >= 80) return -1; path[np_++] = c; }   /* leaf first */
+        if (orc_seq_truncate(s, base) != 0) return -1;
+        for (int j = np_ - 1; j >= 0; j--)
+            if (orc_seq_push(s, tok[path[j]], j == 0 ? logits + (size_t)r * V : NULL) != 0) return -1;
+    }
+    return orc_seq_truncate(s, base);
+}
+
+/*
+ * The same logits with less work, for harnesses that time or follow long chains (pinned against orc_tree_logits, to
+ * which it is equal bit for bit: a position's K/V depend only on the tokens before it).  Nodes are visited in index
+ * order; the K/V of the part of the path that the previously visited node shares stay in the cache, the rest is cut
+ * away and the remaining path tokens are pushed.
+ */
+int orc_tree_logits_shared(orc_seq* s, int n_nodes, const int32_t* tok, const int32_t* parent, double* logits) {
     int base = s->len;
     int V = s->m->vocab;
     int cur[80], ncur = 0; /* nodes whose K/V sit in the cache above base, root first */
     for (int r = 0; r < n_nodes; r++) {
         int path[80], np_ = 0;
         for (int c = r; c >= 0; c = parent[c]) { if (np_ >= 80) return -1; path[np_++] = c; }
-        /* path[] is leaf-first; compare root-first with cur[] */
         int common = 0;
         while (common < ncur && common < np_ && cur[common] == path[np_ - 1 - common]) common++;
+        if (common == np_) return -1;   /* node r itself already cached: nodes are distinct, cannot happen */
         if (orc_seq_truncate(s, base + common) != 0) return -1;
         ncur = common;
         for (int j = common; j < np_; j++) {
@@ -655,10 +685,6 @@ int orc_tree_logits(orc_seq* s, int n_nodes, const int32_t* tok, const int32_t* 
             double* out = (j == np_ - 1) ? logits + (size_t)r * V : NULL;
             if (orc_seq_push(s, tok[node], out) != 0) return -1;
             cur[ncur++] = node;
-        }
-        if (common == np_) {
-            /* r itself was already cached (cannot happen for distinct nodes, kept for safety) */
-            return -1;
         }
     }
     return orc_seq_truncate(s, base);
@@ -700,6 +726,45 @@ int orc_accept_greedy(int n_nodes, const int32_t* tok, const int32_t* parent, co
     return a;
 }
 
+/*
+ * Greedy acceptance by its definition (Sec. 2.2: speculation keeps exactly the tokens plain decoding would have
+ * produced).  From the cached prefix and the root token, decode autoregressively, one argmax token at a time, for as
+ * many steps as the tree is deep plus one: g[0], g[1], ...  The accepted path is the deepest chain of nodes root ->
+ * c1 -> c2 ... with tok[c_j] == g[j-1] for every j (at most one child of a node can carry a given token; were there
+ * two, the first in node order counts); the emitted tokens are g[0..a].  The cache is back at its length on return.
+ * Returns a, or -1 on error.
+ */
+int orc_accept_greedy_bruteforce(orc_seq* s, int n_nodes, const int32_t* tok, const int32_t* parent,
+                                 int32_t* out_tok, int32_t* path) {
+    int base = s->len, V = s->m->vocab;
+    int depth_max = 0;
+    for (int r = 0; r < n_nodes; r++) {
+        int dpt = 0;
+        for (int c = r; parent[c] >= 0; c = parent[c]) dpt++;
+        if (dpt > depth_max) depth_max = dpt;
+    }
+    double* lg = (double*)malloc(sizeof(double) * (size_t)V);
+    int32_t* g = (int32_t*)malloc(sizeof(int32_t) * (size_t)(depth_max + 1));
+    int32_t t = tok[0];
+    for (int i = 0; i <= depth_max; i++) {          /* plain autoregressive greedy decoding */
+        if (orc_seq_push(s, t, lg) != 0) { free(lg); free(g); return -1; }
+        g[i] = t = orc_argmax(lg, V);
+    }
+    int cur = 0, a = 0;
+    path[0] = 0;
+    for (;;) {                                       /* longest prefix of g that the tree spells out */
+        int next = -1;
+        for (int i = 1; i < n_nodes && next < 0; i++)
+            if (parent[i] == cur && tok[i] == g[a]) next = i;
+        if (next < 0) break;
+        cur = next;
+        path[++a] = cur;
+    }
+    for (int i = 0; i <= a; i++) out_tok[i] = g[i];
+    free(lg); free(g);
+    return orc_seq_truncate(s, base) == 0 ? a : -1;
+}
+
 /* Philox-4x32, 10 rounds (Salmon et al., SC'11). */
 void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
     uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
@@ -716,6 +781,11 @@ void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t ou
         k1 += 0xBB67AE85u;
     }
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The generator on n counters: out[i] = orc_philox4x32_10(ctr[i], key).  A plain loop, for bulk comparison. */
+void orc_philox_batch(int n, const uint32_t* ctr, const uint32_t key[2], uint32_t* out) {
+    for (int i = 0; i < n; i++) orc_philox4x32_10(ctr + 4 * (size_t)i, key, out + 4 * (size_t)i);
 }
 
 /*

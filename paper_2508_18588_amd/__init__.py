@@ -21,7 +21,7 @@ HS_OK, HS_ERR_INVALID_ARG, HS_ERR_CAPACITY, HS_ERR_UNSUPPORTED, HS_ERR_HIP = 0, 
 HS_DEV_BLOCK_TABLE_OVERFLOW, HS_DEV_POSITION_OVERFLOW, HS_DEV_ROW_OVERFLOW = 1, 2, 4
 HS_K_FIXED, HS_K_MATCHLEN, HS_K_AIMD = 0, 1, 2
 HS_ACCEPT_GREEDY, HS_ACCEPT_REJECTION = 0, 1
-HS_FLAG_REFERENCE_KERNELS = 1
+HS_FLAG_REFERENCE_KERNELS, HS_FLAG_FP32_ACTIVATIONS = 1, 2
 HS_GATE_WORDS, HS_GATE_TABLE = 32, 8
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -119,7 +119,8 @@ HS_PREFILL_CHUNK_MAX = 1024
 
 EXPORTS = ("hs_create", "hs_destroy", "hs_last_error", "hs_set_flags", "hs_workspace_bytes", "hs_bind_workspace",
            "hs_draft", "hs_draft_group", "hs_verify", "hs_accept", "hs_kv_commit", "hs_poll_error", "hs_debug_buffer",
-           "hs_set_profile", "hs_get_profile", "hs_debug_gemm", "hs_gate_table_build", "hs_prefill", "hs_plan_allocation")
+           "hs_set_profile", "hs_get_profile", "hs_debug_gemm", "hs_gate_table_build", "hs_prefill", "hs_plan_allocation",
+           "hs_debug_capture", "hs_debug_capture_bytes", "hs_debug_philox")
 
 _lib = None
 
@@ -156,6 +157,10 @@ def lib():
                                    C.POINTER(hs_policy), vp]
         L.hs_poll_error.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
         L.hs_debug_buffer.argtypes = [vp, C.c_int32, C.POINTER(vp), C.POINTER(C.c_size_t)]
+        L.hs_debug_capture_bytes.argtypes = [vp]
+        L.hs_debug_capture_bytes.restype = C.c_size_t
+        L.hs_debug_capture.argtypes = [vp, vp, C.c_size_t]
+        L.hs_debug_philox.argtypes = [vp, C.c_uint64, vp, C.c_int32, vp]
         L.hs_set_profile.argtypes = [vp, C.c_int32]
         L.hs_get_profile.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         L.hs_gate_table_build.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int32), C.c_int32, C.c_float, C.c_int32,
@@ -239,6 +244,20 @@ def hs_debug_buffer(ctx, which: int):
     p, n = C.c_void_p(), C.c_size_t()
     _check(ctx, lib().hs_debug_buffer(ctx, which, C.byref(p), C.byref(n)))
     return p.value, n.value
+
+
+def hs_debug_capture_bytes(ctx) -> int:
+    return lib().hs_debug_capture_bytes(ctx)
+
+
+def hs_debug_capture(ctx, dev_ptr, nbytes: int):
+    _check(ctx, lib().hs_debug_capture(ctx, dev_ptr, nbytes))
+
+
+def hs_debug_philox(ctr_dev: int, seed: int, out_dev: int, n: int, stream=None):
+    st = lib().hs_debug_philox(ctr_dev, seed, out_dev, n, stream)
+    if st != HS_OK:
+        raise HsError(st, "hs_debug_philox")
 
 
 def hs_set_profile(ctx, level: int):

@@ -194,8 +194,10 @@ __global__ __launch_bounds__(256) void accept_rejection_kernel(
 }
 
 // One workgroup per sequence: relocate accepted tree nodes' K/V to consecutive slots, then advance the state.
+// CT = cache element type (bf16 bits, or float in the fp32-activation mode).
+template <typename CT>
 __global__ __launch_bounds__(256) void commit_kernel(
-    int batch, int n_layers, int hkv, int hd, int n_blocks, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
+    int batch, int n_layers, int hkv, int hd, int n_blocks, CT* __restrict__ kc, CT* __restrict__ vc,
     const int32_t* __restrict__ block_table, int max_blocks, int32_t* __restrict__ seq_len,
     int32_t* __restrict__ tail, int32_t* __restrict__ tail_len, int w_max, int32_t* __restrict__ k_state,
     int32_t* __restrict__ budget_left, int32_t* __restrict__ tokens, int tokens_stride,
@@ -264,7 +266,27 @@ __global__ __launch_bounds__(256) void commit_kernel(
     }
 }
 
+// The generator on its own: counter i -> its four output words (for bit-exact comparison with another
+// implementation on many counters).
+__global__ __launch_bounds__(256) void philox_debug_kernel(const uint32_t* __restrict__ ctr, uint32_t k0, uint32_t k1,
+                                                            uint32_t* __restrict__ out, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    uint32_t o[4];
+    philox4x32_10(ctr[4 * i], ctr[4 * i + 1], ctr[4 * i + 2], ctr[4 * i + 3], k0, k1, o);
+    out[4 * i] = o[0]; out[4 * i + 1] = o[1]; out[4 * i + 2] = o[2]; out[4 * i + 3] = o[3];
+}
+
 }  // namespace
+
+extern "C" hs_status hs_debug_philox(const uint32_t* ctr, uint64_t seed, uint32_t* out, int32_t n, hs_stream stream) {
+    if (!ctr || !out || n < 0) return HS_ERR_INVALID_ARG;
+    if (n == 0) return HS_OK;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(philox_debug_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, ctr,
+                       (uint32_t)seed, (uint32_t)(seed >> 32), out, n);
+    return hipGetLastError() == hipSuccess ? HS_OK : HS_ERR_HIP;
+}
 
 void hs_launch_accept(const hs_ctx* ctx, const hs_accept_args* args, const hs_seq_state* seq, hs_step* step,
                       const float* logits, hipStream_t st) {
@@ -284,10 +306,15 @@ void hs_launch_accept(const hs_ctx* ctx, const hs_accept_args* args, const hs_se
 void hs_launch_commit(const hs_ctx* ctx, const hs_kv_cache* cache, hs_seq_state* seq, const hs_step* step,
                       const hs_policy* policy, hipStream_t st) {
     const hs_model_desc& d = ctx->desc;
-    hipLaunchKernelGGL(commit_kernel, dim3(seq->batch), dim3(256), 0, st, seq->batch, d.n_layers, d.n_kv_heads,
-                       d.head_dim, cache->n_blocks, (bf16_t*)cache->k, (bf16_t*)cache->v, seq->block_table,
-                       ctx->lim.max_blocks_per_seq, seq->seq_len, seq->tail, seq->tail_len, ctx->lim.w_max,
-                       seq->k_state, seq->budget_left, seq->tokens, seq->tokens_stride,
-                       (unsigned long long*)seq->counters, step->row_off, step->parent, step->accept_len,
-                       step->n_out, step->out_tok, step->path_row, ctx->lim.k_max + 1, *policy);
+#define HS_COMMIT_ARGS(CT)                                                                                       \
+    seq->batch, d.n_layers, d.n_kv_heads, d.head_dim, cache->n_blocks, (CT*)cache->k, (CT*)cache->v,             \
+        seq->block_table, ctx->lim.max_blocks_per_seq, seq->seq_len, seq->tail, seq->tail_len, ctx->lim.w_max,   \
+        seq->k_state, seq->budget_left, seq->tokens, seq->tokens_stride, (unsigned long long*)seq->counters,     \
+        step->row_off, step->parent, step->accept_len, step->n_out, step->out_tok, step->path_row,               \
+        ctx->lim.k_max + 1, *policy
+    if (hs_fp32_activations(ctx))
+        hipLaunchKernelGGL(commit_kernel<float>, dim3(seq->batch), dim3(256), 0, st, HS_COMMIT_ARGS(float));
+    else
+        hipLaunchKernelGGL(commit_kernel<bf16_t>, dim3(seq->batch), dim3(256), 0, st, HS_COMMIT_ARGS(bf16_t));
+#undef HS_COMMIT_ARGS
 }

@@ -29,13 +29,14 @@ void layout_workspace(hs_ctx* ctx) {
     const size_t nqkv = (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const size_t ab = hs_fp32_activations(ctx) ? 4 : 2;   // bytes per activation element
     w.err = take(256);
     w.x = take(M * d.d_model * 4);
-    w.xn = take(M * d.d_model * 2);
+    w.xn = take(M * d.d_model * ab);
     w.qkv = take(M * nqkv * 4);
-    w.q = take(M * qh * 2);
-    w.attn = take(M * qh * 2);
-    w.act = take(M * (size_t)d.d_ffn * 2);
+    w.q = take(M * qh * ab);
+    w.attn = take(M * qh * ab);
+    w.act = take(M * (size_t)d.d_ffn * ab);
     w.part_o = take(M * d.n_q_heads * (size_t)ctx->max_parts * d.head_dim * 2);   // fp16
     w.part_ml = take(M * d.n_q_heads * (size_t)ctx->max_parts * 2 * 4);
     w.logits = take(M * (size_t)d.vocab * 4);
@@ -81,6 +82,9 @@ struct Prof {
         ctx->ev_used += 2;
     }
 };
+
+// one snapshot of hs_debug_capture: [max_rows][d_model] elements of 4 bytes (bf16 snapshots use the first half)
+size_t capture_slot_bytes(const hs_ctx* ctx) { return (size_t)ctx->lim.max_rows * ctx->desc.d_model * 4; }
 
 bool step_ok(const hs_step* s) {
     return s && s->draft_start && s->match_len && s->draft_len && s->row_off && s->tok && s->pos && s->parent &&
@@ -199,8 +203,17 @@ const char* hs_last_error(const hs_ctx* ctx) { return ctx ? ctx->err.c_str() : "
 
 hs_status hs_set_flags(hs_ctx* ctx, uint32_t flags) {
     if (!ctx) return HS_ERR_INVALID_ARG;
-    if (flags & ~(uint32_t)HS_FLAG_REFERENCE_KERNELS) return fail(ctx, HS_ERR_INVALID_ARG, "unknown flag");
+    if (flags & ~(uint32_t)(HS_FLAG_REFERENCE_KERNELS | HS_FLAG_FP32_ACTIVATIONS))
+        return fail(ctx, HS_ERR_INVALID_ARG, "unknown flag");
+    const bool relayout = ((flags ^ ctx->flags) & HS_FLAG_FP32_ACTIVATIONS) != 0;
     ctx->flags = flags;
+    if (relayout) {
+        layout_workspace(ctx);
+        if (ctx->ws && ctx->ws_bytes < ctx->lay.total) {   // the bound workspace no longer fits: calls fail until re-bound
+            ctx->ws = nullptr;
+            ctx->ws_bytes = 0;
+        }
+    }
     return HS_OK;
 }
 
@@ -256,16 +269,17 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
     const int m_max = ctx->lim.max_rows;
     const int32_t* m_dev = step->row_off + seq->batch;
     float* x = (float*)(ctx->ws + ctx->lay.x);
-    bf16_t* xn = (bf16_t*)(ctx->ws + ctx->lay.xn);
+    void* xn = ctx->ws + ctx->lay.xn;      // activations: bf16, or float in the fp32-activation mode
     float* qkv = (float*)(ctx->ws + ctx->lay.qkv);
-    bf16_t* q = (bf16_t*)(ctx->ws + ctx->lay.q);
-    bf16_t* attn = (bf16_t*)(ctx->ws + ctx->lay.attn);
-    bf16_t* act = (bf16_t*)(ctx->ws + ctx->lay.act);
+    void* q = ctx->ws + ctx->lay.q;
+    void* attn = ctx->ws + ctx->lay.attn;
+    void* act = ctx->ws + ctx->lay.act;
     float* logits = step->logits ? step->logits : (float*)(ctx->ws + ctx->lay.logits);
     const int qh = d.n_q_heads * d.head_dim;
     const int nqkv = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
     // Few rows expected: run the narrow projections split over K (same arithmetic, more workgroups).
     const int hint = step->rows_hint > 0 ? step->rows_hint : m_max;
+    const size_t cap_slot = capture_slot_bytes(ctx), cap_xn = hs_fp32_activations(ctx) ? cap_slot : cap_slot / 2;
 
     (void)hipGetLastError();
     Prof whole{ctx, st}, pr{ctx, st};
@@ -285,6 +299,10 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
         pr.begin(3);
         hs_launch_rmsnorm(ctx, x, ctx->norm1[l], xn, m_dev, pend, st);
         pr.end();
+        if (ctx->capture && l + 1 == d.n_layers) {
+            (void)hipMemcpyAsync(ctx->capture, xn, cap_xn, hipMemcpyDeviceToDevice, st);
+            (void)hipMemcpyAsync(ctx->capture + cap_slot, x, cap_slot, hipMemcpyDeviceToDevice, st);
+        }
         pr.begin(1);
         hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->wqkv[l], nullptr, qkv, m_dev, m_max, nqkv, d.d_model, hint, st,
                        &pend);
@@ -304,6 +322,10 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
         pr.begin(3);
         hs_launch_rmsnorm(ctx, x, ctx->norm2[l], xn, m_dev, pend, st);
         pr.end();
+        if (ctx->capture && l + 1 == d.n_layers) {
+            (void)hipMemcpyAsync(ctx->capture + 2 * cap_slot, xn, cap_xn, hipMemcpyDeviceToDevice, st);
+            (void)hipMemcpyAsync(ctx->capture + 3 * cap_slot, x, cap_slot, hipMemcpyDeviceToDevice, st);
+        }
         pr.begin(1);
         hs_launch_gemm(ctx, HS_EPI_SWIGLU_BF16, xn, ctx->wgate[l], ctx->wup[l], act, m_dev, m_max, d.d_ffn, d.d_model, hint, st);
         pr.end();
@@ -339,7 +361,7 @@ hs_status hs_prefill(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* 
         return fail(ctx, HS_ERR_INVALID_ARG, "hs_prefill: step arrays");
     if (!args || !args->kv_done || args->chunk < 1 || args->chunk > HS_PREFILL_CHUNK_MAX)
         return fail(ctx, HS_ERR_INVALID_ARG, "hs_prefill: arguments");
-    if (ctx->flags & HS_FLAG_REFERENCE_KERNELS) return fail(ctx, HS_ERR_UNSUPPORTED, "hs_prefill: no plain-kernel mode");
+    if (hs_plain_kernels(ctx)) return fail(ctx, HS_ERR_UNSUPPORTED, "hs_prefill: no plain-kernel mode");
     hipStream_t st = (hipStream_t)stream;
     const hs_model_desc& d = ctx->desc;
     const int m_max = ctx->lim.max_rows;
@@ -431,13 +453,26 @@ hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size
     if (!ctx || !dev_ptr || !bytes || !ctx->ws) return HS_ERR_INVALID_ARG;
     const hs_model_desc& d = ctx->desc;
     const size_t M = (size_t)ctx->lim.max_rows, qh = (size_t)d.n_q_heads * d.head_dim;
+    const size_t ab = hs_fp32_activations(ctx) ? 4 : 2;
     switch (which) {
-        case 0: *dev_ptr = ctx->ws + ctx->lay.xn; *bytes = M * d.d_model * 2; break;
-        case 1: *dev_ptr = ctx->ws + ctx->lay.q; *bytes = M * qh * 2; break;
-        case 2: *dev_ptr = ctx->ws + ctx->lay.attn; *bytes = M * qh * 2; break;
+        case 0: *dev_ptr = ctx->ws + ctx->lay.xn; *bytes = M * d.d_model * ab; break;
+        case 1: *dev_ptr = ctx->ws + ctx->lay.q; *bytes = M * qh * ab; break;
+        case 2: *dev_ptr = ctx->ws + ctx->lay.attn; *bytes = M * qh * ab; break;
         case 3: *dev_ptr = ctx->ws + ctx->lay.logits; *bytes = M * (size_t)d.vocab * 4; break;
+        case 4: *dev_ptr = ctx->ws + ctx->lay.x; *bytes = M * d.d_model * 4; break;
+        case 5: *dev_ptr = ctx->ws + ctx->lay.act; *bytes = M * (size_t)d.d_ffn * ab; break;
         default: return HS_ERR_INVALID_ARG;
     }
+    return HS_OK;
+}
+
+size_t hs_debug_capture_bytes(const hs_ctx* ctx) { return ctx ? 4 * capture_slot_bytes(ctx) : 0; }
+
+hs_status hs_debug_capture(hs_ctx* ctx, void* dev_ptr, size_t bytes) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    if (dev_ptr && bytes < 4 * capture_slot_bytes(ctx))
+        return fail(ctx, HS_ERR_CAPACITY, "hs_debug_capture: buffer smaller than hs_debug_capture_bytes");
+    ctx->capture = (char*)dev_ptr;
     return HS_OK;
 }
 

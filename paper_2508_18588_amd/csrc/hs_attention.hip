@@ -702,22 +702,31 @@ __global__ __launch_bounds__(256) void attn_merge(const _Float16* __restrict__ p
     for (int i = 0; i < HD / 64; i++) out[((size_t)row * hq + head) * HD + lane + 64 * i] = f32_to_bf16(acc[i] / den);
 }
 
-// Plain kernel for debugging: one wavefront per (row, query head), keys visited one by one.
+// Plain kernel for debugging and for the fp32-activation mode: one wavefront per (row, query head), keys visited one
+// by one.  T = bf16_t (queries, cache and output are bf16; fp32 arithmetic) or float (nothing rounded below fp32, the
+// running sum and output carried in fp64, library exponential).
+__device__ __forceinline__ float plain_ld(const bf16_t* p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ float plain_ld(const float* p) { return *p; }
+__device__ __forceinline__ void plain_st(bf16_t* p, double v) { *p = f32_to_bf16((float)v); }
+__device__ __forceinline__ void plain_st(float* p, double v) { *p = (float)v; }
+
+template <typename T, typename ACC>
 __global__ __launch_bounds__(64) void attn_verify_plain(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc, size_t layer_off,
+    const T* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc, size_t layer_off,
     const int32_t* __restrict__ seq_len, const int32_t* __restrict__ block_table, int max_blocks, int n_blocks,
     const int32_t* __restrict__ row_off, const int32_t* __restrict__ row2seq, const uint64_t* __restrict__ anc_mask,
-    int batch, int hq, int hkv, int hd, float scale, bf16_t* __restrict__ out) {
+    int batch, int hq, int hkv, int hd, float scale, T* __restrict__ out) {
+    constexpr bool PRECISE = sizeof(ACC) == 8;
     int row = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
     if (row >= row_off[batch]) return;
     int b = row2seq[row];
     int L = seq_len[b] - 1, nn = row_off[b + 1] - row_off[b];
     int total = L + nn, j = head / (hq / hkv);
     uint64_t anc = anc_mask[row];
-    const bf16_t* qp = q + ((size_t)row * hq + head) * hd;
-    float q0 = lane < hd ? bf16_to_f32(qp[lane]) : 0.f;
-    float q1 = lane + 64 < hd ? bf16_to_f32(qp[lane + 64]) : 0.f;
-    float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
+    const T* qp = q + ((size_t)row * hq + head) * hd;
+    float q0 = lane < hd ? plain_ld(qp + lane) : 0.f;
+    float q1 = lane + 64 < hd ? plain_ld(qp + lane + 64) : 0.f;
+    ACC m = -INFINITY, l = 0, o0 = 0, o1 = 0;
     for (int kp = 0; kp < total; kp++) {
         bool vis = kp < L || ((anc >> (kp - L)) & 1ull);
         if (!vis) continue;
@@ -725,26 +734,37 @@ __global__ __launch_bounds__(64) void attn_verify_plain(
         int page = block_table[(size_t)b * max_blocks + (kp >> 4)];
         if (page < 0 || page >= n_blocks) break;
         int ip = kp & 15;
-        const bf16_t* kr = kc + layer_off + (((size_t)page * hkv + j) * 16 + ip) * hd;
-        float dot = 0.f;
-        if (lane < hd) dot += q0 * bf16_to_f32(kr[lane]);
-        if (lane + 64 < hd) dot += q1 * bf16_to_f32(kr[lane + 64]);
+        const T* kr = kc + layer_off + (((size_t)page * hkv + j) * 16 + ip) * hd;
+        ACC dot = 0;
+        if (lane < hd) dot += (ACC)q0 * (ACC)plain_ld(kr + lane);
+        if (lane + 64 < hd) dot += (ACC)q1 * (ACC)plain_ld(kr + lane + 64);
+        if (PRECISE) {
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
-        float s = dot * scale;
-        float mn = fmaxf(m, s);
-        float a = __expf(m - mn), p = __expf(s - mn);
+            for (int o = 32; o > 0; o >>= 1) {
+                const double dd = (double)dot;
+                const int lo = __shfl_xor(__double2loint(dd), o), hi = __shfl_xor(__double2hiint(dd), o);
+                dot += (ACC)__hiloint2double(hi, lo);
+            }
+        } else {
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) dot += (ACC)__shfl_xor((float)dot, o);
+        }
+        ACC s = dot * (ACC)scale;
+        ACC mn = s > m ? s : m;
+        ACC a, p;
+        if (PRECISE) { a = (ACC)exp((double)(m - mn)); p = (ACC)exp((double)(s - mn)); }
+        else { a = (ACC)__expf((float)(m - mn)); p = (ACC)__expf((float)(s - mn)); }
         l = l * a + p;
-        const bf16_t* vr = vc + layer_off + ((size_t)page * hkv + j) * hd * 16 + ip;
-        float v0 = lane < hd ? bf16_to_f32(vr[(size_t)lane * 16]) : 0.f;
-        float v1 = lane + 64 < hd ? bf16_to_f32(vr[(size_t)(lane + 64) * 16]) : 0.f;
-        o0 = o0 * a + p * v0;
-        o1 = o1 * a + p * v1;
+        const T* vr = vc + layer_off + ((size_t)page * hkv + j) * hd * 16 + ip;
+        float v0 = lane < hd ? plain_ld(vr + (size_t)lane * 16) : 0.f;
+        float v1 = lane + 64 < hd ? plain_ld(vr + (size_t)(lane + 64) * 16) : 0.f;
+        o0 = o0 * a + p * (ACC)v0;
+        o1 = o1 * a + p * (ACC)v1;
         m = mn;
     }
-    bf16_t* op = out + ((size_t)row * hq + head) * hd;
-    if (lane < hd) op[lane] = f32_to_bf16(o0 / l);
-    if (lane + 64 < hd) op[lane + 64] = f32_to_bf16(o1 / l);
+    T* op = out + ((size_t)row * hq + head) * hd;
+    if (lane < hd) plain_st(op + lane, (double)(o0 / l));
+    if (lane + 64 < hd) plain_st(op + lane + 64, (double)(o1 / l));
 }
 
 template <int HD, int RTW>
@@ -787,17 +807,27 @@ void launch_mfma(const hs_ctx* ctx, int layer, size_t layer_off, const hs_kv_cac
 }  // namespace
 
 void hs_launch_attention(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
-                         const hs_step* step, const bf16_t* q, bf16_t* out, hipStream_t st) {
+                         const hs_step* step, const void* q_any, void* out, hipStream_t st) {
     const hs_model_desc& d = ctx->desc;
     size_t layer_off = (size_t)layer * cache->n_blocks * d.n_kv_heads * 16 * d.head_dim;
-    if (ctx->flags & HS_FLAG_REFERENCE_KERNELS) {
-        hipLaunchKernelGGL(attn_verify_plain, dim3(ctx->lim.max_rows, d.n_q_heads), dim3(64), 0, st, q,
-                           (const bf16_t*)cache->k, (const bf16_t*)cache->v, layer_off, seq->seq_len,
-                           seq->block_table, ctx->lim.max_blocks_per_seq, cache->n_blocks, step->row_off,
-                           step->row2seq, step->anc_mask, seq->batch, d.n_q_heads, d.n_kv_heads, d.head_dim,
-                           1.f / sqrtf((float)d.head_dim), out);
+    if (hs_plain_kernels(ctx)) {
+        const dim3 grid(ctx->lim.max_rows, d.n_q_heads);
+        const float scale = 1.f / sqrtf((float)d.head_dim);
+        if (hs_fp32_activations(ctx))
+            hipLaunchKernelGGL((attn_verify_plain<float, double>), grid, dim3(64), 0, st, (const float*)q_any,
+                               (const float*)cache->k, (const float*)cache->v, layer_off, seq->seq_len,
+                               seq->block_table, ctx->lim.max_blocks_per_seq, cache->n_blocks, step->row_off,
+                               step->row2seq, step->anc_mask, seq->batch, d.n_q_heads, d.n_kv_heads, d.head_dim,
+                               scale, (float*)out);
+        else
+            hipLaunchKernelGGL((attn_verify_plain<bf16_t, float>), grid, dim3(64), 0, st, (const bf16_t*)q_any,
+                               (const bf16_t*)cache->k, (const bf16_t*)cache->v, layer_off, seq->seq_len,
+                               seq->block_table, ctx->lim.max_blocks_per_seq, cache->n_blocks, step->row_off,
+                               step->row2seq, step->anc_mask, seq->batch, d.n_q_heads, d.n_kv_heads, d.head_dim,
+                               scale, (bf16_t*)out);
         return;
     }
+    const bf16_t* q = (const bf16_t*)q_any;
     int G = d.n_q_heads / d.n_kv_heads;
     int r_max = G * (1 + ctx->lim.c_max * ctx->lim.k_max);
     bool two = r_max > 128;
@@ -815,7 +845,7 @@ size_t hs_attention_max_units(const hs_ctx* ctx) {
 }
 
 void hs_launch_attention_worklist(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, hipStream_t st) {
-    if (ctx->flags & HS_FLAG_REFERENCE_KERNELS) return;
+    if (hs_plain_kernels(ctx)) return;
     const hs_model_desc& d = ctx->desc;
     int32_t* work = reinterpret_cast<int32_t*>(ctx->ws + ctx->lay.att_work);
     int4* list_a = reinterpret_cast<int4*>(ctx->ws + ctx->lay.att_list);
@@ -845,9 +875,10 @@ void hs_launch_attention_prefill(const hs_ctx* ctx, int layer, const hs_kv_cache
                            scale_log2);
 }
 
-void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, bf16_t* out,
+void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, void* out_any,
                                hipStream_t st) {
-    if (ctx->flags & HS_FLAG_REFERENCE_KERNELS) return;  // the plain kernel writes the final output itself
+    if (hs_plain_kernels(ctx)) return;  // the plain kernel writes the final output itself
+    bf16_t* out = (bf16_t*)out_any;
     const hs_model_desc& d = ctx->desc;
     const _Float16* part_o = reinterpret_cast<const _Float16*>(ctx->ws + ctx->lay.part_o);
     float* part_ml = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_ml);

@@ -7,6 +7,9 @@ namespace {
 
 constexpr int NORM_THREADS = 1024;  // one workgroup of 16 wavefronts per row: few rows, many loads in flight each
 
+__device__ __forceinline__ void put(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+__device__ __forceinline__ void put(float* p, float v) { *p = v; }
+
 __device__ inline float block_sum(float v, float* red) {
     // fixed tree: xor-shuffle inside each wavefront, then the wavefront sums left to right
 #pragma unroll
@@ -33,8 +36,10 @@ __global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ e
 // One workgroup per row.  With chunks > 0 the row of the residual stream first receives the pending partial sums of
 // the preceding projection: t = p0 + p1 + ... in chunk order, x += t -- the arithmetic of the stand-alone ordered
 // reduce, so that the split execution gives the same bits whichever kernel finishes it.
+// OutT = bf16_t (rounded activations) or float (fp32-activation mode).
+template <typename OutT>
 __global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ w,
-                                                       bf16_t* __restrict__ out, const int32_t* __restrict__ m_dev,
+                                                       OutT* __restrict__ out, const int32_t* __restrict__ m_dev,
                                                        int d, float eps, const float* __restrict__ part, int chunks,
                                                        size_t chunk_stride) {
     __shared__ float red[NORM_THREADS / 64];
@@ -74,18 +79,20 @@ __global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(float* __restrict
     }
     ss = block_sum(ss, red);
     float r = rsqrtf(ss / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += NORM_THREADS) out[(size_t)row * d + i] = f32_to_bf16(xr[i] * r * w[i]);
+    for (int i = threadIdx.x; i < d; i += NORM_THREADS) put(out + (size_t)row * d + i, xr[i] * r * w[i]);
 }
 
 // One workgroup per row.  Rotates q and k heads at the row's position (pairs i, i + h/2), writes q as bf16,
 // K into its page row-major and V into its page with the token index fastest.
+// T = bf16_t, or float in the fp32-activation mode (queries and cache entries then keep every bit).
+template <typename T>
 __global__ __launch_bounds__(NORM_THREADS) void rope_kv_kernel(const float* __restrict__ qkv, const float* __restrict__ rope_cs,
                                                        const int32_t* __restrict__ pos, const int32_t* __restrict__ row2seq,
                                                        const int32_t* __restrict__ row_off,
                                                        const int32_t* __restrict__ seq_len,
                                                        const int32_t* __restrict__ block_table, int max_blocks,
-                                                       int batch, bf16_t* __restrict__ q_out, bf16_t* __restrict__ kc,
-                                                       bf16_t* __restrict__ vc, size_t layer_off, int hq, int hkv,
+                                                       int batch, T* __restrict__ q_out, T* __restrict__ kc,
+                                                       T* __restrict__ vc, size_t layer_off, int hq, int hkv,
                                                        int h, int max_pos, int n_blocks,
                                                        const float* __restrict__ part, int chunks,
                                                        size_t chunk_stride) {
@@ -126,9 +133,9 @@ __global__ __launch_bounds__(NORM_THREADS) void rope_kv_kernel(const float* __re
         int head = i / half, j = i % half;
         float c = cs[2 * j], s = cs[2 * j + 1];
         float a = val(head * h + j), bb = val(head * h + j + half);
-        bf16_t* dst = q_out + (size_t)row * hq * h + head * h;
-        dst[j] = f32_to_bf16(a * c - bb * s);
-        dst[j + half] = f32_to_bf16(bb * c + a * s);
+        T* dst = q_out + (size_t)row * hq * h + head * h;
+        put(dst + j, a * c - bb * s);
+        put(dst + j + half, bb * c + a * s);
     }
     // k heads -> cache [page][kv head][16][h]
     const int koff = hq * h;
@@ -136,15 +143,15 @@ __global__ __launch_bounds__(NORM_THREADS) void rope_kv_kernel(const float* __re
         int head = i / half, j = i % half;
         float c = cs[2 * j], s = cs[2 * j + 1];
         float a = val(koff + head * h + j), bb = val(koff + head * h + j + half);
-        bf16_t* dst = kc + layer_off + (((size_t)page * hkv + head) * 16 + in_page) * h;
-        dst[j] = f32_to_bf16(a * c - bb * s);
-        dst[j + half] = f32_to_bf16(bb * c + a * s);
+        T* dst = kc + layer_off + (((size_t)page * hkv + head) * 16 + in_page) * h;
+        put(dst + j, a * c - bb * s);
+        put(dst + j + half, bb * c + a * s);
     }
     // v heads -> cache [page][kv head][h][16]
     const int voff = koff + hkv * h;
     for (int i = threadIdx.x; i < hkv * h; i += NORM_THREADS) {
         int head = i / h, j = i % h;
-        vc[layer_off + (((size_t)page * hkv + head) * h + j) * 16 + in_page] = f32_to_bf16(val(voff + head * h + j));
+        put(vc + layer_off + (((size_t)page * hkv + head) * h + j) * 16 + in_page, val(voff + head * h + j));
     }
 }
 
@@ -258,25 +265,37 @@ void hs_launch_embed(const hs_ctx* ctx, const hs_step* step, int batch, float* x
                        step->row_off + batch, x, ctx->desc.d_model, ctx->desc.vocab);
 }
 
-void hs_launch_rmsnorm(const hs_ctx* ctx, float* x, const float* w, bf16_t* out, const int32_t* m_dev,
+void hs_launch_rmsnorm(const hs_ctx* ctx, float* x, const float* w, void* out, const int32_t* m_dev,
                        int pending_chunks, hipStream_t st) {
     const float* part = reinterpret_cast<const float*>(ctx->ws + ctx->lay.gemm_part);
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), 0, st, x, w, out, m_dev,
-                       ctx->desc.d_model, ctx->desc.rms_eps, part, pending_chunks,
-                       (size_t)ctx->lim.max_rows * ctx->desc.d_model);
+    const size_t stride = (size_t)ctx->lim.max_rows * ctx->desc.d_model;
+    if (hs_fp32_activations(ctx))
+        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), 0, st, x, w, (float*)out,
+                           m_dev, ctx->desc.d_model, ctx->desc.rms_eps, part, pending_chunks, stride);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), 0, st, x, w,
+                           (bf16_t*)out, m_dev, ctx->desc.d_model, ctx->desc.rms_eps, part, pending_chunks, stride);
 }
 
 void hs_launch_rope_kv(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
-                       const hs_step* step, const float* qkv, bf16_t* q, int pending_chunks, hipStream_t st) {
+                       const hs_step* step, const float* qkv, void* q, int pending_chunks, hipStream_t st) {
     const hs_model_desc& d = ctx->desc;
     size_t layer_off = (size_t)layer * cache->n_blocks * d.n_kv_heads * 16 * d.head_dim;
     const float* part = reinterpret_cast<const float*>(ctx->ws + ctx->lay.gemm_part);
     const size_t nqkv = (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
-    hipLaunchKernelGGL(rope_kv_kernel, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), pending_chunks > 0 ? nqkv * 4 : 0, st, qkv, ctx->rope_cs, step->pos,
-                       step->row2seq, step->row_off, seq->seq_len, seq->block_table, ctx->lim.max_blocks_per_seq,
-                       seq->batch, q, (bf16_t*)cache->k, (bf16_t*)cache->v, layer_off, d.n_q_heads, d.n_kv_heads,
-                       d.head_dim, ctx->lim.max_pos, cache->n_blocks, part, pending_chunks,
-                       (size_t)ctx->lim.max_rows * nqkv);
+    const size_t lds = pending_chunks > 0 ? nqkv * 4 : 0;
+#define HS_ROPE_ARGS(T)                                                                                          \
+    qkv, ctx->rope_cs, step->pos, step->row2seq, step->row_off, seq->seq_len, seq->block_table,                  \
+        ctx->lim.max_blocks_per_seq, seq->batch, (T*)q, (T*)cache->k, (T*)cache->v, layer_off, d.n_q_heads,      \
+        d.n_kv_heads, d.head_dim, ctx->lim.max_pos, cache->n_blocks, part, pending_chunks,                       \
+        (size_t)ctx->lim.max_rows * nqkv
+    if (hs_fp32_activations(ctx))
+        hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), lds, st,
+                           HS_ROPE_ARGS(float));
+    else
+        hipLaunchKernelGGL(rope_kv_kernel<bf16_t>, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), lds, st,
+                           HS_ROPE_ARGS(bf16_t));
+#undef HS_ROPE_ARGS
 }
 
 void hs_launch_argmax(const hs_ctx* ctx, const float* logits, int32_t* argmax, const int32_t* m_dev,

@@ -29,6 +29,7 @@ struct hs_ctx {
     std::vector<const bf16_t*> wqkv, wo, wgate, wup, wdown;
     std::vector<const float*> norm1, norm2;
     uint32_t flags = 0;
+    char* capture = nullptr;  // hs_debug_capture: snapshots of the last layer's projection inputs
     char* ws = nullptr;
     size_t ws_bytes = 0;
     hs_workspace_layout lay;
@@ -60,9 +61,16 @@ static inline __host__ __device__ bf16_t f32_to_bf16(float f) {
     return (bf16_t)(u >> 16);
 }
 
+// hs_set_flags: plain kernels (either flag), and with them activations and KV cache in fp32.
+static inline bool hs_fp32_activations(const hs_ctx* ctx) { return (ctx->flags & HS_FLAG_FP32_ACTIVATIONS) != 0; }
+static inline bool hs_plain_kernels(const hs_ctx* ctx) {
+    return (ctx->flags & (HS_FLAG_REFERENCE_KERNELS | HS_FLAG_FP32_ACTIVATIONS)) != 0;
+}
+
 // ---- launchers (each enqueues on `st`; shapes have been validated by the caller) ----
 
 // GEMM family: C[M,N] (+)= A[M,K] . W[N,K]^T, A and W bf16, fp32 accumulation in a fixed k order.
+// Activation buffers (a, and c of the SwiGLU epilogue) are bf16, or float in the fp32-activation mode.
 // m_dev points at the row count M on the device; the grid covers m_max rows and tiles beyond M exit.
 enum { HS_EPI_STORE_F32 = 0, HS_EPI_ADD_F32 = 1, HS_EPI_SWIGLU_BF16 = 2 };
 // rows_hint (host-side estimate of the live row count) selects the tile height and the split execution
@@ -70,7 +78,7 @@ enum { HS_EPI_STORE_F32 = 0, HS_EPI_ADD_F32 = 1, HS_EPI_SWIGLU_BF16 = 2 };
 // pending: if not null and the split execution was chosen, the ordered reduce is NOT launched: *pending receives the
 // number of chunk partials left in the workspace ([chunk][m_max][n] floats at lay.gemm_part) for the next kernel in
 // line to add up in chunk order and apply the epilogue (store / add to c); otherwise *pending = 0.
-void hs_launch_gemm(const hs_ctx* ctx, int epi, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c,
+void hs_launch_gemm(const hs_ctx* ctx, int epi, const void* a, const bf16_t* w, const bf16_t* w2, void* c,
                     const int32_t* m_dev, int m_max, int n, int k, int rows_hint, hipStream_t st,
                     int* pending = nullptr);
 int hs_gemm_chunks(int n, int k);
@@ -78,14 +86,14 @@ int hs_gemm_chunks(int n, int k);
 void hs_launch_embed(const hs_ctx* ctx, const hs_step* step, int batch, float* x, hipStream_t st);
 // RMSNorm of the residual stream; with pending_chunks > 0 it first adds the pending chunk partials of the
 // preceding projection (in chunk order) to x.
-void hs_launch_rmsnorm(const hs_ctx* ctx, float* x, const float* w, bf16_t* out, const int32_t* m_dev,
+void hs_launch_rmsnorm(const hs_ctx* ctx, float* x, const float* w, void* out, const int32_t* m_dev,
                        int pending_chunks, hipStream_t st);
 // Rotary embedding + KV write; with pending_chunks > 0 the QKV values are the chunk-ordered sums of the pending
 // partials instead of qkv.
 void hs_launch_rope_kv(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
-                       const hs_step* step, const float* qkv, bf16_t* q, int pending_chunks, hipStream_t st);
+                       const hs_step* step, const float* qkv, void* q, int pending_chunks, hipStream_t st);
 void hs_launch_attention(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, const hs_seq_state* seq,
-                         const hs_step* step, const bf16_t* q, bf16_t* out, hipStream_t st);
+                         const hs_step* step, const void* q, void* out, hipStream_t st);
 // Chunked prefill: row arrays of one call (rows of sequence b = its next tokens from the token log) and the causal
 // attention over [0, kv_done + i] for token i of the chunk.  len_plus1[b] = cached positions + 1.
 void hs_launch_prefill_rows(const hs_ctx* ctx, const hs_seq_state* seq, int32_t* kv_done, int chunk, hs_step* step,
@@ -96,7 +104,7 @@ void hs_launch_attention_prefill(const hs_ctx* ctx, int layer, const hs_kv_cache
 // Unit lists of the verify attention (one per hs_verify call, before the first layer) and their capacity.
 void hs_launch_attention_worklist(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, hipStream_t st);
 size_t hs_attention_max_units(const hs_ctx* ctx);
-void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, bf16_t* out,
+void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, void* out,
                                hipStream_t st);
 void hs_launch_argmax(const hs_ctx* ctx, const float* logits, int32_t* argmax, const int32_t* m_dev,
                       hipStream_t st);

@@ -10,7 +10,7 @@ from dataclasses import dataclass
 import numpy as np
 import torch
 
-from . import (HS_ACCEPT_GREEDY, HS_GATE_TABLE, HS_GATE_WORDS, HS_K_FIXED, hs_gate_table_build, hs_accept, hs_accept_args, hs_bind_workspace, hs_create, hs_debug_buffer, hs_debug_gemm,
+from . import (HS_FLAG_FP32_ACTIVATIONS, hs_debug_capture, hs_debug_capture_bytes, HS_ACCEPT_GREEDY, HS_GATE_TABLE, HS_GATE_WORDS, HS_K_FIXED, hs_gate_table_build, hs_accept, hs_accept_args, hs_bind_workspace, hs_create, hs_debug_buffer, hs_debug_gemm,
                hs_destroy, hs_draft, hs_draft_args, hs_draft_group, hs_group_draft_args, hs_get_profile, hs_kv_cache, hs_kv_commit, hs_limits,
                hs_model_desc, hs_policy, hs_poll_error, hs_prefill, hs_prefill_args, hs_seq_state, hs_set_flags, hs_set_profile, hs_step,
                hs_verify, hs_weights, hs_workspace_bytes)
@@ -50,7 +50,8 @@ class Engine:
 
     def __init__(self, shape, weights: dict, rope, max_batch: int, k_max: int, c_max: int, max_len: int,
                  w_max: int = 32, seq_caps=None, shuffle_pages_seed: int | None = None, n_layers: int | None = None,
-                 keep_logits: bool = True, g_max: int = 0, max_rows: int | None = None):
+                 keep_logits: bool = True, g_max: int = 0, max_rows: int | None = None, precise: bool = False):
+        """precise: run in the library's fp32-activation mode (plain kernels, float KV cache)."""
         self.shape = shape
         self.dev = torch.device("cuda:0")
         L = len(weights["wqkv"]) if n_layers is None else n_layers
@@ -78,8 +79,10 @@ class Engine:
             o += n
         self.block_table = _dev(bt)
         kv_elems = L * self.n_blocks * shape.n_kv_heads * 16 * shape.head_dim
-        self.kc = torch.zeros(kv_elems, dtype=torch.int16, device=self.dev)
-        self.vc = torch.zeros(kv_elems, dtype=torch.int16, device=self.dev)
+        self.precise = precise
+        kv_dtype = torch.float32 if precise else torch.int16
+        self.kc = torch.zeros(kv_elems, dtype=kv_dtype, device=self.dev)
+        self.vc = torch.zeros(kv_elems, dtype=kv_dtype, device=self.dev)
         # ---- context
         desc = hs_model_desc(L, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
                              shape.vocab, 16, shape.rms_eps)
@@ -97,6 +100,8 @@ class Engine:
         self.g_max = g_max
         lim = hs_limits(max_batch, k_max, c_max, self.max_rows, self.max_blocks, self.max_pos, w_max, g_max)
         self.ctx = hs_create(desc, hw, lim)
+        if precise:
+            hs_set_flags(self.ctx, HS_FLAG_FP32_ACTIVATIONS)   # before the workspace is sized
         nbytes = hs_workspace_bytes(self.ctx)
         self.workspace = torch.zeros(nbytes + 256, dtype=torch.uint8, device=self.dev)
         base = self.workspace.data_ptr()
@@ -369,8 +374,16 @@ class Engine:
             calls += 1
         return calls
 
+    def capture_last_layer(self):
+        """Switch on hs_debug_capture; returns the four snapshot slots as flat uint8 views (see the header)."""
+        n = hs_debug_capture_bytes(self.ctx)
+        self._capture = torch.zeros(n, dtype=torch.uint8, device=self.dev)
+        hs_debug_capture(self.ctx, self._capture.data_ptr(), n)
+        return [self._capture[i * (n // 4):(i + 1) * (n // 4)] for i in range(4)]
+
     def debug_tensor(self, which: int):
-        """0 final hidden (bf16 bits), 1 queries, 2 attention output, 3 workspace logits -- as flat torch views."""
+        """0 final hidden (bf16 bits), 1 queries, 2 attention output, 3 workspace logits, 4 residual stream (f32),
+        5 feed-forward activation -- as flat uint8 torch views."""
         ptr, n = hs_debug_buffer(self.ctx, which)
         off = ptr - self.workspace.data_ptr()
         return self.workspace[off:off + n]

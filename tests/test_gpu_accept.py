@@ -187,3 +187,27 @@ def test_tree_rejection_sampling_end_to_end(toy):
     eng.close()
     print("tree rejection e2e: steps", steps, "accepted", accepted)
     assert accepted > 5   # sampling soon leaves the greedy history; the draft path was still exercised
+
+
+def test_philox_words_equal_the_oracles_on_a_million_counters():
+    """The generator itself, GPU against the oracle, bit for bit: all four output words of 2^20 counters -- the
+    counter layouts hs_accept uses (position, draw kind 0..7, 64-bit sequence ids) and fully random 128-bit counters
+    -- under three keys."""
+    import oracle
+    from paper_2508_18588_amd import hs_debug_philox
+    rng = np.random.default_rng(31)
+    n = 1 << 20
+    ctr = rng.integers(0, 2 ** 32, (n, 4), dtype=np.uint64).astype(np.uint32)
+    half = n // 2
+    ctr[:half, 0] = rng.integers(0, 40000, half)      # positions
+    ctr[:half, 1] = rng.integers(0, 8, half)          # draw kinds
+    ctr[0] = 0
+    ctr[1] = 0xFFFFFFFF
+    d_ctr = torch.from_numpy(ctr.view(np.int32)).cuda()
+    d_out = torch.empty_like(d_ctr)
+    for seed in (0, 0xC0FFEE05 * 0x9E3779B1 & (2 ** 63 - 1), 2 ** 64 - 1):
+        hs_debug_philox(d_ctr.data_ptr(), seed, d_out.data_ptr(), n, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        got = d_out.cpu().numpy().view(np.uint32)
+        want = oracle.philox_batch(ctr, [seed & 0xFFFFFFFF, seed >> 32])
+        assert (got == want).all(), seed

@@ -15,13 +15,18 @@ from gpu_common import LOGIT_TOL, OracleBatch, check_cache, make_histories, np_o
 pytestmark = pytest.mark.gpu
 
 
-def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=(), gate=None):
+def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=(), gate=None, tol=LOGIT_TOL, rel_tol=None,
+             bruteforce=False):
     """Run until every budget is spent.  Returns statistics.  gate: the oracle's copy of the speculation gate's
     words (the engine holds its own); the oracle decides each step from the oracle-side totals, and a step it
-    switches off must come out of the HIP path as one row per live sequence."""
+    switches off must come out of the HIP path as one row per live sequence.  tol: absolute logit tolerance;
+    rel_tol: if given, additionally max|dlogit| of a row <= rel_tol * max|logit| of that row.
+    bruteforce: the GPU's acceptance is also compared with acceptance by definition (the oracle decodes
+    autoregressively from the same state and takes the longest prefix the draft tree spells out)."""
     import dataclasses
     B = len(ob.x)
-    stats = dict(steps=0, accepted=0, emitted=0, flagged=0, max_logit_err=0.0, rows=0, drafted=0, off_steps=0)
+    stats = dict(steps=0, accepted=0, emitted=0, flagged=0, max_logit_err=0.0, max_rel_err=0.0, rows=0, drafted=0,
+                 off_steps=0, positions=0, margin_below_tol=0)
     pol_on = pol
     pol_off = dataclasses.replace(pol, k_mode=oracle.K_FIXED, k_fixed=0)
     for _ in range(max_steps):
@@ -53,7 +58,13 @@ def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=(), gate=None):
             want = ob.logits(b, tree)
             err = float(np.abs(lg[sl] - want).max())
             stats["max_logit_err"] = max(stats["max_logit_err"], err)
-            assert err <= LOGIT_TOL, (b, err)
+            assert err <= tol, (b, err)
+            rel = float((np.abs(lg[sl] - want).max(1) / np.abs(want).max(1)).max())
+            stats["max_rel_err"] = max(stats["max_rel_err"], rel)
+            if rel_tol is not None:
+                assert rel <= rel_tol, (b, rel)
+            stats["positions"] += len(want)
+            stats["margin_below_tol"] += sum(top2_margin(r) <= tol for r in want)
             # the GPU's argmax must be the argmax of its own logits (lowest id on ties)
             assert st["argmax"][sl].tolist() == [int(np.argmax(r)) for r in lg[sl]]
             # oracle decision on oracle logits vs GPU decision; the GPU's walk must also be the greedy walk of
@@ -65,10 +76,16 @@ def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=(), gate=None):
             assert st["accept_len"][b] == a_g and n == a_g + 1
             assert st["out_tok"][b, :n].tolist() == out_g.tolist()
             assert st["path_row"][b, :n].tolist() == path_g.tolist()
+            if bruteforce:
+                a_b, out_b, path_b = ob.seqs[b].accept_greedy_bruteforce(tree["tok"], tree["parent"])
+                assert (a_b, out_b.tolist(), path_b.tolist()) == (a_o, out_o.tolist(), path_o.tolist())
+                stats["bruteforce_checked"] = stats.get("bruteforce_checked", 0) + 1
+                stats["bruteforce_equal"] = stats.get("bruteforce_equal", 0) + int(
+                    (a_b, out_b.tolist(), path_b.tolist()) == (a_g, out_g.tolist(), path_g.tolist()))
             if out_g.tolist() != out_o.tolist():
                 # allowed only where a visited row's top-2 margin is within the logit tolerance
                 visited = set(path_o.tolist()) | set(path_g.tolist())
-                assert min(top2_margin(want[r]) for r in visited) <= LOGIT_TOL, (b, out_g, out_o)
+                assert min(top2_margin(want[r]) for r in visited) <= tol, (b, out_g, out_o)
                 stats["flagged"] += 1
             ob.commit(b, tree, a_g, out_g, path_g, pol_on)   # the oracle follows the GPU's tokens
             stats["accepted"] += a_g
@@ -95,7 +112,7 @@ def lockstep(eng, ob, cands, pol, max_steps, check_kv_layers=(), gate=None):
     for b in range(B):
         assert toks[b, :len(ob.x[b])].tolist() == ob.x[b]
     for layer in check_kv_layers:
-        check_cache(eng, ob, layer)
+        check_cache(eng, ob, layer, tol=tol, rtol=2e-2 if rel_tol is None else 10 * rel_tol)
     return stats
 
 

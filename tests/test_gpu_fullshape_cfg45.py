@@ -17,7 +17,7 @@ import torch
 import oracle
 from hs_inputs import CONFIG_SHAPES, config_seed, lengths_lognormal
 from hs_inputs.device import fill_kv_random, make_weights_device, rope_device
-from gpu_common import np_of
+from gpu_common import check_last_layer_projections, np_of
 
 pytestmark = pytest.mark.gpu
 
@@ -103,10 +103,16 @@ def test_config4_launch_sampled_parity_and_greedy_commit():
                          parent=np.arange(-1, n - 1), pos=np.arange(int(ctx[b]), int(ctx[b]) + n)))
         parents.append(rows[-1]["parent"])
     m = eng.set_rows(rows)
+    cap = eng.capture_last_layer()
+    eng.set_rows_hint(m)
     eng.verify()
     torch.cuda.synchronize()
     assert eng.poll_error() == 0
     ro = np_of(eng.st["row_off"])
+    # every projection of the last layer at this launch (4352 rows: twelve 384-row passes) against its definition
+    print("config 4 last-layer projections, worst abs error:",
+          check_last_layer_projections(eng, cap, m, [0, 383, 384, 2175, 2176, m - 2, m - 1]
+                                       + rng.integers(0, m, 10).tolist(), rng))
     # sequences: 33 nodes (seven row tiles per KV head), the longest and the shortest context, a few in between
     picks = [32, 65, 98, int(np.argmax(ctx)), int(np.argmin(ctx)), 0, 3, 140, 255]
     worst = check_attention_rows(eng, m, ctx, ro, parents, picks, rng)
@@ -193,9 +199,16 @@ def test_config5_launch_tree_draft_verify_rejection_commit():
         assert len(t["tok"]) == 1 + 8 + (8 - b % 9 if b % 9 < 8 else 0)
         trees.append(t)
     m = int(ro[B])
+    cap = eng.capture_last_layer()
+    eng.set_rows_hint(m)
     eng.verify()
     torch.cuda.synchronize()
     assert eng.poll_error() == 0
+    # every projection of the last layer at the 14B shape (N, K = 7168 x 5120, 5120 x 5120, 2 x 13824 x 5120,
+    # 5120 x 13824) against its definition
+    print("config 5 last-layer projections, worst abs error:",
+          check_last_layer_projections(eng, cap, m, [0, 383, 384, 767, 768, m - 1] + rng.integers(0, m, 10).tolist(),
+                                       rng))
     ctx = np.full(B, Lc, np.int64)
     worst = check_attention_rows(eng, m, ctx, ro, [t["parent"] for t in trees], [0, 1, 4, 8, 9, 31, 63], rng)
     check_lm_head(eng, m, rng)

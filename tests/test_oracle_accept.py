@@ -99,6 +99,36 @@ def oracle_spec_rollout(model, prompt, hist, n_new, W, m_min, k_mode, k_fixed, k
     return x[len(prompt):], steps, accepted
 
 
+def test_bruteforce_greedy_accept_is_autoregressive_decode_plus_longest_prefix():
+    """orc_accept_greedy_bruteforce on the real decoder: its emitted tokens are the plain autoregressive greedy
+    continuation (oracle.ar_greedy, a separate loop), its accepted length the longest prefix of that continuation
+    that the draft tree spells out (computed here from the token lists) -- and the one-pass rule (each node's argmax
+    compared with its children) gives the same answer.  Chains and 2-branch trees, drafts built to agree with the
+    continuation for 0..K tokens."""
+    w = make_weights(SHAPE, seed=6, std=0.3)
+    model = oracle.Model(SHAPE, w, rope_table(64, SHAPE.head_dim))
+    rng = np.random.default_rng(3)
+    prompt = rng.integers(0, SHAPE.vocab, 9).astype(np.int32)
+    seq = oracle.Seq(model, 40)
+    seq.extend(prompt[:-1])
+    g = oracle.ar_greedy(seq, prompt[-1], 7)
+    seq.truncate(len(prompt) - 1)
+    other = lambda t: (t + 1) % SHAPE.vocab
+    for agree0 in range(0, 6):
+        for agree1 in range(0, 6):
+            c0 = [g[i] if i < agree0 else other(g[i]) for i in range(5)]
+            c1 = [g[i] if i < agree1 else other(other(g[i])) for i in range(5)]
+            for chains in ([c0], [c0, c1]):
+                t = oracle.build_tree(chains, int(prompt[-1]), len(prompt) - 1)
+                a, out, path = seq.accept_greedy_bruteforce(t["tok"], t["parent"])
+                assert len(seq) == len(prompt) - 1
+                want = min(5, max(agree0, agree1 if len(chains) == 2 else 0))
+                assert a == want and out.tolist() == g[:want + 1]
+                lg = seq.tree_logits(t["tok"], t["parent"], plain=True)
+                a1, out1, path1 = oracle.accept_greedy(t["tok"], t["parent"], [oracle.argmax(r) for r in lg])
+                assert (a1, out1.tolist(), path1.tolist()) == (a, out.tolist(), path.tolist())
+
+
 @pytest.mark.parametrize("k_mode", [oracle.K_FIXED, oracle.K_MATCHLEN, oracle.K_AIMD])
 def test_speculative_greedy_equals_autoregressive_greedy(k_mode):
     w = make_weights(SHAPE, seed=5, std=0.3)
@@ -127,6 +157,26 @@ def test_philox_known_answers(golden_dir):
         assert oracle.philox4x32_10(v[0:4], v[4:6]) == v[6:10]
         n += 1
     assert n == 3
+
+
+def test_philox_batch_is_the_generator_per_counter_and_a_bijection(golden_dir):
+    """The bulk form equals the single-counter form (which carries the published known answers), and -- a keyed
+    bijection of the counter space -- maps 2^16 distinct counters to 2^16 distinct outputs."""
+    kat = [[int(t, 16) for t in line.split()] for line in open(os.path.join(golden_dir, "philox4x32_10_kat.txt"))
+           if line.strip() and not line.startswith("#")]
+    for v in kat:
+        assert oracle.philox_batch(np.array([v[0:4]], np.uint32), v[4:6])[0].tolist() == v[6:10]
+    rng = np.random.default_rng(5)
+    ctr = rng.integers(0, 2 ** 32, (2000, 4), dtype=np.uint64).astype(np.uint32)
+    key = [0xDEADBEEF, 0x12345678]
+    out = oracle.philox_batch(ctr, key)
+    for i in range(0, 2000, 97):
+        assert out[i].tolist() == oracle.philox4x32_10(ctr[i].tolist(), key)
+    grid = np.zeros((1 << 16, 4), np.uint32)
+    grid[:, 0] = np.arange(1 << 16) & 0xFF
+    grid[:, 1] = np.arange(1 << 16) >> 8
+    o = oracle.philox_batch(grid, key)
+    assert len({tuple(r) for r in o.tolist()}) == 1 << 16
 
 
 def test_uniform_layout_and_range():

@@ -157,12 +157,20 @@ def test_tree_logits_equal_plain_sequences(small):
     tree = oracle.build_tree([[42, 7, 9], [42, 11, 3]], root_tok=prefix[-1], l_cached=len(prefix) - 1)
     seq = oracle.Seq(model, 32)
     seq.extend(prefix[:-1])
-    lg = seq.tree_logits(tree["tok"], tree["parent"])
+    lg = seq.tree_logits(tree["tok"], tree["parent"], plain=True)
     assert len(seq) == len(prefix) - 1
     paths = {0: [], 1: [42], 2: [42, 7], 3: [42, 7, 9], 4: [42, 11], 5: [42, 11, 3]}
     for r, extra in paths.items():
         want = oracle.Seq(model, 32).extend(prefix + extra)
         np.testing.assert_array_equal(lg[r], want)
+    # the shared-prefix walk (used where long chains are followed) gives the same bits, on this tree, on a chain
+    # and on a tree whose second branch forks at the root
+    np.testing.assert_array_equal(seq.tree_logits(tree["tok"], tree["parent"]), lg)
+    assert len(seq) == len(prefix) - 1
+    for chains in ([[5, 6, 7, 8, 9, 10]], [[1, 2, 3], [4, 5, 6]], [[]]):
+        t = oracle.build_tree(chains, root_tok=prefix[-1], l_cached=len(prefix) - 1)
+        np.testing.assert_array_equal(seq.tree_logits(t["tok"], t["parent"]),
+                                      seq.tree_logits(t["tok"], t["parent"], plain=True))
 
 
 def test_loaded_cache_reproduces_computed_cache(small):
@@ -183,3 +191,32 @@ def test_loaded_cache_reproduces_computed_cache(small):
 def test_argmax_lowest_id_on_ties():
     assert oracle.argmax(np.array([1.0, 3.0, 3.0, 2.0])) == 1
     assert oracle.argmax(np.array([5.0])) == 0
+
+
+def test_residual_trace_is_the_truncated_models_hidden_state(small):
+    """The inspection hook returns the residual stream after the embedding and after every layer: row 0 is the
+    token's embedding, and row l is exactly what a decoder made of the first l layers feeds its final norm -- so the
+    logits of that shorter model (computed by a separate oracle instance) are lm_head . RMSNorm(row l)."""
+    w, rope, model = small
+    toks = [3, 17, 42, 8, 29]
+    s = oracle.Seq(model, 16)
+    s.extend(toks[:-1])
+    logits, h = s.push_traced(toks[-1])
+    f = lambda a: bf16_to_f32(a).astype(np.float64)
+    np.testing.assert_array_equal(h[0], f(w["embed"])[toks[-1]])
+
+    def head(x):
+        n = x / np.sqrt((x * x).mean() + SHAPE.rms_eps) * w["norm_f"].astype(np.float64)
+        return f(w["lm_head"]) @ n
+
+    np.testing.assert_allclose(head(h[-1]), logits, rtol=1e-12, atol=1e-12)
+    assert np.abs(h[1] - h[0]).max() > 1e-3 and np.abs(h[2] - h[1]).max() > 1e-3
+    for l in (1,):
+        wl = {k: (v[:l] if isinstance(v, list) else v) for k, v in w.items()}
+        short = oracle.Seq(oracle.Model(SHAPE, wl, rope), 16)
+        short.extend(toks[:-1])
+        np.testing.assert_allclose(head(h[l]), short.push(toks[-1]), rtol=1e-12, atol=1e-12)
+    # the hook is off again: a later push leaves the buffer alone
+    before = h.copy()
+    s.push(5)
+    np.testing.assert_array_equal(h, before)
