@@ -226,6 +226,19 @@ hs_status hs_bind_workspace(hs_ctx* ctx, void* dev_ptr, size_t bytes);
  * row_off.  Reads seq.tail/tail_len/seq_len/k_state/budget_left. */
 hs_status hs_draft(hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step, hs_stream stream);
 
+/* hs_draft for callers that cannot allocate device memory or have none to spare for this call (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same results bit for bit, but the
+ * kernels' scratch -- one 8-byte winner per (sequence, candidate, 4096-token history segment) -- lives in a static
+ * device array inside the library (65536 slots = 512 KiB, held by every GPU the library runs on until the process
+ * ends) instead of the bound workspace; no workspace needs to be bound, and nothing is allocated or freed.
+ * HS_ERR_CAPACITY if batch * n_cand * ceil((max_pos + 32) / 4096) exceeds 65536.  The device error word is the
+ * workspace's if one is bound, else a word inside the static array (hs_poll_error reads whichever applies).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams) race;
+ * calls on one stream, or ordered by events, are safe.  The array's address is looked up per device on the first
+ * call made with that device current. */
+hs_status hs_draft_static(hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
+                          hs_stream stream);
+
 /* Reward-aware draft from ALL responses of the prompt's last rollout (Sec. 5.3: the responses are indexed together,
  * every branch carries the summed rewards of the responses below it, and where the continuations of the matched
  * pattern differ the branch with the highest priority is followed).  Stated on the flat responses:

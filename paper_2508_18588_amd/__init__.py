@@ -120,7 +120,7 @@ HS_PREFILL_CHUNK_MAX = 1024
 EXPORTS = ("hs_create", "hs_destroy", "hs_last_error", "hs_set_flags", "hs_workspace_bytes", "hs_bind_workspace",
            "hs_draft", "hs_draft_group", "hs_verify", "hs_accept", "hs_kv_commit", "hs_poll_error", "hs_debug_buffer",
            "hs_set_profile", "hs_get_profile", "hs_debug_gemm", "hs_gate_table_build", "hs_prefill", "hs_plan_allocation",
-           "hs_debug_capture", "hs_debug_capture_bytes", "hs_debug_philox")
+           "hs_debug_capture", "hs_debug_capture_bytes", "hs_debug_philox", "hs_draft_static")
 
 _lib = None
 
@@ -147,6 +147,7 @@ def lib():
         L.hs_workspace_bytes.restype = C.c_size_t
         L.hs_bind_workspace.argtypes = [vp, vp, C.c_size_t]
         L.hs_draft.argtypes = [vp, C.POINTER(hs_draft_args), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
+        L.hs_draft_static.argtypes = [vp, C.POINTER(hs_draft_args), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
         L.hs_draft_group.argtypes = [vp, C.POINTER(hs_group_draft_args), C.POINTER(hs_seq_state), C.POINTER(hs_step),
                                      vp]
         L.hs_verify.argtypes = [vp, C.POINTER(hs_kv_cache), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
@@ -212,6 +213,10 @@ def hs_bind_workspace(ctx, dev_ptr: int, nbytes: int):
 
 def hs_draft(ctx, args: hs_draft_args, seq: hs_seq_state, step: hs_step, stream=None):
     _check(ctx, lib().hs_draft(ctx, C.byref(args), C.byref(seq), C.byref(step), stream))
+
+
+def hs_draft_static(ctx, args: hs_draft_args, seq: hs_seq_state, step: hs_step, stream=None):
+    _check(ctx, lib().hs_draft_static(ctx, C.byref(args), C.byref(seq), C.byref(step), stream))
 
 
 def hs_draft_group(ctx, args: hs_group_draft_args, seq: hs_seq_state, step: hs_step, stream=None):

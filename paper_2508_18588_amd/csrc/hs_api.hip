@@ -242,6 +242,28 @@ hs_status hs_draft(hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* s
     return HS_OK;
 }
 
+hs_status hs_draft_static(hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
+                          hs_stream stream) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    if (!args || !args->hist || !args->hist_off) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_static: null history");
+    if (args->n_cand < 1 || args->n_cand > ctx->lim.c_max) return fail(ctx, HS_ERR_CAPACITY, "hs_draft_static: n_cand");
+    if (!policy_ok(ctx, &args->policy)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_static: policy out of range");
+    if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_static: sequence state");
+    if (!step_ok(step)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_static: step arrays");
+    if ((long long)seq->batch * args->n_cand * ctx->max_segs > HS_DRAFT_STATIC_ENTRIES)
+        return fail(ctx, HS_ERR_CAPACITY,
+                    "hs_draft_static: batch * n_cand * history segments exceeds the static scratch (65536 slots); "
+                    "use hs_draft with a workspace");
+    (void)hipGetLastError();
+    hipError_t why = hipSuccess;
+    if (!hs_launch_draft_static(ctx, args, seq, step, (hipStream_t)stream, &why)) {
+        ctx->err = std::string("hs_draft_static: address of the static scratch array: ") + hipGetErrorString(why);
+        return HS_ERR_HIP;
+    }
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_draft_static", e);
+    return HS_OK;
+}
+
 hs_status hs_draft_group(hs_ctx* ctx, const hs_group_draft_args* args, const hs_seq_state* seq, hs_step* step,
                          hs_stream stream) {
     if (!ctx) return HS_ERR_INVALID_ARG;
@@ -433,15 +455,21 @@ hs_status hs_kv_commit(hs_ctx* ctx, const hs_kv_cache* cache, hs_seq_state* seq,
 
 hs_status hs_poll_error(hs_ctx* ctx, hs_stream stream, uint32_t* error_bits) {
     if (!ctx || !error_bits) return HS_ERR_INVALID_ARG;
-    if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
+    // the error word: in the workspace, or -- no workspace bound, only hs_draft_static can have run -- in its array
+    char* word = ctx->ws ? ctx->ws + ctx->lay.err : nullptr;
+    if (!word) {
+        hipError_t why = hipSuccess;
+        word = reinterpret_cast<char*>(hs_draft_static_error_word(&why));
+        if (!word) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
+    }
     hipStream_t st = (hipStream_t)stream;
     uint32_t v = 0;
-    if (hipMemcpyAsync(&v, ctx->ws + ctx->lay.err, 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+    if (hipMemcpyAsync(&v, word, 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
         hipStreamSynchronize(st) != hipSuccess)
         return fail(ctx, HS_ERR_HIP, "hs_poll_error: copy failed");
     if (v != 0) {
         uint32_t zero = 0;
-        if (hipMemcpyAsync(ctx->ws + ctx->lay.err, &zero, 4, hipMemcpyHostToDevice, st) != hipSuccess ||
+        if (hipMemcpyAsync(word, &zero, 4, hipMemcpyHostToDevice, st) != hipSuccess ||
             hipStreamSynchronize(st) != hipSuccess)
             return fail(ctx, HS_ERR_HIP, "hs_poll_error: clear failed");
     }

@@ -8,6 +8,8 @@
 // key.  Kernel 2 (build): one thread per sequence reduces the segment winners, applies the draft-length policy,
 // merges the candidates' chains into a token tree, and a workgroup-wide prefix sum over node counts yields the
 // ragged row offsets the verify step consumes.
+#include <mutex>
+
 #include "hs_internal.h"
 
 namespace {
@@ -394,10 +396,10 @@ __global__ __launch_bounds__(256) void draft_group_walk_kernel(
 
 }  // namespace
 
-void hs_launch_draft(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
-                     hipStream_t st) {
-    unsigned long long* best = reinterpret_cast<unsigned long long*>(ctx->ws + ctx->lay.draft_best);
-    uint32_t* err = reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.err);
+namespace {
+
+void launch_draft(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
+                  unsigned long long* best, uint32_t* err, hipStream_t st) {
     const hs_policy& p = args->policy;
     dim3 grid(ctx->max_segs, seq->batch * args->n_cand);
     hipLaunchKernelGGL(draft_scan_kernel, grid, dim3(256), 0, st, args->hist, args->hist_off, args->n_cand,
@@ -409,6 +411,58 @@ void hs_launch_draft(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_
                        step->draft_start, step->match_len, step->draft_len, step->row_off, step->tok, step->pos,
                        step->parent, step->anc_mask, step->row2seq, err, 0, nullptr, seq->gate,
                        (const unsigned long long*)seq->counters);
+}
+
+}  // namespace
+
+void hs_launch_draft(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
+                     hipStream_t st) {
+    launch_draft(ctx, args, seq, step, reinterpret_cast<unsigned long long*>(ctx->ws + ctx->lay.draft_best),
+                 reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.err), st);
+}
+
+// ---- hs_draft for callers that cannot allocate: the segment winners (and, with no workspace bound, the error word)
+// live in a static device array instead of the caller's workspace.
+namespace {
+
+// [0, HS_DRAFT_STATIC_ENTRIES): segment winners, 8 bytes each; then one 8-byte slot whose first word is the error word.
+static __device__ __align__(256) unsigned long long scratch[HS_DRAFT_STATIC_ENTRIES + 1];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+unsigned long long* scratch_ptr[MAX_DEVICES];   // device address of `scratch` on each device (each has its own copy)
+
+// The address of this device's copy of the array, looked up once per device with that device current.
+unsigned long long* scratch_on_current_device(hipError_t* why) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= MAX_DEVICES) { *why = e != hipSuccess ? e : hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { *why = e != hipSuccess ? e : hipErrorInvalidSymbol; return nullptr; }
+        scratch_ptr[dev] = static_cast<unsigned long long*>(p);
+    }
+    return scratch_ptr[dev];
+}
+
+}  // namespace
+
+uint32_t* hs_draft_static_error_word(hipError_t* why) {
+    unsigned long long* base = scratch_on_current_device(why);
+    return base ? reinterpret_cast<uint32_t*>(base + HS_DRAFT_STATIC_ENTRIES) : nullptr;
+}
+
+bool hs_launch_draft_static(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
+                            hipStream_t st, hipError_t* why) {
+    unsigned long long* base = scratch_on_current_device(why);
+    if (!base) return false;
+    uint32_t* err = ctx->ws ? reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.err)
+                            : reinterpret_cast<uint32_t*>(base + HS_DRAFT_STATIC_ENTRIES);
+    // every winner slot the build kernel reads is written by the scan kernel of the same call: nothing to clear
+    launch_draft(ctx, args, seq, step, base, err, st);
+    return true;
 }
 
 void hs_launch_draft_group(const hs_ctx* ctx, const hs_group_draft_args* args, const hs_seq_state* seq,

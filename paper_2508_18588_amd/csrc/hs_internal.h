@@ -110,6 +110,13 @@ void hs_launch_argmax(const hs_ctx* ctx, const float* logits, int32_t* argmax, c
                       hipStream_t st);
 void hs_launch_draft(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
                      hipStream_t st);
+// hs_draft_static: segment winners in a static device array of HS_DRAFT_STATIC_ENTRIES slots.  Returns false (with the
+// HIP error) if the array's address on the current device cannot be had.  hs_draft_static_error_word: the error word
+// kept inside that array (used when no workspace is bound).
+constexpr int HS_DRAFT_STATIC_ENTRIES = 1 << 16;
+bool hs_launch_draft_static(const hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* seq, hs_step* step,
+                            hipStream_t st, hipError_t* why);
+uint32_t* hs_draft_static_error_word(hipError_t* why);
 void hs_launch_draft_group(const hs_ctx* ctx, const hs_group_draft_args* args, const hs_seq_state* seq,
                            hs_step* step, hipStream_t st);
 void hs_launch_accept(const hs_ctx* ctx, const hs_accept_args* args, const hs_seq_state* seq, hs_step* step,
