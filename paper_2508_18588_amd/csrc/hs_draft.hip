@@ -234,7 +234,21 @@ __global__ __launch_bounds__(256) void draft_build_kernel(
         if (threadIdx.x == 0) carry_s = carry + total;
         __syncthreads();
     }
-    if (threadIdx.x == 0) row_off[batch] = min(carry_s, max_rows);
+    if (threadIdx.x == 0) {
+        int total = carry_s;
+        if (total > max_rows) {
+            // Only with limits that hs_create does not admit (max_rows < max_batch * nodes): the first sequence that
+            // does not fit and every one after it get no rows, consistently for the kernels that read row_off.
+            int cut = -1;
+            for (int b = 0; b < batch; b++) {
+                const int end = b + 1 < batch ? row_off[b + 1] : total;
+                if (cut < 0 && end > max_rows) cut = row_off[b];
+                if (cut >= 0 && b + 1 < batch) row_off[b + 1] = cut;
+            }
+            total = cut;
+        }
+        row_off[batch] = total;
+    }
 }
 
 

@@ -196,7 +196,8 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
 // kv_done advances by n_b.
 __global__ __launch_bounds__(256) void prefill_rows_kernel(
     const int32_t* __restrict__ seq_len, int32_t* __restrict__ kv_done, const int32_t* __restrict__ tokens,
-    int tokens_stride, int batch, int chunk, int max_rows, int max_pos, int32_t* __restrict__ row_off,
+    int tokens_stride, int batch, int chunk, int max_rows, int max_pos, const int32_t* __restrict__ block_table,
+    int max_blocks, int32_t* __restrict__ row_off,
     int32_t* __restrict__ tok, int32_t* __restrict__ pos, int32_t* __restrict__ parent, int32_t* __restrict__ row2seq,
     int32_t* __restrict__ len_plus1, uint32_t* __restrict__ err) {
     __shared__ int sw[4];
@@ -212,6 +213,11 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(
             want = max(0, min(chunk, seq_len[b] - 1 - done));
             if (done + want > max_pos) {        // rotary table too short: nothing of this sequence is laid out
                 atomicOr(err, (uint32_t)HS_DEV_POSITION_OVERFLOW);
+                want = 0;
+            } else if (want > 0 && (done + want > max_blocks * 16 ||
+                                    block_table[(size_t)b * max_blocks + ((done + want - 1) >> 4)] < 0)) {
+                // the sequence outgrows its block table (or the pages the caller gave it): likewise
+                atomicOr(err, (uint32_t)HS_DEV_BLOCK_TABLE_OVERFLOW);
                 want = 0;
             }
         }
@@ -255,7 +261,8 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(
 void hs_launch_prefill_rows(const hs_ctx* ctx, const hs_seq_state* seq, int32_t* kv_done, int chunk, hs_step* step,
                             int32_t* len_plus1, hipStream_t st) {
     hipLaunchKernelGGL(prefill_rows_kernel, dim3(1), dim3(256), 0, st, seq->seq_len, kv_done, seq->tokens,
-                       seq->tokens_stride, seq->batch, chunk, ctx->lim.max_rows, ctx->lim.max_pos, step->row_off,
+                       seq->tokens_stride, seq->batch, chunk, ctx->lim.max_rows, ctx->lim.max_pos, seq->block_table,
+                       ctx->lim.max_blocks_per_seq, step->row_off,
                        step->tok, step->pos, step->parent, step->row2seq, len_plus1,
                        reinterpret_cast<uint32_t*>(ctx->ws + ctx->lay.err));
 }

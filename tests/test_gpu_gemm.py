@@ -77,15 +77,17 @@ def test_projection_equals_its_definition_for_every_row_count_and_hint(rig, name
         assert (outs[0] == outs[1]).all() and (outs[0] == outs[2]).all(), (name, m, "row hint changed the bits")
 
 
-def test_lm_head_of_a_small_vocabulary_splits_k_and_has_room_for_its_partial_sums():
+@pytest.mark.parametrize("vocab", [4160, 4097])
+def test_lm_head_of_a_small_vocabulary_splits_k_and_has_room_for_its_partial_sums(vocab):
     """vocab 4160 with d_model 1024: the LM head runs in 3 K chunks whose partial sums (3 x 4160 columns) are wider
     than those of any layer projection; the workspace must hold them.  One projection against its definition, then a
-    few decode steps end to end (the LM head inside hs_verify) against the oracle."""
+    few decode steps end to end (the LM head inside hs_verify) against the oracle.  vocab 4097: rows of the partial
+    sums and of the logits are not 16-byte aligned (the ordered reduce and the argmax take their scalar paths)."""
     import oracle
     from paper_2508_18588_amd.runtime import Engine, Policy
     from gpu_common import OracleBatch
     from test_gpu_decode import lockstep
-    shape = ModelShape(n_layers=1, d_model=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ffn=1024, vocab=4160)
+    shape = ModelShape(n_layers=1, d_model=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ffn=1024, vocab=vocab)
     w = make_weights(shape, 53)
     rope = rope_table(128, shape.head_dim)
     eng = Engine(shape, w, rope, max_batch=4, k_max=4, c_max=1, max_len=64, max_rows=300)

@@ -137,6 +137,15 @@ def test_prefill_edge_cases(toy):
     assert eng.poll_error() & 2                      # position overflow
     assert np_of(eng.kv_done)[:2].tolist() == [39, 0]
     eng.close()
+    # a text longer than the pages its sequence was given: flagged (block-table overflow), nothing of it is laid out,
+    # kv_done does not move; the other sequence is served
+    eng = Engine(shape, w, rope, max_batch=2, k_max=4, c_max=1, max_len=120, seq_caps=[120, 40], max_rows=300)
+    eng.load_sequences(toks, budgets=[8] * 2)
+    eng.prefill_chunked(512)
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 1                     # HS_DEV_BLOCK_TABLE_OVERFLOW
+    assert np_of(eng.kv_done)[:2].tolist() == [39, 0]
+    eng.close()
 
 
 def test_prefill_7b_shape_two_layers():
