@@ -86,6 +86,13 @@ def main():
                     help="debug: history = the rollout itself (every draft accepted, rows per step at their maximum)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events (roofline null)")
+    ap.add_argument("--gemm-probe", default="",
+                    help="instead of the benchmark: one layer's four projections and the LM head of the configuration's "
+                         "shape, each launched alone at these row counts (comma separated), timed with events; "
+                         "prints one JSON line (the command rocprofv3 counter runs of the GEMM kernel are made with)")
+    ap.add_argument("--draft-probe", action="store_true",
+                    help="instead of the benchmark: the draft scan on a scaled input (128 sequences x 16 responses x "
+                         "32768 tokens = 268 MB of history through hs_draft_group), timed with events")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed steps run three 1 GiB device-to-device copies: a kernel of known traffic "
                          "that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -104,6 +111,10 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
     hs.lib()
+    if args.gemm_probe:
+        return gemm_probe_main(args, [int(r) for r in args.gemm_probe.split(",")])
+    if args.draft_probe:
+        return draft_probe_main(args)
     cfg = args.config
     wp = workload_params(cfg, args.reuse)
     shape = CONFIG_SHAPES[cfg]
@@ -131,7 +142,8 @@ def main():
     max_len = int(ctx.max()) + 1 + T
     rope = rope_device(max_len + 64, shape.head_dim)
     eng = Engine(shape, w, rope, max_batch=B, k_max=wp["k_max"], c_max=n_cand, max_len=max_len,
-                 seq_caps=[int(c) + 1 + T for c in ctx], shuffle_pages_seed=(None if os.environ.get("HS_BENCH_PAGES") == "bump" else seed & 0xFFFF), keep_logits=False)
+                 seq_caps=[int(c) + 1 + T for c in ctx], shuffle_pages_seed=seed & 0xFFFF, keep_logits=False,
+                 workspace_logits=(mode == hs.HS_ACCEPT_REJECTION))   # rejection sampling reads the logits
     # context: L_b cached positions (synthetic K/V of the scale a real prefill writes) + one committed root token
     kv_std = 0.02 * float(np.sqrt(shape.d_model))
     fill_kv_random(eng.kc, eng.vc, seed + 1, kv_std)
@@ -167,16 +179,32 @@ def main():
     state = [eng.seq_len, eng.tail, eng.tail_len, eng.k_state, eng.budget_left]
     snap = [t.clone() for t in state] if wp.get("snapshot") else None
 
-    def one_step():
+    step_events = []   # (before hs_draft, after hs_draft, after hs_kv_commit) of every timed step
+
+    def one_step(timed=False):
         if snap is not None:
             for t, s0 in zip(state, snap):
                 t.copy_(s0)
-        eng.step(pol, mode, temperature, philox_seed)
+        if not timed:
+            eng.step(pol, mode, temperature, philox_seed)
+            return
+        # HIP events on the stream the four calls are enqueued on (torch's current stream)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record()
+        eng.draft(pol)
+        ev[1].record()
+        eng.verify()
+        eng.accept_commit(pol, mode, temperature, philox_seed)
+        ev[2].record()
+        step_events.append(ev)
 
     # ---- warm-up, then the timed region
     first = None
     warm_rows = []
+    want_sample = not args.no_cpu_baseline and n_cand == 1 and mode == hs.HS_ACCEPT_GREEDY
     for i in range(args.warmup):
+        if i == 0 and want_sample:   # the oracle-checked step keeps its logits (the timed steps keep none)
+            eng.set_flags(eng.flags | hs.HS_FLAG_WORKSPACE_LOGITS)
         one_step()
         warm_rows.append(int(eng.st["row_off"][B].item()))
         if i == 0:
@@ -185,11 +213,13 @@ def main():
             # logits of the sequence the oracle will re-compute (shortest context among those that drafted)
             ro = first["row_off"]
             cand = [b for b in range(B) if ro[b + 1] - ro[b] > 1]
-            if cand:
+            if cand and want_sample:
                 bs = min(cand, key=lambda i: len(toks[i]))
                 lg = eng.debug_tensor(3).view(torch.float32).view(-1, shape.vocab)
                 first["sample_seq"] = bs
                 first["sample_logits"] = lg[ro[bs]:ro[bs + 1]].cpu().numpy().copy()
+            if want_sample:
+                eng.set_flags(eng.flags & ~hs.HS_FLAG_WORKSPACE_LOGITS)
     torch.cuda.synchronize()
     if args.warmup > 0:
         # launch-shape hint: mean rows of the warm-up steps after the first (in which every sequence drafts a full
@@ -205,11 +235,15 @@ def main():
     t2 = time.perf_counter()
     step_rows = []
     for _ in range(args.steps):
-        one_step()
+        one_step(timed=True)
         if args.print_rows:     # diagnostic: synchronises every step, the timing of such a run means nothing
             step_rows.append(int(eng.st["row_off"][B].item()))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t2
+    ev_all = sorted(e[0].elapsed_time(e[2]) for e in step_events)
+    ev_vac = sorted(e[1].elapsed_time(e[2]) for e in step_events)
+    ev_draft = sorted(e[0].elapsed_time(e[1]) for e in step_events)
+    med = lambda v: (v[(len(v) - 1) // 2] + v[len(v) // 2]) / 2
     if step_rows:
         log(f"rows per timed step: {step_rows}")
     prof = None if args.no_profile else eng.get_profile()
@@ -294,24 +328,100 @@ def main():
                    # Sec. 5.4 (throughput-aware control): drafting pays while the acceptance rate stays above this
                    "break_even_acceptance_rate": round(max(0.0, ms_per_step / ar_ms - 1.0) * seq_steps
                                                        / max(1, drafted), 3),
-                   "kv_resident_gb": round(float(len0.sum()) * kv_tok_bytes * n_layers / 1e9, 1), **extras},
+                   "kv_resident_gb": round(float(len0.sum()) * kv_tok_bytes * n_layers / 1e9, 1),
+                   # HIP events per step: all four calls / verify + accept + commit / the draft call alone
+                   "median_ms_per_step": round(med(ev_all), 3),
+                   "median_verify_accept_commit_ms": round(med(ev_vac), 3),
+                   "median_draft_us": round(med(ev_draft) * 1e3, 1),
+                   "accepted_tokens_per_s_at_median_step": round(accepted / args.steps / (med(ev_all) * 1e-3), 1),
+                   **extras},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     if args.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda:0")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        t3 = time.perf_counter()
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        log(f"calibration copy: 3 x 1 GiB read + 1 GiB written in {(time.perf_counter() - t3) * 1e3:.2f} ms "
-            f"({3 * 2 * 2 ** 30 / (time.perf_counter() - t3) / 1e9:.0f} GB/s read+write)")
+        calibration_copy(torch)
     eng.close()
     print(json.dumps(result), flush=True)
 
 
-def gemm_probe(eng, shape, rows):
+def gemm_probe_main(args, rows_list):
+    """One layer of the configuration's shape; every projection alone at each row count."""
+    import torch
+
+    from paper_2508_18588_amd.runtime import Engine
+    from hs_inputs import CONFIG_SHAPES, config_seed
+    from hs_inputs.device import make_weights_device, rope_device
+    shape = CONFIG_SHAPES[args.config]
+    w = make_weights_device(shape, config_seed(args.config), 1)
+    m_max = max(rows_list)
+    eng = Engine(shape, w, rope_device(64, shape.head_dim), max_batch=max(1, (m_max + 16) // 17), k_max=16, c_max=1,
+                 max_len=32, max_rows=m_max, keep_logits=False)
+    out = {"probe": "gemm", "config": args.config, "per_rows": [gemm_probe(eng, shape, r, reps=args.steps) for r in rows_list]}
+    if args.calibrate_copy:
+        calibration_copy(torch)
+    eng.close()
+    print(json.dumps(out), flush=True)
+
+
+def draft_probe_main(args):
+    """The draft scan in its bandwidth regime: 128 sequences, 16 previous-epoch responses of 32768 tokens each
+    (4 bytes per token: 268 MB of history read once per call)."""
+    import numpy as np
+    import torch
+
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    from hs_inputs import CONFIG_SHAPES, config_seed, make_weights, rope_table
+    shape = CONFIG_SHAPES[1]                     # the draft does not touch the model: the toy shape keeps set-up short
+    B, G, LH, W = 128, 16, 32768, 16
+    rng = np.random.default_rng(config_seed(3))
+    eng = Engine(shape, make_weights(shape, 1), rope_table(LH + 64, shape.head_dim), max_batch=B, k_max=16, c_max=1,
+                 max_len=64, g_max=G, keep_logits=False)
+    toks = [rng.integers(0, 152064, 40).astype(np.int32) for _ in range(B)]
+    groups = []
+    for b in range(B):
+        row = []
+        for g in range(G):
+            hst = rng.integers(0, 152064, LH).astype(np.int32)
+            at = int(rng.integers(W, LH - 64))
+            hst[at - 8:at] = toks[b][-8:]        # every response contains the sequence's last 8 tokens once
+            row.append(hst)
+        groups.append(row)
+    eng.load_sequences(toks, budgets=[64] * B)
+    eng.set_group_history(groups, [[1] * G for _ in range(B)])
+    pol = Policy(window=W, m_min=3, k_fixed=8, k_max=16)
+    for _ in range(3):
+        eng.draft_group(pol)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        eng.draft_group(pol)
+    e1.record()
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 0
+    ms = e0.elapsed_time(e1) / args.steps
+    nbytes = B * G * LH * 4
+    drafted = int(eng.st["row_off"][B].item()) - B
+    print(json.dumps({"probe": "draft", "history_bytes": nbytes, "ms_per_call": round(ms, 4),
+                      "call_gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                      "call_frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                      "drafted_tokens": drafted,
+                      "note": "whole hs_draft_group call (scan + reward walk + row build); the scan kernel alone is in "
+                              "the rocprofv3 kernel trace of this command"}), flush=True)
+    eng.close()
+
+
+def calibration_copy(torch):
+    src = torch.ones(1 << 28, dtype=torch.int32, device="cuda:0")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    log(f"calibration copy: 3 x 1 GiB read + 1 GiB written in {(time.perf_counter() - t3) * 1e3:.2f} ms "
+        f"({3 * 2 * 2 ** 30 / (time.perf_counter() - t3) / 1e9:.0f} GB/s read+write)")
+
+
+def gemm_probe(eng, shape, rows, reps=5):
     import torch
     dev = eng.dev
     g = torch.Generator(device=dev).manual_seed(7)
@@ -334,7 +444,6 @@ def gemm_probe(eng, shape, rows):
         for _ in range(2):
             eng.gemm(epi, a, w, w2, c, m_dev, eng.max_rows, rows)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 5
         e0.record()
         for _ in range(reps):
             eng.gemm(epi, a, w, w2, c, m_dev, eng.max_rows, rows)
@@ -343,6 +452,8 @@ def gemm_probe(eng, shape, rows):
         ms = e0.elapsed_time(e1) / reps
         flops = 2.0 * rows * n * k * (2 if w2 is not None else 1)
         out[name + "_tflops"] = round(flops / (ms * 1e-3) / 1e12, 1)
+        out[name + "_us"] = round(ms * 1e3, 1)
+        out[name + "_weight_gbs"] = round(n * k * 2 * (2 if w2 is not None else 1) / (ms * 1e-3) / 1e9, 1)
         if name != "lm_head":
             layer_flops += flops
             layer_ms += ms
@@ -356,11 +467,14 @@ def gemm_probe(eng, shape, rows):
 
 
 def cpu_baseline(eng, shape, w, rope, toks, hists, pol, first, B, n_layers, weights_to_host):
-    """Time the oracle on the first speculative step of one sequence (the shortest context that drafted)."""
+    """Time the oracle on the first speculative step of one sequence (the shortest context that drafted), and compare
+    the path's results for that sequence with it: logits, emitted tokens, and the residual stream after 1, 2, 4, ...
+    layers (the path re-run on that one sequence with the first l layers of the same weights)."""
     import numpy as np
     import torch
 
     import oracle
+    from paper_2508_18588_amd.runtime import Engine
     if first is None:
         return None
     if "sample_seq" not in first:
@@ -374,37 +488,74 @@ def cpu_baseline(eng, shape, w, rope, toks, hists, pol, first, B, n_layers, weig
     pages = eng.block_table[b, :(L + 15) // 16].long()
     kc = eng.kc.view(n_layers, eng.n_blocks, hkv, 16, h)[:, pages].view(torch.bfloat16)
     vc = eng.vc.view(n_layers, eng.n_blocks, hkv, h, 16)[:, pages].view(torch.bfloat16)
-    k = kc.permute(0, 1, 3, 2, 4).reshape(n_layers, -1, hkv * h)[:, :L].double().cpu().numpy()
-    v = vc.permute(0, 1, 4, 2, 3).reshape(n_layers, -1, hkv * h)[:, :L].double().cpu().numpy()
+    k_ctx = kc.permute(0, 1, 3, 2, 4).reshape(n_layers, -1, hkv * h)[:, :L]       # [layers, L, hkv*h] bf16
+    v_ctx = vc.permute(0, 1, 4, 2, 3).reshape(n_layers, -1, hkv * h)[:, :L]
     seq = oracle.Seq(model, L + 64)
-    seq.load_kv(k, v)
+    seq.load_kv(k_ctx.double().cpu().numpy(), v_ctx.double().cpu().numpy())
     log(f"cpu_baseline: sequence {b} (context {L}), host copy of weights and its K/V in {time.time() - t0:.1f}s")
     x = toks[b]
     t1 = time.time()
     p, m = oracle.suffix_match(hists[b][0], x, pol.window, pol.m_min)
     kk = oracle.draft_len(oracle.k_policy(pol.k_mode, pol.k_fixed, 2, m, pol.k_max), len(hists[b][0]), p, 256)
     tree = oracle.build_tree([hists[b][0][p:p + kk]], x[-1], L)
-    lg = seq.tree_logits(tree["tok"], tree["parent"])
+    # one candidate: the tree is a chain, whose nodes' logits are those of its tokens pushed one after the other
+    # (tree_logits does exactly that on a chain); pushed here one by one to keep each token's residual stream
+    lg, hid = [], []
+    for t in tree["tok"]:
+        l_, h_ = seq.push_traced(int(t))
+        lg.append(l_)
+        hid.append(h_)
+    seq.truncate(L)
+    lg, hid = np.stack(lg), np.stack(hid)                                          # [rows, V], [rows, layers+1, d]
     a, out, path = oracle.accept_greedy(tree["tok"], tree["parent"], [oracle.argmax(r) for r in lg])
     dt = time.time() - t1
     gpu_out = first["out_tok"][b, :first["n_out"][b]].tolist()
-    # parity of this sample: logits within the bf16 tolerance; tokens equal unless a visited row's top-2 margin in
-    # the oracle's logits is below that tolerance (a near-tie, decided by rounding)
-    err = float(np.abs(first["sample_logits"] - lg).max())
+    # parity of this sample: logits, tokens (equal unless a visited row's top-2 margin in the oracle's logits is
+    # within the logit error: a near-tie decided by rounding)
+    derr = np.abs(first["sample_logits"] - lg)
+    err = float(derr.max())
     same = out.tolist() == gpu_out
+    margins = np.sort(lg, axis=1)
+    margins = margins[:, -1] - margins[:, -2]
     margin = None
     if not same:
         n = min(len(gpu_out), len(out))
         j = next((i for i in range(n) if gpu_out[i] != int(out[i])), n - 1)
-        row = np.sort(lg[int(path[j])])
-        margin = float(row[-1] - row[-2])
+        margin = float(margins[int(path[j])])
     log(f"cpu_baseline: {len(tree['tok'])} rows in {dt:.1f}s; oracle emitted {out.tolist()}, GPU emitted {gpu_out}")
+    # ---- error against depth: the same rows through the first l layers only
+    depth = {}
+    rows = [dict(tok=tree["tok"], parent=tree["parent"], pos=tree["pos"])]
+    for l in [d_ for d_ in (1, 2, 4, 8, 16, n_layers) if d_ <= n_layers]:
+        rep = Engine(shape, w, rope, max_batch=1, k_max=len(tree["tok"]) - 1 or 1, c_max=1, max_len=L + 40,
+                     n_layers=l, keep_logits=False)
+        rep.load_sequences([x], budgets=[64])
+        pos = torch.arange(L, device=rep.dev)
+        pg, sl = rep.block_table[0, (pos // 16).long()].long(), (pos % 16).long()
+        rk = rep.kc.view(l, rep.n_blocks, hkv, 16, h)
+        rv = rep.vc.view(l, rep.n_blocks, hkv, h, 16)
+        for li in range(l):
+            rk[li, pg, :, sl, :] = k_ctx[li].view(L, hkv, h).view(torch.int16)
+            rv[li, pg, :, :, sl] = v_ctx[li].view(L, hkv, h).view(torch.int16)
+        mrows = rep.set_rows(rows)
+        rep.verify()
+        torch.cuda.synchronize()
+        xr = rep.debug_tensor(4).view(torch.float32)[:mrows * shape.d_model].view(mrows, -1).double().cpu().numpy()
+        rep.close()
+        want = hid[:, l]
+        depth[str(l)] = round(float(np.sqrt(((xr - want) ** 2).mean() / (want ** 2).mean())), 5)
     return {"value": round(a / dt, 4), "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"1 of {B} sequences (context {L} tokens), 1 speculative step of {len(tree['tok'])} rows "
                       f"through all {n_layers} layers; accepted {a}, committed {a + 1} tokens in {dt:.1f} s",
             "committed_tokens_per_s": round((a + 1) / dt, 4),
-            "parity_sample": {"max_abs_logit_err_vs_gpu": round(err, 5), "same_tokens_as_gpu": same,
-                              "oracle_top2_margin_at_first_difference": margin}}
+            "parity_sample": {"max_abs_logit_err_vs_gpu": round(err, 5),
+                              "rms_logit_err_vs_gpu": round(float(np.sqrt((derr ** 2).mean())), 5),
+                              "logit_std": round(float(lg.std()), 3),
+                              "rows_with_top2_margin_below_max_err": int((margins <= err).sum()),
+                              "rows": int(len(margins)),
+                              "same_tokens_as_gpu": same,
+                              "oracle_top2_margin_at_first_difference": margin,
+                              "residual_rel_rms_err_after_layers": depth}}
 
 
 if __name__ == "__main__":

@@ -64,8 +64,14 @@ enum { HS_ACCEPT_GREEDY = 0, HS_ACCEPT_REJECTION = 1 };    /* hs_accept_args.mod
  * sums carried in fp64, and the KV cache holding fp32 values: hs_kv_cache.k / .v then point at float arrays of the
  * same index layout (twice the bytes), for hs_verify and hs_kv_commit alike.  Only the bf16 weights are rounded, as in
  * the definition of the model, so logits agree with an fp64 evaluation to fp32 rounding (about 1e-5 of a row's
- * largest logit at 28 layers).  Slow; meant for checking the fast path's rounding, not for serving. */
-enum { HS_FLAG_REFERENCE_KERNELS = 1, HS_FLAG_FP32_ACTIVATIONS = 2 };
+ * largest logit at 28 layers).  Slow; meant for checking the fast path's rounding, not for serving.
+ * HS_FLAG_WORKSPACE_LOGITS: hs_verify keeps the fp32 logits of all rows in the workspace when hs_step.logits is
+ * NULL (rejection sampling needs them; so does hs_debug_buffer 3).  Without the flag and without hs_step.logits no
+ * [rows][vocab] array exists at all: the LM head reduces every row to its largest logit per column group in its
+ * epilogue, and hs_accept / hs_accept_commit finish the argmax (greedy acceptance only; hs_step.argmax is then
+ * written by them, not by hs_verify).  With the plain kernels, or a vocabulary so small that the LM head splits its
+ * reduction, the logits are always kept. */
+enum { HS_FLAG_REFERENCE_KERNELS = 1, HS_FLAG_FP32_ACTIVATIONS = 2, HS_FLAG_WORKSPACE_LOGITS = 4 };
 
 /* Pre-norm decoder: RMSNorm, rotary embedding (pairs i, i + head_dim/2), grouped-query attention with scale
  * 1/sqrt(head_dim), SwiGLU feed-forward, untied LM head, no biases. */
@@ -157,7 +163,7 @@ typedef struct hs_policy {
  * The caller prepends the last window-1 prompt tokens to each response so the response start is matchable. */
 typedef struct hs_draft_args {
     int32_t n_cand;           /* 1..c_max */
-    const int32_t* hist;      /* DEVICE */
+    const int32_t* hist;      /* DEVICE, 16-byte aligned (the candidates inside it may start anywhere) */
     const int32_t* hist_off;  /* DEVICE [batch*n_cand + 1] */
     hs_policy policy;
 } hs_draft_args;
@@ -167,7 +173,7 @@ typedef struct hs_draft_args {
  * tokens in front, as for hs_draft), reward[b*n_resp + g] in 0..2^20 the reward that response earned. */
 typedef struct hs_group_draft_args {
     int32_t n_resp;           /* 1..g_max */
-    const int32_t* hist;      /* DEVICE */
+    const int32_t* hist;      /* DEVICE, 16-byte aligned */
     const int32_t* hist_off;  /* DEVICE [batch*n_resp + 1] */
     const int32_t* reward;    /* DEVICE [batch*n_resp] */
     hs_policy policy;
@@ -185,8 +191,9 @@ typedef struct hs_step {
     int32_t* parent;       /* [M] parent node index within the sequence, -1 for the root */
     uint64_t* anc_mask;    /* [M] bit i: node i of the same sequence is this node or an ancestor */
     int32_t* row2seq;      /* [M] */
-    float* logits;         /* optional [max_rows][vocab]; NULL keeps logits in the workspace */
-    int32_t* argmax;       /* [M] lowest index of the largest logit */
+    float* logits;         /* optional [max_rows][vocab]; NULL: no logits are kept unless HS_FLAG_WORKSPACE_LOGITS */
+    int32_t* argmax;       /* [M] lowest index of the largest logit (written by hs_verify, or by hs_accept when no
+                              logits are kept) */
     int32_t* accept_len;   /* [batch] accepted draft tokens a_b */
     int32_t* n_out;        /* [batch] emitted tokens (a_b + 1; 0 for a finished sequence) */
     int32_t* out_tok;      /* [batch][k_max+1] emitted tokens */
@@ -207,13 +214,12 @@ typedef struct hs_accept_args {
 /* Validates the shape and copies the descriptors.  Supported: head_dim 64 or 128, kv_block 16, n_q_heads a
  * multiple of n_kv_heads with at most 8 query heads per KV head, d_model / d_ffn / n_q_heads*head_dim multiples
  * of 64.  The length of the attention's split-KV partitions (256, 512 or 1024 keys) is chosen here from the limits
- * alone; the environment variable HS_ATT_PART (a multiple of 32, 32..1024), read here, overrides it for experiments
- * -- results of contexts created with different partition lengths differ in the last bits. */
+ * alone -- results of contexts created with different limits can differ in the last bits. */
 hs_status hs_create(const hs_model_desc* desc, const hs_weights* weights, const hs_limits* limits, hs_ctx** out);
 void hs_destroy(hs_ctx* ctx);
 const char* hs_last_error(const hs_ctx* ctx);
-/* Changing HS_FLAG_FP32_ACTIVATIONS changes hs_workspace_bytes; a bound workspace that is too small for the new
- * layout is unbound (bind a larger one before the next call).  hs_prefill supports neither flag. */
+/* Changing the flags can change hs_workspace_bytes; a bound workspace that is too small for the new layout is
+ * unbound (bind a larger one before the next call).  hs_prefill supports neither of the plain-kernel flags. */
 hs_status hs_set_flags(hs_ctx* ctx, uint32_t flags);
 
 /* Scratch the kernels need (activations, split-KV partials, logits).  The caller allocates at least
@@ -256,7 +262,8 @@ hs_status hs_draft_group(hs_ctx* ctx, const hs_group_draft_args* args, const hs_
 
 /* One target-model forward pass over all M rows (Sec. 2.2).  Writes every row's K/V into the cache at slot
  * L_b + node index, attends over positions [0, L_b) plus the node's ancestors-or-self, and writes
- * step.argmax and the logits (step.logits, or the workspace if NULL). */
+ * the logits (to step.logits; or to the workspace if that is NULL and HS_FLAG_WORKSPACE_LOGITS is set) and
+ * step.argmax -- or, with neither, only per-row maxima from which hs_accept derives step.argmax (see hs_set_flags). */
 hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* seq, hs_step* step, hs_stream stream);
 
 /* Chunked prefill: recomputes the KV cache of text that already exists -- the prompt, or the prompt plus the tokens a
@@ -289,6 +296,12 @@ hs_status hs_accept(hs_ctx* ctx, const hs_accept_args* args, const hs_seq_state*
  * budget_left -= n_out, tail/tokens/k_state/counters updated. */
 hs_status hs_kv_commit(hs_ctx* ctx, const hs_kv_cache* cache, hs_seq_state* seq, const hs_step* step,
                        const hs_policy* policy, hs_stream stream);
+
+/* hs_accept followed by hs_kv_commit as ONE kernel launch (one workgroup per sequence: argmax of its rows where the
+ * LM head left only row maxima, acceptance walk or rejection sampling, K/V relocation, state update): same arguments,
+ * same results bit for bit as the two calls in a row. */
+hs_status hs_accept_commit(hs_ctx* ctx, const hs_accept_args* args, const hs_kv_cache* cache, hs_seq_state* seq,
+                           hs_step* step, const hs_policy* policy, hs_stream stream);
 
 /* Synchronises `stream`, returns and clears the sticky device error word. */
 hs_status hs_poll_error(hs_ctx* ctx, hs_stream stream, uint32_t* error_bits);
@@ -340,11 +353,15 @@ hs_status hs_debug_philox(const uint32_t* ctr, uint64_t seed, uint32_t* out, int
 
 /* One projection on its own, through the same launcher hs_verify uses (unit-level parity tests and timing):
  * C[m, n] (+)= A[m, k] . W[n, k]^T with bf16 operands, K-contiguous, fp32 accumulation in the shape's fixed K
- * order.  epi 0: C f32 = product; 1: C f32 += product; 2: SwiGLU, C bf16 [m][n] = silu(A.W^T) * (A.W2^T).
+ * order.  epi 0: C f32 = product; 1: C f32 += product; 2: SwiGLU, C bf16 [m][n] = silu(A.W^T) * (A.W2^T); 3: the
+ * row-maximum epilogue of the LM head: nothing of the product is stored, C is uint64 [m_max][g], g =
+ * hs_debug_rowmax_groups(n) column groups, each entry (order-preserving bits of the group's largest value of that
+ * row) << 32 | (0xFFFFFFFF - its column), lowest column on ties -- the maximum over a row's entries names its argmax.
  * All pointers are device memory owned by the caller; m_dev points at the int32 row count (<= m_max, the leading
  * dimension of the partial-sum scratch, itself <= the context's max_rows); n, k must not exceed the widest
  * projection of the context's model (the split execution borrows the context's workspace) and k % 64 == 0.
  * rows_hint steers launch shapes only.  Enqueues on `stream`; HS_ERR_INVALID_ARG on bad arguments. */
+int32_t hs_debug_rowmax_groups(int32_t n);
 hs_status hs_debug_gemm(hs_ctx* ctx, int32_t epi, const void* a, const void* w, const void* w2, void* c,
                         const int32_t* m_dev, int32_t m_max, int32_t n, int32_t k, int32_t rows_hint,
                         hs_stream stream);

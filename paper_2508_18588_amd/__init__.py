@@ -21,7 +21,7 @@ HS_OK, HS_ERR_INVALID_ARG, HS_ERR_CAPACITY, HS_ERR_UNSUPPORTED, HS_ERR_HIP = 0, 
 HS_DEV_BLOCK_TABLE_OVERFLOW, HS_DEV_POSITION_OVERFLOW, HS_DEV_ROW_OVERFLOW = 1, 2, 4
 HS_K_FIXED, HS_K_MATCHLEN, HS_K_AIMD = 0, 1, 2
 HS_ACCEPT_GREEDY, HS_ACCEPT_REJECTION = 0, 1
-HS_FLAG_REFERENCE_KERNELS, HS_FLAG_FP32_ACTIVATIONS = 1, 2
+HS_FLAG_REFERENCE_KERNELS, HS_FLAG_FP32_ACTIVATIONS, HS_FLAG_WORKSPACE_LOGITS = 1, 2, 4
 HS_GATE_WORDS, HS_GATE_TABLE = 32, 8
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -120,7 +120,7 @@ HS_PREFILL_CHUNK_MAX = 1024
 EXPORTS = ("hs_create", "hs_destroy", "hs_last_error", "hs_set_flags", "hs_workspace_bytes", "hs_bind_workspace",
            "hs_draft", "hs_draft_group", "hs_verify", "hs_accept", "hs_kv_commit", "hs_poll_error", "hs_debug_buffer",
            "hs_set_profile", "hs_get_profile", "hs_debug_gemm", "hs_gate_table_build", "hs_prefill", "hs_plan_allocation",
-           "hs_debug_capture", "hs_debug_capture_bytes", "hs_debug_philox", "hs_draft_static")
+           "hs_debug_capture", "hs_debug_capture_bytes", "hs_debug_philox", "hs_draft_static", "hs_accept_commit", "hs_debug_rowmax_groups")
 
 _lib = None
 
@@ -156,6 +156,9 @@ def lib():
         L.hs_accept.argtypes = [vp, C.POINTER(hs_accept_args), C.POINTER(hs_seq_state), C.POINTER(hs_step), vp]
         L.hs_kv_commit.argtypes = [vp, C.POINTER(hs_kv_cache), C.POINTER(hs_seq_state), C.POINTER(hs_step),
                                    C.POINTER(hs_policy), vp]
+        L.hs_debug_rowmax_groups.argtypes = [C.c_int32]
+        L.hs_accept_commit.argtypes = [vp, C.POINTER(hs_accept_args), C.POINTER(hs_kv_cache), C.POINTER(hs_seq_state),
+                                       C.POINTER(hs_step), C.POINTER(hs_policy), vp]
         L.hs_poll_error.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
         L.hs_debug_buffer.argtypes = [vp, C.c_int32, C.POINTER(vp), C.POINTER(C.c_size_t)]
         L.hs_debug_capture_bytes.argtypes = [vp]
@@ -239,6 +242,12 @@ def hs_kv_commit(ctx, cache: hs_kv_cache, seq: hs_seq_state, step: hs_step, poli
     _check(ctx, lib().hs_kv_commit(ctx, C.byref(cache), C.byref(seq), C.byref(step), C.byref(policy), stream))
 
 
+def hs_accept_commit(ctx, args: hs_accept_args, cache: hs_kv_cache, seq: hs_seq_state, step: hs_step,
+                     policy: hs_policy, stream=None):
+    _check(ctx, lib().hs_accept_commit(ctx, C.byref(args), C.byref(cache), C.byref(seq), C.byref(step),
+                                       C.byref(policy), stream))
+
+
 def hs_poll_error(ctx, stream=None) -> int:
     bits = C.c_uint32()
     _check(ctx, lib().hs_poll_error(ctx, stream, C.byref(bits)))
@@ -272,6 +281,10 @@ def hs_set_profile(ctx, level: int):
 def hs_debug_gemm(ctx, epi: int, a: int, w: int, w2: int, c: int, m_dev: int, m_max: int, n: int, k: int,
                   rows_hint: int, stream):
     _check(ctx, lib().hs_debug_gemm(ctx, epi, a, w, w2 or None, c, m_dev, m_max, n, k, rows_hint, stream))
+
+
+def hs_debug_rowmax_groups(n: int) -> int:
+    return lib().hs_debug_rowmax_groups(n)
 
 
 def hs_gate_table_build(ms, rows, k_bar: float, b_max: int):

@@ -31,16 +31,11 @@ __device__ inline double uniform01(uint64_t seed, uint64_t seq_id, uint32_t posi
     return (double)(o[0] >> 8) * (1.0 / 16777216.0);
 }
 
-__global__ __launch_bounds__(64) void accept_greedy_kernel(int batch, const int32_t* __restrict__ row_off,
-                                                            const int32_t* __restrict__ tok,
-                                                            const int32_t* __restrict__ parent,
-                                                            const int32_t* __restrict__ argmax, int k_stride,
-                                                            int32_t* __restrict__ accept_len, int32_t* __restrict__ n_out,
-                                                            int32_t* __restrict__ out_tok, int32_t* __restrict__ path_row) {
-    int b = blockIdx.x * 64 + threadIdx.x;
-    if (b >= batch) return;
-    int r0 = row_off[b], nn = row_off[b + 1] - r0;
-    if (nn <= 0) { accept_len[b] = 0; n_out[b] = 0; return; }
+// Greedy walk of one sequence's tree (one thread): follow the child whose token is the current node's argmax.
+__device__ inline void accept_greedy_walk(int b, int r0, int nn, const int32_t* __restrict__ tok,
+                                          const int32_t* __restrict__ parent, const int32_t* __restrict__ argmax,
+                                          int k_stride, int32_t* __restrict__ accept_len, int32_t* __restrict__ n_out,
+                                          int32_t* __restrict__ out_tok, int32_t* __restrict__ path_row) {
     int cur = 0, a = 0;
     path_row[(size_t)b * k_stride] = 0;
     for (;;) {
@@ -79,9 +74,10 @@ __device__ inline float block_max_f32(float v, float* red) {
     return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
-// One workgroup per sequence.  Probabilities are evaluated in fp64 from the fp32 logits.
-__global__ __launch_bounds__(256) void accept_rejection_kernel(
-    int batch, int vocab, const int32_t* __restrict__ row_off, const int32_t* __restrict__ tok,
+// Rejection sampling of one sequence by its workgroup (nn > 0).  Probabilities are evaluated in fp64 from the fp32
+// logits.
+__device__ inline void accept_rejection_seq(
+    int b, int r0, int nn, int vocab, const int32_t* __restrict__ tok,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ pos, const float* __restrict__ logits,
     const uint64_t* __restrict__ seq_id, double inv_temp, uint64_t seed, int k_stride,
     int32_t* __restrict__ accept_len, int32_t* __restrict__ n_out, int32_t* __restrict__ out_tok,
@@ -91,12 +87,7 @@ __global__ __launch_bounds__(256) void accept_rejection_kernel(
     __shared__ double chunk_sum[256];
     __shared__ int s_next, s_nrej, s_rej[8], s_chunk, s_pick;
     __shared__ double s_before, s_target;
-    const int b = blockIdx.x, tid = threadIdx.x;
-    const int r0 = row_off[b], nn = row_off[b + 1] - r0;
-    if (nn <= 0) {
-        if (tid == 0) { accept_len[b] = 0; n_out[b] = 0; }
-        return;
-    }
+    const int tid = threadIdx.x;
     const uint64_t sid = seq_id[b];
     int cur = 0, a = 0;
     if (tid == 0) path_row[(size_t)b * k_stride] = 0;
@@ -193,18 +184,18 @@ __global__ __launch_bounds__(256) void accept_rejection_kernel(
     }
 }
 
-// One workgroup per sequence: relocate accepted tree nodes' K/V to consecutive slots, then advance the state.
-// CT = cache element type (bf16 bits, or float in the fp32-activation mode).
+// Commit of one sequence by its workgroup: relocate accepted tree nodes' K/V to consecutive slots, then advance the
+// state.  CT = cache element type (bf16 bits, or float in the fp32-activation mode).
 template <typename CT>
-__global__ __launch_bounds__(256) void commit_kernel(
-    int batch, int n_layers, int hkv, int hd, int n_blocks, CT* __restrict__ kc, CT* __restrict__ vc,
+__device__ inline void commit_seq(
+    int b, int n_layers, int hkv, int hd, int n_blocks, CT* __restrict__ kc, CT* __restrict__ vc,
     const int32_t* __restrict__ block_table, int max_blocks, int32_t* __restrict__ seq_len,
     int32_t* __restrict__ tail, int32_t* __restrict__ tail_len, int w_max, int32_t* __restrict__ k_state,
     int32_t* __restrict__ budget_left, int32_t* __restrict__ tokens, int tokens_stride,
     unsigned long long* __restrict__ counters, const int32_t* __restrict__ row_off,
     const int32_t* __restrict__ parent, const int32_t* __restrict__ accept_len, const int32_t* __restrict__ n_out,
-    const int32_t* __restrict__ out_tok, const int32_t* __restrict__ path_row, int k_stride, hs_policy pol) {
-    const int b = blockIdx.x, tid = threadIdx.x;
+    const int32_t* __restrict__ out_tok, const int32_t* __restrict__ path_row, int k_stride, const hs_policy& pol) {
+    const int tid = threadIdx.x;
     const int r0 = row_off[b], nn = row_off[b + 1] - r0;
     const int no = n_out[b];
     if (nn <= 0 || no <= 0) return;
@@ -266,6 +257,77 @@ __global__ __launch_bounds__(256) void commit_kernel(
     }
 }
 
+// Acceptance and commit of one step in ONE launch, one workgroup per sequence (either half can be switched off: the
+// two entry points that run them separately use the same kernel).
+//   1. With `keys` (the LM head ran with its row-maximum epilogue and no logits exist): every row's argmax = the
+//      largest of its n_keys per-column-group keys, one wavefront per row; written to argmax[].
+//   2. Acceptance: greedy walk (thread 0) or rejection sampling (the workgroup).
+//   3. Commit.
+struct accept_commit_args {
+    int batch, vocab, k_stride, mode, do_accept, do_commit;
+    const int32_t *row_off, *tok, *parent, *pos;
+    const float* logits;
+    const unsigned long long* keys;
+    int n_keys;
+    int32_t* argmax;
+    const uint64_t* seq_id;
+    double inv_temp;
+    uint64_t seed;
+    int32_t *accept_len, *n_out, *out_tok, *path_row;
+    // commit
+    int n_layers, hkv, hd, n_blocks, max_blocks, w_max, tokens_stride;
+    void *kc, *vc;
+    const int32_t* block_table;
+    int32_t *seq_len, *tail, *tail_len, *k_state, *budget_left, *tokens;
+    unsigned long long* counters;
+    hs_policy pol;
+};
+
+template <typename CT>
+__global__ __launch_bounds__(256) void accept_commit_kernel(accept_commit_args p) {
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int r0 = p.row_off[b], nn = p.row_off[b + 1] - r0;
+    if (p.do_accept) {
+        if (nn <= 0) {
+            if (tid == 0) { p.accept_len[b] = 0; p.n_out[b] = 0; }
+        } else {
+            if (p.keys) {
+                const int lane = tid & 63, wave = tid >> 6;
+                for (int r = wave; r < nn; r += 4) {
+                    const unsigned long long* kr = p.keys + (size_t)(r0 + r) * p.n_keys;
+                    unsigned long long best = 0ull;
+                    for (int g = lane; g < p.n_keys; g += 64) {
+                        const unsigned long long k = kr[g];
+                        if (k > best) best = k;
+                    }
+#pragma unroll
+                    for (int o = 32; o > 0; o >>= 1) {
+                        const unsigned lo = __shfl_xor((unsigned)best, o), hi = __shfl_xor((unsigned)(best >> 32), o);
+                        const unsigned long long other = ((unsigned long long)hi << 32) | lo;
+                        if (other > best) best = other;
+                    }
+                    if (lane == 0) p.argmax[r0 + r] = (int32_t)(0xFFFFFFFFu - (unsigned)best);
+                }
+                __syncthreads();   // the walk reads argmax[] written by the other wavefronts
+            }
+            if (p.mode == HS_ACCEPT_GREEDY) {
+                if (tid == 0)
+                    accept_greedy_walk(b, r0, nn, p.tok, p.parent, p.argmax, p.k_stride, p.accept_len, p.n_out,
+                                       p.out_tok, p.path_row);
+            } else {
+                accept_rejection_seq(b, r0, nn, p.vocab, p.tok, p.parent, p.pos, p.logits, p.seq_id, p.inv_temp,
+                                     p.seed, p.k_stride, p.accept_len, p.n_out, p.out_tok, p.path_row);
+            }
+        }
+        __syncthreads();           // the commit reads what thread 0 wrote
+    }
+    if (p.do_commit)
+        commit_seq<CT>(b, p.n_layers, p.hkv, p.hd, p.n_blocks, (CT*)p.kc, (CT*)p.vc, p.block_table, p.max_blocks,
+                       p.seq_len, p.tail, p.tail_len, p.w_max, p.k_state, p.budget_left, p.tokens, p.tokens_stride,
+                       p.counters, p.row_off, p.parent, p.accept_len, p.n_out, p.out_tok, p.path_row, p.k_stride,
+                       p.pol);
+}
+
 // The generator on its own: counter i -> its four output words (for bit-exact comparison with another
 // implementation on many counters).
 __global__ __launch_bounds__(256) void philox_debug_kernel(const uint32_t* __restrict__ ctr, uint32_t k0, uint32_t k1,
@@ -288,33 +350,41 @@ extern "C" hs_status hs_debug_philox(const uint32_t* ctr, uint64_t seed, uint32_
     return hipGetLastError() == hipSuccess ? HS_OK : HS_ERR_HIP;
 }
 
-void hs_launch_accept(const hs_ctx* ctx, const hs_accept_args* args, const hs_seq_state* seq, hs_step* step,
-                      const float* logits, hipStream_t st) {
-    const int ks = ctx->lim.k_max + 1;
-    if (args->mode == HS_ACCEPT_GREEDY) {
-        hipLaunchKernelGGL(accept_greedy_kernel, dim3((seq->batch + 63) / 64), dim3(64), 0, st, seq->batch,
-                           step->row_off, step->tok, step->parent, step->argmax, ks, step->accept_len, step->n_out,
-                           step->out_tok, step->path_row);
-    } else {
-        hipLaunchKernelGGL(accept_rejection_kernel, dim3(seq->batch), dim3(256), 0, st, seq->batch, ctx->desc.vocab,
-                           step->row_off, step->tok, step->parent, step->pos, logits, seq->seq_id,
-                           1.0 / (double)args->temperature, args->seed, ks, step->accept_len, step->n_out,
-                           step->out_tok, step->path_row);
-    }
-}
-
-void hs_launch_commit(const hs_ctx* ctx, const hs_kv_cache* cache, hs_seq_state* seq, const hs_step* step,
-                      const hs_policy* policy, hipStream_t st) {
+void hs_launch_accept_commit(const hs_ctx* ctx, const hs_accept_args* args, const hs_kv_cache* cache,
+                             const hs_seq_state* seq, const hs_step* step, const float* logits,
+                             const unsigned long long* keys, int n_keys, const hs_policy* policy, hipStream_t st) {
     const hs_model_desc& d = ctx->desc;
-#define HS_COMMIT_ARGS(CT)                                                                                       \
-    seq->batch, d.n_layers, d.n_kv_heads, d.head_dim, cache->n_blocks, (CT*)cache->k, (CT*)cache->v,             \
-        seq->block_table, ctx->lim.max_blocks_per_seq, seq->seq_len, seq->tail, seq->tail_len, ctx->lim.w_max,   \
-        seq->k_state, seq->budget_left, seq->tokens, seq->tokens_stride, (unsigned long long*)seq->counters,     \
-        step->row_off, step->parent, step->accept_len, step->n_out, step->out_tok, step->path_row,               \
-        ctx->lim.k_max + 1, *policy
+    accept_commit_args p = {};
+    p.batch = seq->batch;
+    p.vocab = d.vocab;
+    p.k_stride = ctx->lim.k_max + 1;
+    p.do_accept = args != nullptr;
+    p.do_commit = policy != nullptr;
+    p.row_off = step->row_off; p.tok = step->tok; p.parent = step->parent; p.pos = step->pos;
+    p.logits = logits;
+    p.keys = keys;
+    p.n_keys = n_keys;
+    p.argmax = step->argmax;
+    p.seq_id = seq->seq_id;
+    if (args) {
+        p.mode = args->mode;
+        p.inv_temp = args->mode == HS_ACCEPT_REJECTION ? 1.0 / (double)args->temperature : 1.0;
+        p.seed = args->seed;
+    }
+    p.accept_len = step->accept_len; p.n_out = step->n_out; p.out_tok = step->out_tok; p.path_row = step->path_row;
+    if (policy) {
+        p.n_layers = d.n_layers; p.hkv = d.n_kv_heads; p.hd = d.head_dim;
+        p.n_blocks = cache->n_blocks; p.max_blocks = ctx->lim.max_blocks_per_seq;
+        p.w_max = ctx->lim.w_max; p.tokens_stride = seq->tokens_stride;
+        p.kc = cache->k; p.vc = cache->v;
+        p.block_table = seq->block_table;
+        p.seq_len = seq->seq_len; p.tail = seq->tail; p.tail_len = seq->tail_len; p.k_state = seq->k_state;
+        p.budget_left = seq->budget_left; p.tokens = seq->tokens;
+        p.counters = (unsigned long long*)seq->counters;
+        p.pol = *policy;
+    }
     if (hs_fp32_activations(ctx))
-        hipLaunchKernelGGL(commit_kernel<float>, dim3(seq->batch), dim3(256), 0, st, HS_COMMIT_ARGS(float));
+        hipLaunchKernelGGL(accept_commit_kernel<float>, dim3(seq->batch), dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL(commit_kernel<bf16_t>, dim3(seq->batch), dim3(256), 0, st, HS_COMMIT_ARGS(bf16_t));
-#undef HS_COMMIT_ARGS
+        hipLaunchKernelGGL(accept_commit_kernel<bf16_t>, dim3(seq->batch), dim3(256), 0, st, p);
 }

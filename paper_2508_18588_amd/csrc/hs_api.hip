@@ -39,7 +39,9 @@ void layout_workspace(hs_ctx* ctx) {
     w.act = take(M * (size_t)d.d_ffn * ab);
     w.part_o = take(M * d.n_q_heads * (size_t)ctx->max_parts * d.head_dim * 2);   // fp16
     w.part_ml = take(M * d.n_q_heads * (size_t)ctx->max_parts * 2 * 4);
-    w.logits = take(M * (size_t)d.vocab * 4);
+    w.logits_bytes = hs_logits_in_workspace(ctx) ? M * (size_t)d.vocab * 4 : 0;
+    w.logits = take(w.logits_bytes);
+    w.rowmax = take(M * (size_t)hs_gemm_rowmax_groups(d.vocab) * 8);
     w.draft_best = take((size_t)l.max_batch * std::max(l.c_max, l.g_max) * ctx->max_segs * 8);
     // (the LM head splits K only when the vocabulary is small; it then writes partial sums like the others)
     const int lm_chunks = hs_gemm_chunks(d.vocab, d.d_model);
@@ -174,10 +176,6 @@ hs_status hs_create(const hs_model_desc* desc, const hs_weights* w, const hs_lim
             }
         }
     }
-    if (const char* e = std::getenv("HS_ATT_PART")) {
-        int v = std::atoi(e);
-        if (v >= 32 && v <= 1024 && v % 32 == 0) ctx->att_part = v;
-    }
     const long long max_keys = (long long)l.max_blocks_per_seq * 16;
     ctx->max_parts = (int)((max_keys + ctx->att_part - 1) / ctx->att_part);
     ctx->max_segs = (l.max_pos + 32 + HS_DRAFT_SEG - 1) / HS_DRAFT_SEG;
@@ -203,9 +201,9 @@ const char* hs_last_error(const hs_ctx* ctx) { return ctx ? ctx->err.c_str() : "
 
 hs_status hs_set_flags(hs_ctx* ctx, uint32_t flags) {
     if (!ctx) return HS_ERR_INVALID_ARG;
-    if (flags & ~(uint32_t)(HS_FLAG_REFERENCE_KERNELS | HS_FLAG_FP32_ACTIVATIONS))
+    if (flags & ~(uint32_t)(HS_FLAG_REFERENCE_KERNELS | HS_FLAG_FP32_ACTIVATIONS | HS_FLAG_WORKSPACE_LOGITS))
         return fail(ctx, HS_ERR_INVALID_ARG, "unknown flag");
-    const bool relayout = ((flags ^ ctx->flags) & HS_FLAG_FP32_ACTIVATIONS) != 0;
+    const bool relayout = flags != ctx->flags;   // activation width, and whether the logits live in the workspace
     ctx->flags = flags;
     if (relayout) {
         layout_workspace(ctx);
@@ -232,6 +230,7 @@ hs_status hs_draft(hs_ctx* ctx, const hs_draft_args* args, const hs_seq_state* s
     if (!ctx) return HS_ERR_INVALID_ARG;
     if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
     if (!args || !args->hist || !args->hist_off) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft: null history");
+    if (((uintptr_t)args->hist & 15u) != 0) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft: hist must be 16-byte aligned");
     if (args->n_cand < 1 || args->n_cand > ctx->lim.c_max) return fail(ctx, HS_ERR_CAPACITY, "hs_draft: n_cand");
     if (!policy_ok(ctx, &args->policy)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft: policy out of range");
     if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft: sequence state");
@@ -246,6 +245,8 @@ hs_status hs_draft_static(hs_ctx* ctx, const hs_draft_args* args, const hs_seq_s
                           hs_stream stream) {
     if (!ctx) return HS_ERR_INVALID_ARG;
     if (!args || !args->hist || !args->hist_off) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_static: null history");
+    if (((uintptr_t)args->hist & 15u) != 0)
+        return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_static: hist must be 16-byte aligned");
     if (args->n_cand < 1 || args->n_cand > ctx->lim.c_max) return fail(ctx, HS_ERR_CAPACITY, "hs_draft_static: n_cand");
     if (!policy_ok(ctx, &args->policy)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_static: policy out of range");
     if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_static: sequence state");
@@ -270,6 +271,8 @@ hs_status hs_draft_group(hs_ctx* ctx, const hs_group_draft_args* args, const hs_
     if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
     if (!args || !args->hist || !args->hist_off || !args->reward)
         return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_group: null history or rewards");
+    if (((uintptr_t)args->hist & 15u) != 0)
+        return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_group: hist must be 16-byte aligned");
     if (args->n_resp < 1 || args->n_resp > ctx->lim.g_max) return fail(ctx, HS_ERR_CAPACITY, "hs_draft_group: n_resp");
     if (!policy_ok(ctx, &args->policy)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_group: policy out of range");
     if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_draft_group: sequence state");
@@ -296,6 +299,7 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
     void* q = ctx->ws + ctx->lay.q;
     void* attn = ctx->ws + ctx->lay.attn;
     void* act = ctx->ws + ctx->lay.act;
+    const bool head_fused = hs_head_fused(ctx, step);
     float* logits = step->logits ? step->logits : (float*)(ctx->ws + ctx->lay.logits);
     const int qh = d.n_q_heads * d.head_dim;
     const int nqkv = (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim;
@@ -359,12 +363,22 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
     pr.begin(3);
     hs_launch_rmsnorm(ctx, x, ctx->norm_f, xn, m_dev, pend, st);
     pr.end();
-    pr.begin(2);
-    hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->lm_head, nullptr, logits, m_dev, m_max, d.vocab, d.d_model, hint, st);
-    pr.end();
-    pr.begin(3);
-    hs_launch_argmax(ctx, logits, step->argmax, m_dev, st);
-    pr.end();
+    if (head_fused) {
+        // no [rows][vocab] array: the LM head leaves one (largest value, column) key per row and column group,
+        // hs_accept / hs_accept_commit take the maximum over a row's keys
+        pr.begin(2);
+        hs_launch_gemm(ctx, HS_EPI_ROWMAX, xn, ctx->lm_head, nullptr, ctx->ws + ctx->lay.rowmax, m_dev, m_max, d.vocab,
+                       d.d_model, hint, st);
+        pr.end();
+    } else {
+        pr.begin(2);
+        hs_launch_gemm(ctx, HS_EPI_STORE_F32, xn, ctx->lm_head, nullptr, logits, m_dev, m_max, d.vocab, d.d_model, hint,
+                       st);
+        pr.end();
+        pr.begin(3);
+        hs_launch_argmax(ctx, logits, step->argmax, m_dev, st);
+        pr.end();
+    }
     if (ctx->profile) {
         (void)hipEventRecord(ctx->ev[whole_slot + 1], st);
         ctx->ev_last = whole_slot + 1;
@@ -424,33 +438,65 @@ hs_status hs_prefill(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* 
     return HS_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+// Shared by hs_accept, hs_kv_commit and hs_accept_commit: args == nullptr skips acceptance, policy == nullptr the commit.
+hs_status accept_commit(hs_ctx* ctx, const char* who, const hs_accept_args* args, const hs_kv_cache* cache,
+                        const hs_seq_state* seq, const hs_step* step, const hs_policy* policy, hs_stream stream) {
+    const float* logits = nullptr;
+    const unsigned long long* keys = nullptr;
+    if (args) {
+        if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
+        if (args->mode != HS_ACCEPT_GREEDY && args->mode != HS_ACCEPT_REJECTION)
+            return fail(ctx, HS_ERR_INVALID_ARG, "acceptance mode");
+        if (args->mode == HS_ACCEPT_REJECTION && !(args->temperature > 0.f))
+            return fail(ctx, HS_ERR_INVALID_ARG, "temperature must be positive");
+        if (hs_head_fused(ctx, step)) {
+            if (args->mode == HS_ACCEPT_REJECTION)
+                return fail(ctx, HS_ERR_INVALID_ARG,
+                            "rejection sampling needs the logits: pass hs_step.logits or set HS_FLAG_WORKSPACE_LOGITS");
+            keys = (const unsigned long long*)(ctx->ws + ctx->lay.rowmax);
+        } else {
+            logits = step->logits ? step->logits : (const float*)(ctx->ws + ctx->lay.logits);
+        }
+    }
+    if (policy) {
+        if (!cache_ok(cache)) return fail(ctx, HS_ERR_INVALID_ARG, "cache");
+        if (!policy_ok(ctx, policy)) return fail(ctx, HS_ERR_INVALID_ARG, "policy out of range");
+    }
+    if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "sequence state");
+    if (!step_ok(step)) return fail(ctx, HS_ERR_INVALID_ARG, "step arrays");
+    (void)hipGetLastError();
+    hs_launch_accept_commit(ctx, args, cache, seq, step, logits, keys, hs_gemm_rowmax_groups(ctx->desc.vocab), policy,
+                            (hipStream_t)stream);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, who, e);
+    return HS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 hs_status hs_accept(hs_ctx* ctx, const hs_accept_args* args, const hs_seq_state* seq, hs_step* step, hs_stream stream) {
     if (!ctx) return HS_ERR_INVALID_ARG;
-    if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
-    if (!args || (args->mode != HS_ACCEPT_GREEDY && args->mode != HS_ACCEPT_REJECTION))
-        return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept: mode");
-    if (args->mode == HS_ACCEPT_REJECTION && !(args->temperature > 0.f))
-        return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept: temperature must be positive");
-    if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept: sequence state");
-    if (!step_ok(step)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept: step arrays");
-    const float* logits = step->logits ? step->logits : (const float*)(ctx->ws + ctx->lay.logits);
-    (void)hipGetLastError();
-    hs_launch_accept(ctx, args, seq, step, logits, (hipStream_t)stream);
-    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_accept", e);
-    return HS_OK;
+    if (!args) return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept: arguments");
+    return accept_commit(ctx, "hs_accept", args, nullptr, seq, step, nullptr, stream);
 }
 
 hs_status hs_kv_commit(hs_ctx* ctx, const hs_kv_cache* cache, hs_seq_state* seq, const hs_step* step,
                        const hs_policy* policy, hs_stream stream) {
     if (!ctx) return HS_ERR_INVALID_ARG;
-    if (!cache_ok(cache)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: cache");
-    if (!seq_ok(ctx, seq)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: sequence state");
-    if (!step_ok(step)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: step arrays");
-    if (!policy_ok(ctx, policy)) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: policy out of range");
-    (void)hipGetLastError();
-    hs_launch_commit(ctx, cache, seq, step, policy, (hipStream_t)stream);
-    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_kv_commit", e);
-    return HS_OK;
+    if (!policy) return fail(ctx, HS_ERR_INVALID_ARG, "hs_kv_commit: policy");
+    return accept_commit(ctx, "hs_kv_commit", nullptr, cache, seq, step, policy, stream);
+}
+
+hs_status hs_accept_commit(hs_ctx* ctx, const hs_accept_args* args, const hs_kv_cache* cache, hs_seq_state* seq,
+                           hs_step* step, const hs_policy* policy, hs_stream stream) {
+    if (!ctx) return HS_ERR_INVALID_ARG;
+    if (!args || !policy) return fail(ctx, HS_ERR_INVALID_ARG, "hs_accept_commit: arguments");
+    return accept_commit(ctx, "hs_accept_commit", args, cache, seq, step, policy, stream);
 }
 
 hs_status hs_poll_error(hs_ctx* ctx, hs_stream stream, uint32_t* error_bits) {
@@ -486,7 +532,9 @@ hs_status hs_debug_buffer(const hs_ctx* ctx, int32_t which, void** dev_ptr, size
         case 0: *dev_ptr = ctx->ws + ctx->lay.xn; *bytes = M * d.d_model * ab; break;
         case 1: *dev_ptr = ctx->ws + ctx->lay.q; *bytes = M * qh * ab; break;
         case 2: *dev_ptr = ctx->ws + ctx->lay.attn; *bytes = M * qh * ab; break;
-        case 3: *dev_ptr = ctx->ws + ctx->lay.logits; *bytes = M * (size_t)d.vocab * 4; break;
+        case 3:
+            if (ctx->lay.logits_bytes == 0) return HS_ERR_INVALID_ARG;   // no logits kept: see HS_FLAG_WORKSPACE_LOGITS
+            *dev_ptr = ctx->ws + ctx->lay.logits; *bytes = ctx->lay.logits_bytes; break;
         case 4: *dev_ptr = ctx->ws + ctx->lay.x; *bytes = M * d.d_model * 4; break;
         case 5: *dev_ptr = ctx->ws + ctx->lay.act; *bytes = M * (size_t)d.d_ffn * ab; break;
         default: return HS_ERR_INVALID_ARG;
@@ -573,7 +621,7 @@ hs_status hs_debug_gemm(hs_ctx* ctx, int32_t epi, const void* a, const void* w, 
                         hs_stream stream) {
     if (!ctx) return HS_ERR_INVALID_ARG;
     if (!ctx->ws) return fail(ctx, HS_ERR_CAPACITY, "no workspace bound");
-    if (epi < HS_EPI_STORE_F32 || epi > HS_EPI_SWIGLU_BF16 || !a || !w || !c || !m_dev ||
+    if (epi < HS_EPI_STORE_F32 || epi > HS_EPI_ROWMAX || !a || !w || !c || !m_dev ||
         (epi == HS_EPI_SWIGLU_BF16 && !w2))
         return fail(ctx, HS_ERR_INVALID_ARG, "hs_debug_gemm: arguments");
     const hs_model_desc& d = ctx->desc;
@@ -584,7 +632,7 @@ hs_status hs_debug_gemm(hs_ctx* ctx, int32_t epi, const void* a, const void* w, 
     if (m_max < 1 || m_max > ctx->lim.max_rows || n < 1 || n > n_lim || k < 64 || k > k_lim || k % 64 != 0)
         return fail(ctx, HS_ERR_INVALID_ARG, "hs_debug_gemm: shape outside the context's model");
     // the split execution writes chunks * m_max * n floats of partial sums
-    const int chunks = epi == HS_EPI_SWIGLU_BF16 ? 1 : hs_gemm_chunks(n, k);
+    const int chunks = (epi == HS_EPI_SWIGLU_BF16 || epi == HS_EPI_ROWMAX) ? 1 : hs_gemm_chunks(n, k);
     if (chunks > 1 && (size_t)chunks * m_max * n * 4 > ctx->lay.gemm_part_bytes)
         return fail(ctx, HS_ERR_CAPACITY, "hs_debug_gemm: partial-sum scratch too small for this shape");
     (void)hipGetLastError();
@@ -593,6 +641,8 @@ hs_status hs_debug_gemm(hs_ctx* ctx, int32_t epi, const void* a, const void* w, 
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail_hip(ctx, "hs_debug_gemm", e);
     return HS_OK;
 }
+
+int32_t hs_debug_rowmax_groups(int32_t n) { return n > 0 ? hs_gemm_rowmax_groups(n) : 0; }
 
 hs_status hs_set_profile(hs_ctx* ctx, int32_t enabled) {
     if (!ctx) return HS_ERR_INVALID_ARG;

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void draft_scan_kernel(const int32_t* __restri
                                                           const int32_t* __restrict__ budget_left, int w_max,
                                                           int window, int m_min, int max_segs,
                                                           unsigned long long* __restrict__ best) {
-    __shared__ int32_t sh[HS_DRAFT_SEG + 32];
+    __shared__ __attribute__((aligned(16))) int32_t sh[HS_DRAFT_SEG + 32 + 8];
     __shared__ int32_t pat[32];
     __shared__ unsigned long long red[4];
     const int seg = blockIdx.x, bc = blockIdx.y, b = bc / n_cand;
@@ -46,16 +46,29 @@ __global__ __launch_bounds__(256) void draft_scan_kernel(const int32_t* __restri
     }
     // pattern, newest token first: pat[i] = i-th token from the end
     if (tid < n_pat) pat[tid] = tail[(size_t)b * w_max + (w_max - 1 - tid)];
-    // tokens hist[base .. p_hi) are needed: base = p_lo - window (clamped)
+    // tokens hist[base .. p_hi) are needed: base = p_lo - window (clamped).  They are staged with 16-byte loads
+    // from the 16-byte boundary at or below the first token: LDS entry `shift` + i holds hist[off + base + i].
+    // (Tokens in front of that boundary belong to this or the previous history: in bounds, never compared.  A
+    // vector that would reach past this history's end is loaded token by token.)
     const int base = max(0, p_lo - window);
     const int count = p_hi - base;
-    for (int i = tid; i < count; i += 256) sh[i] = hist[off + base + i];
+    const int g0 = off + base, a0 = g0 & ~3, shift = g0 - a0, g_end = off + lh;
+    const int4* src4 = reinterpret_cast<const int4*>(hist + a0);
+    for (int v = tid; 4 * v < shift + count; v += 256) {
+        if (a0 + 4 * v + 4 <= g_end) {
+            *reinterpret_cast<int4*>(&sh[4 * v]) = src4[v];
+        } else {
+            for (int e = 0; e < 4; e++)
+                if (a0 + 4 * v + e < g_end) sh[4 * v + e] = hist[a0 + 4 * v + e];
+        }
+    }
     __syncthreads();
     unsigned long long k = 0ull;
+    const int32_t* shb = sh + shift - base;          // shb[i] = hist[off + i]
     for (int p = p_lo + tid; p <= p_hi; p += 256) {
         int lim = min(n_pat, p);
         int m = 0;
-        while (m < lim && sh[p - 1 - m - base] == pat[m]) m++;
+        while (m < lim && shb[p - 1 - m] == pat[m]) m++;
         if (m >= m_min) {
             unsigned long long cand = ((unsigned long long)m << 32) | (0xFFFFFFFFu - (unsigned)p);
             if (cand > k) k = cand;

@@ -162,7 +162,7 @@ void launch(const hs_ctx* ctx, const void* a_any, const bf16_t* w, const bf16_t*
     }
     const bf16_t* a = (const bf16_t*)a_any;
     const int nk = k / BK;
-    int chunks = (EPI == HS_EPI_SWIGLU_BF16) ? 1 : hs_gemm_chunks(n, k);
+    int chunks = (EPI == HS_EPI_SWIGLU_BF16 || EPI == HS_EPI_ROWMAX) ? 1 : hs_gemm_chunks(n, k);
     const int tpc = (nk + chunks - 1) / chunks;
     chunks = (nk + tpc - 1) / tpc;  // no empty chunk
     float* part = reinterpret_cast<float*>(ctx->ws + ctx->lay.gemm_part);
@@ -204,6 +204,9 @@ void hs_launch_gemm(const hs_ctx* ctx, int epi, const void* a, const bf16_t* w, 
             break;
         case HS_EPI_ADD_F32:
             launch<HS_EPI_ADD_F32>(ctx, a, w, w2, c, m_dev, m_max, n, k, rows_hint, st, pending);
+            break;
+        case HS_EPI_ROWMAX:
+            launch<HS_EPI_ROWMAX>(ctx, a, w, w2, c, m_dev, m_max, n, k, rows_hint, st, pending);
             break;
         default:
             launch<HS_EPI_SWIGLU_BF16>(ctx, a, w, w2, c, m_dev, m_max, n, k, rows_hint, st, pending);

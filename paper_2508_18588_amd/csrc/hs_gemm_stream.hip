@@ -54,7 +54,7 @@ struct stream_args {
     const unsigned char* wb[2];  // weight matrices (gate, up) or (W, W)
     void* Cout;
     float* part;
-    int M, m_max, N, K, n0, m0, kt0, kt1, chunk;
+    int M, m_max, N, K, n0, m0, kt0, kt1, chunk, group, n_groups;
     int w_once;  // the launch reads every weight byte once (one row pass): non-temporal weight loads
 };
 
@@ -335,6 +335,30 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
                         }
                     }
                 }
+            } else if (EPI == HS_EPI_ROWMAX) {
+                // Each row's largest value among this workgroup's columns, as a key that orders by value and then by
+                // lower column: first over the lane's NU columns, then over the 32 lanes that hold the row.
+                unsigned long long* keys = reinterpret_cast<unsigned long long*>(p.Cout);
+#pragma unroll
+                for (int e = 0; e < 16; e++) {
+                    unsigned long long key = 0ull;
+#pragma unroll
+                    for (int ni = 0; ni < NU; ni++) {
+                        const int col = p.n0 + 32 * ni + lc;
+                        unsigned u = __float_as_uint(acc[mi][ni][e]);
+                        u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+                        const unsigned long long k2 = ((unsigned long long)u << 32) | (0xFFFFFFFFu - (unsigned)col);
+                        if (col < p.N && k2 > key) key = k2;
+                    }
+#pragma unroll
+                    for (int o = 16; o > 0; o >>= 1) {
+                        const unsigned lo = __shfl_xor((unsigned)key, o), hi = __shfl_xor((unsigned)(key >> 32), o);
+                        const unsigned long long other = ((unsigned long long)hi << 32) | lo;
+                        if (other > key) key = other;
+                    }
+                    const int row = row0 + 8 * (e >> 2) + (e & 3);
+                    if (lc == 0 && row < p.M) keys[(size_t)row * p.n_groups + p.group] = key;
+                }
             } else {
                 float* C = PARTIAL ? p.part + (size_t)p.chunk * p.m_max * p.N : reinterpret_cast<float*>(p.Cout);
                 // A row tile that lies wholly below M (all but the last one of a pass) is stored without row checks,
@@ -424,6 +448,8 @@ __global__ __launch_bounds__(256) void hs_gemm_stream(const bf16_t* __restrict__
     }
     if (group >= n_groups) return;
     p.n0 = group * NCOLS;
+    p.group = group;
+    p.n_groups = n_groups;
     p.chunk = chunk;
     p.w_once = n_pass == 1;
     const int nk = K / BK;
@@ -521,6 +547,11 @@ void launch_stream_shape(const bf16_t* a, const bf16_t* w, const bf16_t* w2, voi
 
 }  // namespace
 
+int hs_gemm_rowmax_groups(int n) {
+    const int nu = choose_units((n + 31) / 32, 1);
+    return (n + 32 * nu - 1) / (32 * nu);
+}
+
 void hs_launch_gemm_stream(int epi, const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, float* part,
                            const int32_t* m_dev, int m_max, int n, int k, int chunks, int tpc, int rows_hint,
                            hipStream_t st) {
@@ -530,6 +561,8 @@ void hs_launch_gemm_stream(int epi, const bf16_t* a, const bf16_t* w, const bf16
     } else if (chunks > 1) {
         // partial sums: the ordered reduce applies the epilogue
         launch_stream_shape<HS_EPI_STORE_F32, true>(HS_ARGS);
+    } else if (epi == HS_EPI_ROWMAX) {
+        launch_stream_shape<HS_EPI_ROWMAX, false>(HS_ARGS);
     } else if (epi == HS_EPI_ADD_F32) {
         launch_stream_shape<HS_EPI_ADD_F32, false>(HS_ARGS);
     } else {

@@ -18,7 +18,7 @@ constexpr int HS_DRAFT_SEG = 4096;
 constexpr int HS_MAX_NODES = 64;  // ancestor masks are 64-bit
 
 struct hs_workspace_layout {
-    size_t x, xn, qkv, q, attn, act, part_o, part_ml, logits, draft_best, gemm_part, gemm_part_bytes, err, pf_len, att_work, att_list, total;
+    size_t x, xn, qkv, q, attn, act, part_o, part_ml, logits, logits_bytes, rowmax, draft_best, gemm_part, gemm_part_bytes, err, pf_len, att_work, att_list, total;
 };
 
 struct hs_ctx {
@@ -66,13 +66,27 @@ static inline bool hs_fp32_activations(const hs_ctx* ctx) { return (ctx->flags &
 static inline bool hs_plain_kernels(const hs_ctx* ctx) {
     return (ctx->flags & (HS_FLAG_REFERENCE_KERNELS | HS_FLAG_FP32_ACTIVATIONS)) != 0;
 }
+int hs_gemm_chunks(int n, int k);
+// Must the logits exist as an [rows][vocab] array?  Yes if the caller asks for them (a destination in the step, or
+// HS_FLAG_WORKSPACE_LOGITS), with the plain kernels, and when the LM head splits K (a small vocabulary).  Otherwise the
+// LM head reduces every row to its argmax in its epilogue and hs_accept finishes the reduction.
+static inline bool hs_logits_in_workspace(const hs_ctx* ctx) {
+    return (ctx->flags & HS_FLAG_WORKSPACE_LOGITS) != 0 || hs_plain_kernels(ctx) ||
+           hs_gemm_chunks(ctx->desc.vocab, ctx->desc.d_model) > 1;
+}
+static inline bool hs_head_fused(const hs_ctx* ctx, const hs_step* step) {
+    return !step->logits && !hs_logits_in_workspace(ctx);
+}
 
 // ---- launchers (each enqueues on `st`; shapes have been validated by the caller) ----
 
 // GEMM family: C[M,N] (+)= A[M,K] . W[N,K]^T, A and W bf16, fp32 accumulation in a fixed k order.
 // Activation buffers (a, and c of the SwiGLU epilogue) are bf16, or float in the fp32-activation mode.
 // m_dev points at the row count M on the device; the grid covers m_max rows and tiles beyond M exit.
-enum { HS_EPI_STORE_F32 = 0, HS_EPI_ADD_F32 = 1, HS_EPI_SWIGLU_BF16 = 2 };
+// HS_EPI_ROWMAX (LM head only, unsplit K): nothing of the product is stored; every workgroup reduces its columns of
+// each row to one 64-bit key, (order-preserving bits of the largest value) << 32 | ~column, smallest column on ties,
+// written to c as unsigned long long [m_max][hs_gemm_rowmax_groups(n)] -- the maximum over a row's keys is its argmax.
+enum { HS_EPI_STORE_F32 = 0, HS_EPI_ADD_F32 = 1, HS_EPI_SWIGLU_BF16 = 2, HS_EPI_ROWMAX = 3 };
 // rows_hint (host-side estimate of the live row count) selects the tile height and the split execution
 // (one workgroup per K chunk + an ordered reduce); results are identical whatever it is.
 // pending: if not null and the split execution was chosen, the ordered reduce is NOT launched: *pending receives the
@@ -81,7 +95,7 @@ enum { HS_EPI_STORE_F32 = 0, HS_EPI_ADD_F32 = 1, HS_EPI_SWIGLU_BF16 = 2 };
 void hs_launch_gemm(const hs_ctx* ctx, int epi, const void* a, const bf16_t* w, const bf16_t* w2, void* c,
                     const int32_t* m_dev, int m_max, int n, int k, int rows_hint, hipStream_t st,
                     int* pending = nullptr);
-int hs_gemm_chunks(int n, int k);
+int hs_gemm_rowmax_groups(int n);   // column groups (= keys per row) of an HS_EPI_ROWMAX launch over n columns
 
 void hs_launch_embed(const hs_ctx* ctx, const hs_step* step, int batch, float* x, hipStream_t st);
 // RMSNorm of the residual stream; with pending_chunks > 0 it first adds the pending chunk partials of the
@@ -119,7 +133,8 @@ bool hs_launch_draft_static(const hs_ctx* ctx, const hs_draft_args* args, const 
 uint32_t* hs_draft_static_error_word(hipError_t* why);
 void hs_launch_draft_group(const hs_ctx* ctx, const hs_group_draft_args* args, const hs_seq_state* seq,
                            hs_step* step, hipStream_t st);
-void hs_launch_accept(const hs_ctx* ctx, const hs_accept_args* args, const hs_seq_state* seq, hs_step* step,
-                      const float* logits, hipStream_t st);
-void hs_launch_commit(const hs_ctx* ctx, const hs_kv_cache* cache, hs_seq_state* seq, const hs_step* step,
-                      const hs_policy* policy, hipStream_t st);
+// Acceptance and/or commit of one step in one launch.  args == nullptr: no acceptance; policy == nullptr: no commit.
+// keys != nullptr: the rows' argmax is first reduced from the LM head's row-maximum keys (n_keys per row).
+void hs_launch_accept_commit(const hs_ctx* ctx, const hs_accept_args* args, const hs_kv_cache* cache,
+                             const hs_seq_state* seq, const hs_step* step, const float* logits,
+                             const unsigned long long* keys, int n_keys, const hs_policy* policy, hipStream_t st);

@@ -10,7 +10,7 @@ from dataclasses import dataclass
 import numpy as np
 import torch
 
-from . import (HS_FLAG_FP32_ACTIVATIONS, hs_debug_capture, hs_debug_capture_bytes, HS_ACCEPT_GREEDY, HS_GATE_TABLE, HS_GATE_WORDS, HS_K_FIXED, hs_gate_table_build, hs_accept, hs_accept_args, hs_bind_workspace, hs_create, hs_debug_buffer, hs_debug_gemm,
+from . import (HS_FLAG_WORKSPACE_LOGITS, hs_accept_commit, HS_FLAG_FP32_ACTIVATIONS, hs_debug_capture, hs_debug_capture_bytes, HS_ACCEPT_GREEDY, HS_GATE_TABLE, HS_GATE_WORDS, HS_K_FIXED, hs_gate_table_build, hs_accept, hs_accept_args, hs_bind_workspace, hs_create, hs_debug_buffer, hs_debug_gemm,
                hs_destroy, hs_draft, hs_draft_args, hs_draft_group, hs_group_draft_args, hs_get_profile, hs_kv_cache, hs_kv_commit, hs_limits,
                hs_model_desc, hs_policy, hs_poll_error, hs_prefill, hs_prefill_args, hs_seq_state, hs_set_flags, hs_set_profile, hs_step,
                hs_verify, hs_weights, hs_workspace_bytes)
@@ -50,8 +50,12 @@ class Engine:
 
     def __init__(self, shape, weights: dict, rope, max_batch: int, k_max: int, c_max: int, max_len: int,
                  w_max: int = 32, seq_caps=None, shuffle_pages_seed: int | None = None, n_layers: int | None = None,
-                 keep_logits: bool = True, g_max: int = 0, max_rows: int | None = None, precise: bool = False):
-        """precise: run in the library's fp32-activation mode (plain kernels, float KV cache)."""
+                 keep_logits: bool = True, g_max: int = 0, max_rows: int | None = None, precise: bool = False,
+                 workspace_logits: bool = False):
+        """keep_logits: give every step a [max_rows, vocab] fp32 logits tensor (hs_step.logits); without it (and
+        without workspace_logits, which keeps them inside the library's workspace) no logits array exists and the
+        argmax comes out of the LM head's epilogue.  precise: run in the library's fp32-activation mode (plain
+        kernels, float KV cache)."""
         self.shape = shape
         self.dev = torch.device("cuda:0")
         L = len(weights["wqkv"]) if n_layers is None else n_layers
@@ -100,13 +104,11 @@ class Engine:
         self.g_max = g_max
         lim = hs_limits(max_batch, k_max, c_max, self.max_rows, self.max_blocks, self.max_pos, w_max, g_max)
         self.ctx = hs_create(desc, hw, lim)
-        if precise:
-            hs_set_flags(self.ctx, HS_FLAG_FP32_ACTIVATIONS)   # before the workspace is sized
-        nbytes = hs_workspace_bytes(self.ctx)
-        self.workspace = torch.zeros(nbytes + 256, dtype=torch.uint8, device=self.dev)
-        base = self.workspace.data_ptr()
-        self._ws_ptr = (base + 255) // 256 * 256
-        hs_bind_workspace(self.ctx, self._ws_ptr, nbytes)
+        self.flags = (HS_FLAG_FP32_ACTIVATIONS if precise else 0) | (HS_FLAG_WORKSPACE_LOGITS if workspace_logits else 0)
+        if self.flags:
+            hs_set_flags(self.ctx, self.flags)   # before the workspace is sized
+        self.workspace = None
+        self._bind_workspace()
         # ---- sequence state and step arrays
         i32 = dict(dtype=torch.int32, device=self.dev)
         B, M = max_batch, self.max_rows
@@ -133,6 +135,14 @@ class Engine:
         self.hist_off = None
         self.n_cand = 1
         self._structs()
+
+    def _bind_workspace(self):
+        """(Re)allocate the workspace if the current flags need more than is bound."""
+        nbytes = hs_workspace_bytes(self.ctx)
+        if self.workspace is None or self.workspace.numel() < nbytes + 256:
+            self.workspace = torch.zeros(nbytes + 256, dtype=torch.uint8, device=self.dev)
+            self._ws_ptr = (self.workspace.data_ptr() + 255) // 256 * 256
+        hs_bind_workspace(self.ctx, self._ws_ptr, nbytes)
 
     def _structs(self):
         s = self.st
@@ -231,8 +241,7 @@ class Engine:
     def step_group(self, policy: Policy, mode: int = HS_ACCEPT_GREEDY, temperature: float = 1.0, seed: int = 0):
         self.draft_group(policy)
         self.verify()
-        self.accept(mode, temperature, seed)
-        self.commit(policy)
+        self.accept_commit(policy, mode, temperature, seed)
 
     def set_rows_hint(self, rows: int):
         """Tell the library how many rows to expect (a launch-shape hint; results do not depend on it)."""
@@ -248,11 +257,14 @@ class Engine:
     def commit(self, policy: Policy):
         hs_kv_commit(self.ctx, self.c_cache, self.c_seq, self.c_step, policy.c(), self.stream())
 
+    def accept_commit(self, policy: Policy, mode: int = HS_ACCEPT_GREEDY, temperature: float = 1.0, seed: int = 0):
+        hs_accept_commit(self.ctx, hs_accept_args(mode, temperature, seed), self.c_cache, self.c_seq, self.c_step,
+                         policy.c(), self.stream())
+
     def step(self, policy: Policy, mode: int = HS_ACCEPT_GREEDY, temperature: float = 1.0, seed: int = 0):
         self.draft(policy)
         self.verify()
-        self.accept(mode, temperature, seed)
-        self.commit(policy)
+        self.accept_commit(policy, mode, temperature, seed)
 
     def set_gate(self, table, probe_every: int = 0):
         """Switch on throughput-aware speculation control with this 17-entry table (None: off).  The monitor starts
@@ -277,7 +289,11 @@ class Engine:
         return hs_poll_error(self.ctx, self.stream())
 
     def set_flags(self, flags: int):
+        """Replace the context's flags (a larger workspace is bound if the new layout needs one)."""
+        torch.cuda.synchronize()
+        self.flags = flags
         hs_set_flags(self.ctx, flags)
+        self._bind_workspace()
 
     def set_profile(self, level: int):
         """0 off, 1 events around the attention kernel and the whole call, 2 around every launch of hs_verify."""

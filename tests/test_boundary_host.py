@@ -20,7 +20,7 @@ def lib():
 
 def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "histospec.h")).read()
-    declared = set(re.findall(r"^\s*(?:hs_status|void|size_t|const char\*)\s+(hs_[a-z_]+)\(", header, re.M))
+    declared = set(re.findall(r"^\s*(?:hs_status|void|size_t|int32_t|const char\*)\s+(hs_[a-z_]+)\(", header, re.M))
     assert declared == set(hs.EXPORTS), declared ^ set(hs.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None

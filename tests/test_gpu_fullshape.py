@@ -105,7 +105,19 @@ def _full_batch_sampled_kernel_parity(cfg, B, ctx, k_max, picks, proj_rows):
     want = xn[rs] @ wsub.T
     np.testing.assert_allclose(lg[np.ix_(rs, cs)], want, atol=2e-4, rtol=1e-4)
     # argmax of every row is the first maximum of its logits
-    assert np_of(eng.st["argmax"])[:m].tolist() == lg.argmax(1).tolist()
+    arg = np_of(eng.st["argmax"])[:m].copy()
+    assert arg.tolist() == lg.argmax(1).tolist()
+    # the same launch without a logits array: the LM head's row-maximum epilogue + the reduction inside the acceptance
+    # kernel must name the same token for every row
+    eng.logits = None
+    eng._structs()
+    eng.c_step.rows_hint = m
+    eng.st["argmax"].fill_(-1)
+    eng.verify()
+    eng.accept()
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 0
+    assert (np_of(eng.st["argmax"])[:m] == arg).all()
     eng.close()
     print(f"config {cfg} full batch: rows", m, "attention max abs err", worst)
 
