@@ -273,6 +273,9 @@ def main():
     kv_tok_bytes = 2 * shape.n_kv_heads * shape.head_dim * 2          # K+V bytes per token and layer
     mean_keys = float((len0 + len1).sum()) / 2 - B + rows_per_step     # sum_b (L_b + nodes_b), mid-region
     att_bytes = mean_keys * kv_tok_bytes + rows_per_step * shape.n_q_heads * shape.head_dim * 2 * 2
+    # flops of the same launch: 4 h per (query row, head, visible key); with many rows per sequence the launch is no
+    # longer bound by HBM alone (flop per KV byte = query heads per KV head x nodes)
+    att_flops = 4.0 * shape.head_dim * shape.n_q_heads * float(((len0 + len1) / 2.0 - 1.0).sum()) * rows_per_step / B
     extras = {}
     if prof is not None:
         ms, n = prof
@@ -282,7 +285,10 @@ def main():
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                     "traffic": ATTN_TRAFFIC_BYTES_PER_LAUNCH if cfg == 3 else None,
                     "algorithmic_bytes_per_launch": int(att_bytes),
-                    "avg_launch_ms": round(att_ms, 4), "launches": n[0]}
+                    "avg_launch_ms": round(att_ms, 4), "launches": n[0],
+                    "flops_per_launch": int(att_flops),
+                    "flop_per_byte": round(att_flops / att_bytes, 1),
+                    "frac_of_bf16_mfma_peak": round(att_flops / (att_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
         msa, _ = prof_all
         gemm_flops = 2.0 * rows_all * (shape.dense_params - shape.d_model * shape.vocab) * n_layers / shape.n_layers
         gemm_ms = msa[1] / prof_all_steps

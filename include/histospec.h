@@ -262,6 +262,10 @@ hs_status hs_draft_group(hs_ctx* ctx, const hs_group_draft_args* args, const hs_
 
 /* One target-model forward pass over all M rows (Sec. 2.2).  Writes every row's K/V into the cache at slot
  * L_b + node index, attends over positions [0, L_b) plus the node's ancestors-or-self, and writes
+ * (Numerical range: the attention runs split over key partitions whose partial outputs -- each a convex combination
+ * of cached V rows -- are held in fp16 before they are merged in fp32.  Results are therefore as described only
+ * while |V| < 65504 for every cached value, and V components below 6e-5 in magnitude lose bits (below 6e-8 they
+ * vanish) in that intermediate; activations of a normalised decoder are far inside this range.)
  * the logits (to step.logits; or to the workspace if that is NULL and HS_FLAG_WORKSPACE_LOGITS is set) and
  * step.argmax -- or, with neither, only per-row maxima from which hs_accept derives step.argmax (see hs_set_flags). */
 hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* seq, hs_step* step, hs_stream stream);

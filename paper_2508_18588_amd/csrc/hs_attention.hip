@@ -20,8 +20,11 @@
 //     the other through a private LDS slice and never synchronises with the others.  With a single 32-row tile the
 //     softmax arithmetic of a partition is one instruction stream; giving every wavefront its own stream keeps all
 //     four SIMDs of a compute unit busy and the KV stream bandwidth-bound.
-//   R > 32: one WORKGROUP per unit; K/V tiles of 64 or 128 keys are staged once and shared, the row tiles are
-//     dealt to the 4 wavefronts.
+//   R > 32: one WORKGROUP per unit; K/V tiles of 128 keys are staged once and shared, the (up to four) 32-row tiles
+//     are dealt to the 4 wavefronts.  A sequence with more than 128 query rows per KV head is cut into units of
+//     four row tiles, each of which walks the partition's keys on its own: holding two row tiles per wavefront
+//     instead would cost every workgroup unit of the launch half the resident workgroups (registers), which was
+//     measured to be far dearer than reading the K/V of the few very long drafts twice.
 // Both run the identical per-row arithmetic on the identical partitions: masked keys contribute exact zeros and
 // partitions merge in index order, so a row's result is bit-identical whether it is verified next to other draft
 // rows or decoded alone.
@@ -201,7 +204,7 @@ struct AttnArgs {
 
 // A unit of work: one partition of one (sequence, KV head), with the sequence's row range and cached length, as the
 // list kernel wrote it (two int4 per unit).
-struct AttnUnit { int b, j, part, r0, nn, L; };
+struct AttnUnit { int b, j, part, r0, nn, L, rt0; };   // rt0: first 32-row tile this unit covers (workgroup units)
 
 __device__ inline AttnUnit attn_unit_from(const int4& p, const int4& q) {
     AttnUnit u;
@@ -211,6 +214,7 @@ __device__ inline AttnUnit attn_unit_from(const int4& p, const int4& q) {
     u.r0 = __builtin_amdgcn_readfirstlane(p.w);
     u.nn = __builtin_amdgcn_readfirstlane(q.x);
     u.L = __builtin_amdgcn_readfirstlane(q.y);
+    u.rt0 = __builtin_amdgcn_readfirstlane(q.z);
     return u;
 }
 
@@ -332,8 +336,9 @@ __device__ inline void attn_wave_stream(const AttnArgs& a, const int4* __restric
 #undef HS_W_FETCH
 }
 
-// One partition of one (sequence, KV head) by the WORKGROUP (R > 32): 64- or 128-key tiles shared by the four wavefronts,
-// 32-row tiles dealt to them round-robin (up to RTW each), one tile of register prefetch.
+// One partition of one (sequence, KV head) by the WORKGROUP (R > 32): 128-key tiles shared by the four wavefronts, the
+// unit's 32-row tiles (un.rt0 .. un.rt0 + 3) dealt to them round-robin, one tile of register prefetch.  (RTW row
+// tiles per wavefront; the launcher instantiates RTW = 1.)
 template <int HD, int RTW>
 __device__ inline void attn_unit_wg(const AttnArgs& a, const AttnUnit& un, bf16_t* sK, bf16_t* sV, int tid) {
     constexpr int KS = HD + 8, VS = 20, NKS = HD / 16, NDT = HD / 32;
@@ -365,7 +370,7 @@ __device__ inline void attn_unit_wg(const AttnArgs& a, const AttnUnit& un, bf16_
     bool rt_on[RTW];
 #pragma unroll
     for (int t = 0; t < RTW; t++) {
-        int rt = slot + 4 * t;
+        int rt = un.rt0 + slot + 4 * t;
         rt_on[t] = rt < nrt;
         load_query_tile<HD>(a.q, a.anc_mask, r0, rt_on[t] ? rt : 0, rt_on[t] ? R : 0, G, a.hq, j, half, l32, qf[t], anc[t]);
 #pragma unroll
@@ -422,22 +427,22 @@ __device__ inline void attn_unit_wg(const AttnArgs& a, const AttnUnit& un, bf16_
 #pragma unroll
     for (int t = 0; t < RTW; t++) {
         if (!rt_on[t]) continue;
-        store_partial<HD>(o[t], m_run[t], l_run[t], a.part_o, a.part_ml, r0, slot + 4 * t, R, G, a.hq, j, a.max_parts,
-                          part, half, l32);
+        store_partial<HD>(o[t], m_run[t], l_run[t], a.part_o, a.part_ml, r0, un.rt0 + slot + 4 * t, R, G, a.hq, j,
+                          a.max_parts, part, half, l32);
     }
 }
 
 // The units of one step, built once per hs_verify call (the same for every layer): a unit = one partition of one
 // (sequence, KV head), in (sequence, partition, head) order.  List A: units of sequences with more than 32 query rows
 // per KV head (taken by whole workgroups), list B: the others (taken by single wavefronts).  An entry is two int4:
-// (sequence, head, partition, first row) (rows, cached length, 0, 0).  work[0] = |A|, work[1] = |B|, work[2 + l] = the
+// (sequence, head, partition, first row) (rows, cached length, first row tile, 0).  work[0] = |A|, work[1] = |B|, work[2 + l] = the
 // counter through which layer l's launch hands out list A (zeroed here).
 __global__ __launch_bounds__(256) void attn_worklist_kernel(const int32_t* __restrict__ seq_len,
                                                              const int32_t* __restrict__ row_off, int batch,
                                                              int part_keys, int G, int hkv, int max_parts, int n_layers,
                                                              int32_t* __restrict__ work, int4* __restrict__ list_a,
                                                              int4* __restrict__ list_b) {
-    __shared__ int s_nu[256], s_off[256], s_r0[256], s_nn[256], s_len[256];
+    __shared__ int s_nu[256], s_off[256], s_r0[256], s_nn[256], s_len[256], s_grp[256];
     __shared__ int sw_a[4], sw_b[4];
     __shared__ int carry_a, carry_b;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -446,7 +451,7 @@ __global__ __launch_bounds__(256) void attn_worklist_kernel(const int32_t* __res
     __syncthreads();
     for (int b0 = 0; b0 < batch; b0 += 256) {
         const int b = b0 + tid;
-        int nu = 0, r0 = 0, nn = 0, L = 0;
+        int nu = 0, r0 = 0, nn = 0, L = 0, ngrp = 1;
         bool is_a = false;
         if (b < batch) {
             r0 = row_off[b];
@@ -454,8 +459,11 @@ __global__ __launch_bounds__(256) void attn_worklist_kernel(const int32_t* __res
             L = seq_len[b] - 1;
             if (nn > 0 && L >= 0) {
                 const int nparts = min(max_parts, (L + nn + part_keys - 1) / part_keys);
-                nu = nparts * hkv;
                 is_a = nn * G > 32;
+                // a workgroup covers four 32-row tiles: a sequence with more query rows per KV head than that gets
+                // one unit per group of four tiles (each walks the partition's keys on its own)
+                if (is_a) ngrp = (nn * G + 127) / 128;
+                nu = nparts * hkv * ngrp;
             }
         }
         int ia = is_a ? nu : 0, ib = is_a ? 0 : nu;
@@ -475,16 +483,18 @@ __global__ __launch_bounds__(256) void attn_worklist_kernel(const int32_t* __res
         s_r0[tid] = r0;
         s_nn[tid] = nn;
         s_len[tid] = L;
+        s_grp[tid] = ngrp;
         __syncthreads();
         if (tid == 255) { carry_a = ba + ia; carry_b = bb + ib; }
         const int nb = min(256, batch - b0);
         for (int i = 0; i < nb; i++) {
             const int n = s_nu[i];
             int4* dst = (n < 0 ? list_a : list_b) + 2 * (size_t)s_off[i];
-            const int cnt = n < 0 ? -n : n;
+            const int cnt = n < 0 ? -n : n, grp = s_grp[i];
             for (int u = tid; u < cnt; u += 256) {
-                dst[2 * u] = make_int4(b0 + i, u % hkv, u / hkv, s_r0[i]);
-                dst[2 * u + 1] = make_int4(s_nn[i], s_len[i], 0, 0);
+                const int v = u / grp;        // (partition, head); the tile groups of one (partition, head) are neighbours
+                dst[2 * u] = make_int4(b0 + i, v % hkv, v / hkv, s_r0[i]);
+                dst[2 * u + 1] = make_int4(s_nn[i], s_len[i], 4 * (u - v * grp), 0);
             }
         }
         __syncthreads();
@@ -828,20 +838,16 @@ void hs_launch_attention(const hs_ctx* ctx, int layer, const hs_kv_cache* cache,
         return;
     }
     const bf16_t* q = (const bf16_t*)q_any;
-    int G = d.n_q_heads / d.n_kv_heads;
-    int r_max = G * (1 + ctx->lim.c_max * ctx->lim.k_max);
-    bool two = r_max > 128;
-    if (d.head_dim == 128) {
-        if (two) launch_mfma<128, 2>(ctx, layer, layer_off, cache, seq, step, q, st);
-        else launch_mfma<128, 1>(ctx, layer, layer_off, cache, seq, step, q, st);
-    } else {
-        if (two) launch_mfma<64, 2>(ctx, layer, layer_off, cache, seq, step, q, st);
-        else launch_mfma<64, 1>(ctx, layer, layer_off, cache, seq, step, q, st);
-    }
+    // one row tile per wavefront, two workgroups per compute unit, whatever the longest draft: a sequence with more
+    // than 128 query rows per KV head comes as several units (see attn_worklist_kernel)
+    if (d.head_dim == 128) launch_mfma<128, 1>(ctx, layer, layer_off, cache, seq, step, q, st);
+    else launch_mfma<64, 1>(ctx, layer, layer_off, cache, seq, step, q, st);
 }
 
 size_t hs_attention_max_units(const hs_ctx* ctx) {
-    return (size_t)ctx->lim.max_batch * ctx->max_parts * ctx->desc.n_kv_heads;
+    // a sequence's (partition, KV head) pairs, times the groups of four row tiles its query rows can fill
+    const int r_max = (ctx->desc.n_q_heads / ctx->desc.n_kv_heads) * (1 + ctx->lim.c_max * ctx->lim.k_max);
+    return (size_t)ctx->lim.max_batch * ctx->max_parts * ctx->desc.n_kv_heads * ((r_max + 127) / 128);
 }
 
 void hs_launch_attention_worklist(const hs_ctx* ctx, const hs_seq_state* seq, const hs_step* step, hipStream_t st) {
