@@ -492,7 +492,9 @@ __global__ __launch_bounds__(256) void attn_worklist_kernel(const int32_t* __res
             int4* dst = (n < 0 ? list_a : list_b) + 2 * (size_t)s_off[i];
             const int cnt = n < 0 ? -n : n, grp = s_grp[i];
             for (int u = tid; u < cnt; u += 256) {
-                const int v = u / grp;        // (partition, head); the tile groups of one (partition, head) are neighbours
+                // v = (partition, head); the tile groups of one (partition, head) are neighbours (grp is 1 or 2: at
+                // most 256 query rows per KV head)
+                const int v = grp == 1 ? u : (grp == 2 ? (u >> 1) : u / grp);
                 dst[2 * u] = make_int4(b0 + i, v % hkv, v / hkv, s_r0[i]);
                 dst[2 * u + 1] = make_int4(s_nn[i], s_len[i], 4 * (u - v * grp), 0);
             }
