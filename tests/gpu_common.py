@@ -105,3 +105,119 @@ def derived_logit_tol(shape, n_layers):
     sigma = 0.02 * np.sqrt(shape.d_model)
     eps = 2.0 ** -9 / np.sqrt(3.0)
     return float(5.2 * sigma * (4.5 * eps * np.sqrt(n_layers) + eps) * 1.5)
+
+
+# ---------------------------------------------------------------- last-layer projections of a real forward pass
+
+def _rows_f64(t, idx):
+    """Rows `idx` of a device matrix holding bf16 values (torch.bfloat16 or int16 bit patterns) or floats -> fp64."""
+    import torch
+    sub = t[torch.as_tensor(np.asarray(idx, np.int64), device=t.device)]
+    if sub.dtype == torch.int16:
+        sub = sub.view(torch.bfloat16)
+    return sub.double().cpu().numpy()
+
+
+def check_last_layer_projections(eng, cap, m, rows, rng, n_cols=24):
+    """Every projection of the last layer against its definition, C = A . W^T as fp64 dot products of the path's own
+    inputs of that projection (snapshots of hs_debug_capture + hs_debug_buffer), at sampled rows and columns of the
+    launch that just ran: QKV (through the rotation, against the query buffer and the cache rows the step wrote),
+    O and down (as the change of the fp32 residual stream), gate/up with SwiGLU (against the activation buffer).
+    Tolerances: fp32 accumulation over K (2e-5 of the output scale), plus one bf16 rounding where the output is
+    stored as bf16, plus the fp32 rounding of the residual add.  Returns the worst errors per projection."""
+    import torch
+    shape, L = eng.shape, eng.n_layers
+    d, F, hq, hkv, h = shape.d_model, shape.d_ffn, shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    qh, half = hq * h, h // 2
+    rows = np.asarray(sorted(set(int(r) for r in rows if 0 <= r < m)), np.int64)
+    assert not eng.precise, "written for the bf16 layout of the snapshots"
+    view = lambda t, dt, cols: t.view(dt)[:m * cols].view(m, cols)
+    xn1 = _rows_f64(view(cap[0], torch.int16, d), rows)
+    x1 = _rows_f64(view(cap[1], torch.float32, d), rows)
+    xn2 = _rows_f64(view(cap[2], torch.int16, d), rows)
+    x2 = _rows_f64(view(cap[3], torch.float32, d), rows)
+    xf = _rows_f64(view(eng.debug_tensor(4), torch.float32, d), rows)
+    q = _rows_f64(view(eng.debug_tensor(1), torch.int16, qh), rows)
+    att = _rows_f64(view(eng.debug_tensor(2), torch.int16, qh), rows)
+    act = _rows_f64(view(eng.debug_tensor(5), torch.int16, F), rows)
+    W = eng.w
+    l = L - 1
+    pos = np_of(eng.st["pos"])[rows]
+    r2s = np_of(eng.st["row2seq"])[rows]
+    ro = np_of(eng.st["row_off"])
+    rope = np_of(eng.rope).astype(np.float64)
+    worst = {}
+    bf = 2.0 ** -8
+
+    def edge_cols(n, groups):
+        c = set(int(x) for x in rng.integers(0, n, n_cols))
+        for g in groups:
+            c.update(x for x in (g - 1, g, n - g, n - g - 1) if 0 <= x < n)
+        c.update((0, n - 1))
+        return np.asarray(sorted(c), np.int64)
+
+    # ---- QKV: rotated queries (buffer 1) and the K / V rows written into the cache at slot L_b + node
+    heads = sorted(set(int(x) for x in rng.integers(0, hq, 4)) | {0, hq - 1})
+    js = sorted(set(int(x) for x in rng.integers(0, half, 6)) | {0, half - 1})
+    wq = W["wqkv"][l]
+    err = 0.0
+    for hd_ in heads:
+        lo = np.asarray([hd_ * h + j for j in js], np.int64)
+        a = xn1 @ _rows_f64(wq, lo).T
+        b = xn1 @ _rows_f64(wq, lo + half).T
+        c, s = rope[pos][:, js, 0], rope[pos][:, js, 1]
+        for want, got in ((a * c - b * s, q[:, lo]), (b * c + a * s, q[:, lo + half])):
+            tol = bf * np.abs(want) + 2e-5 * (np.abs(want).max() + 1.0)
+            assert (np.abs(got - want) <= tol).all(), ("q", hd_)
+            err = max(err, float(np.abs(got - want).max()))
+    kc = eng.kc.view(L, eng.n_blocks, hkv, 16, h)
+    vc = eng.vc.view(L, eng.n_blocks, hkv, h, 16)
+    bt = np_of(eng.block_table)
+    slots = np_of(eng.seq_len)[r2s] - 1 + (rows - ro[r2s])          # seq_len is still the pre-commit length
+    pages = torch.as_tensor(bt[r2s, slots // 16].astype(np.int64), device="cuda:0")
+    ip = torch.as_tensor((slots % 16).astype(np.int64), device="cuda:0")
+    for jj in sorted({0, hkv - 1}):
+        ar = torch.arange(len(rows), device="cuda:0")
+        kgot = kc[l][pages, jj][ar, ip].view(torch.bfloat16).double().cpu().numpy()        # [rows, h]
+        vgot = vc[l][pages, jj][ar, :, ip].view(torch.bfloat16).double().cpu().numpy()
+        lo = np.asarray([qh + jj * h + j for j in js], np.int64)
+        a = xn1 @ _rows_f64(wq, lo).T
+        b = xn1 @ _rows_f64(wq, lo + half).T
+        c, s = rope[pos][:, js, 0], rope[pos][:, js, 1]
+        jn = np.asarray(js)
+        for want, got in ((a * c - b * s, kgot[:, jn]), (b * c + a * s, kgot[:, jn + half])):
+            tol = bf * np.abs(want) + 2e-5 * (np.abs(want).max() + 1.0)
+            assert (np.abs(got - want) <= tol).all(), ("k", jj)
+            err = max(err, float(np.abs(got - want).max()))
+        vo = np.asarray([qh + hkv * h + jj * h + j for j in js + [j + half for j in js]], np.int64)
+        want = xn1 @ _rows_f64(wq, vo).T
+        got = vgot[:, np.concatenate([jn, jn + half])]
+        tol = bf * np.abs(want) + 2e-5 * (np.abs(want).max() + 1.0)
+        assert (np.abs(got - want) <= tol).all(), ("v", jj)
+        err = max(err, float(np.abs(got - want).max()))
+    worst["qkv"] = err
+    # ---- O projection: residual after it minus residual before it
+    cols = edge_cols(d, (64, 128, 160))
+    want = att @ _rows_f64(W["wo"][l], cols).T
+    got = x2[:, cols] - x1[:, cols]
+    tol = 2e-5 * (np.abs(want).max() + 1.0) + 4e-7 * np.abs(x2[:, cols])
+    assert (np.abs(got - want) <= tol).all(), "o"
+    worst["o"] = float(np.abs(got - want).max())
+    # ---- gate/up + SwiGLU: the bf16 activation
+    cols = edge_cols(F, (16, 64, 80, 160))
+    g_ = xn2 @ _rows_f64(W["wgate"][l], cols).T
+    u_ = xn2 @ _rows_f64(W["wup"][l], cols).T
+    want = g_ / (1.0 + np.exp(-g_)) * u_
+    got = act[:, cols]
+    # one bf16 rounding of the result; the hardware reciprocal and exponential of the epilogue add a few fp32 ulps
+    tol = 1.5 * bf * np.abs(want) + 4e-5 * (np.abs(want).max() + 1.0)
+    assert (np.abs(got - want) <= tol).all(), "gate_up"
+    worst["gate_up"] = float(np.abs(got - want).max())
+    # ---- down projection: final residual minus residual before it
+    cols = edge_cols(d, (64, 128, 160))
+    want = act @ _rows_f64(W["wdown"][l], cols).T
+    got = xf[:, cols] - x2[:, cols]
+    tol = 2e-5 * (np.abs(want).max() + 1.0) + 4e-7 * np.abs(xf[:, cols])
+    assert (np.abs(got - want) <= tol).all(), "down"
+    worst["down"] = float(np.abs(got - want).max())
+    return worst
