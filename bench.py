@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--print-rows", action="store_true", help="diagnostic: log the row count of every timed step")
     ap.add_argument("--reuse-all", action="store_true",
                     help="debug: history = the rollout itself (every draft accepted, rows per step at their maximum)")
+    ap.add_argument("--graph", action="store_true",
+                    help="after the timed (eager) steps, record one whole step into a HIP graph and time the same number "
+                         "of replays: reported as config.graph_replay (the headline value stays the eager region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events (roofline null)")
     ap.add_argument("--gemm-probe", default="",
@@ -262,6 +265,25 @@ def main():
         eng.set_profile(0)
         cb = (eng.counters.cpu().numpy() - ca).tolist()
         rows_all = (cb[0] + cb[1]) / prof_all_steps
+    graph_extra = {}
+    if args.graph and snap is None:
+        # the same steps again, replayed from a graph of one step (state simply continues: same workload statistics)
+        cg0 = eng.counters.cpu().numpy().copy()
+        g = eng.capture_step(pol, mode, temperature, philox_seed)
+        g.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        g_el = time.perf_counter() - tg
+        cg1 = (eng.counters.cpu().numpy() - cg0).tolist()
+        graph_extra = {"graph_replay": {"ms_per_step": round(g_el / args.steps * 1e3, 3),
+                                        "accepted_tokens_per_s": round(cg1[2] * args.steps / (args.steps + 1) / g_el, 1),
+                                        "rows_per_step": round((cg1[0] + cg1[1]) / (args.steps + 1), 1),
+                                        "note": "one whole step (all four calls) recorded into a HIP graph and replayed; "
+                                                "not the headline value"}}
+        assert eng.poll_error() == 0
     seq_steps, drafted, accepted, emitted = (c1 - c0).tolist()
     ms_per_step = elapsed / args.steps * 1e3
     rows_per_step = (drafted + seq_steps) / args.steps
@@ -340,7 +362,7 @@ def main():
                    "median_verify_accept_commit_ms": round(med(ev_vac), 3),
                    "median_draft_us": round(med(ev_draft) * 1e3, 1),
                    "accepted_tokens_per_s_at_median_step": round(accepted / args.steps / (med(ev_all) * 1e-3), 1),
-                   **extras},
+                   **graph_extra, **extras},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     if args.calibrate_copy:

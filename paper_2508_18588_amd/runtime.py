@@ -266,6 +266,20 @@ class Engine:
         self.verify()
         self.accept_commit(policy, mode, temperature, seed)
 
+    def capture_step(self, policy: Policy, mode: int = HS_ACCEPT_GREEDY, temperature: float = 1.0, seed: int = 0):
+        """Record one whole decode iteration (draft, verify, accept + commit) into a HIP graph and return it; every
+        `graph.replay()` then runs one iteration.  Possible because nothing in an iteration depends on host values
+        that change from step to step: the row count and every offset live on the device, launch shapes follow the
+        row hint that was set when the graph was recorded.  Run a few eager steps with the same hint first (kernel
+        attributes are set on a kernel's first launch), and keep profiling off."""
+        g = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            self.draft(policy)
+            self.verify()
+            self.accept_commit(policy, mode, temperature, seed)
+        return g
+
     def set_gate(self, table, probe_every: int = 0):
         """Switch on throughput-aware speculation control with this 17-entry table (None: off).  The monitor starts
         empty and picks the counters up where they stand."""

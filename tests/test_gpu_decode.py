@@ -389,3 +389,48 @@ def test_split_and_serial_gemm_execution_agree_bitwise():
         eng.close()
     for a, b in zip(*results):
         assert (a == b).all()
+
+
+def test_whole_step_replayed_from_a_hip_graph_equals_eager_steps(config1):
+    """One decode iteration (draft, verify, accept + commit) recorded into a HIP graph: the row count lives on the
+    device, so the same graph serves every step.  40 replays, each followed by a synchronisation and eager reads,
+    against an engine that runs the same steps eagerly: rows, argmax, acceptance and emitted tokens of every step, and
+    the final sequence state and cache, are identical."""
+    from paper_2508_18588_amd import HS_K_AIMD
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    shape, w, rope, model, prompts, rollouts = config1
+    pol = Policy(window=8, m_min=3, k_mode=HS_K_AIMD, k_max=8)
+    cands = make_histories(prompts, rollouts, 8, 0.10, 0.02, shape.vocab, seed=91)
+    engs = []
+    for _ in range(2):
+        eng = Engine(shape, w, rope, max_batch=4, k_max=8, c_max=1, max_len=64 + 256, shuffle_pages_seed=8,
+                     keep_logits=False)
+        eng.load_sequences(list(prompts), budgets=[200] * 4)
+        eng.set_history(cands)
+        eng.prefill(list(prompts))
+        eng.set_rows_hint(12)
+        for _ in range(3):
+            eng.step(pol)
+        engs.append(eng)
+    eager, replayed = engs
+    graph = replayed.capture_step(pol)
+    keys = ("row_off", "tok", "parent", "argmax", "accept_len", "n_out", "out_tok", "path_row")
+    emitted = 0
+    for s in range(40):
+        eager.step(pol)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert replayed.poll_error() == 0
+        m = int(eager.st["row_off"][4])
+        for k in keys:
+            a, b = np_of(eager.st[k]), np_of(replayed.st[k])
+            if k in ("tok", "parent", "argmax"):
+                a, b = a[:m], b[:m]
+            assert (a == b).all(), (s, k)
+        emitted += int(np_of(eager.st["n_out"]).sum())
+    for k in ("seq_len", "tail", "tail_len", "k_state", "budget_left", "tokens", "counters"):
+        assert (np_of(getattr(eager, k)) == np_of(getattr(replayed, k))).all(), k
+    assert (np_of(eager.kc) == np_of(replayed.kc)).all() and (np_of(eager.vc) == np_of(replayed.vc)).all()
+    assert emitted > 4 * 40        # drafts were accepted along the way
+    for e in engs:
+        e.close()
