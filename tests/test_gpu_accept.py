@@ -124,10 +124,14 @@ def test_finished_and_empty_sequences(toy):
     eng.close()
 
 
-def test_tree_rejection_sampling_end_to_end(toy):
+@pytest.mark.parametrize("precise", [False, True])
+def test_tree_rejection_sampling_end_to_end(toy, precise):
     """Two history candidates per sequence, tree-mask verify, rejection sampling at a low temperature (so that
     drafts are accepted with a useful probability), tree commit -- in lock-step with the oracle: logits within the
-    tolerance every step; the GPU's decisions equal the oracle's rule applied to the GPU's own logits."""
+    tolerance every step.  Default path: the GPU's decisions equal the oracle's rule applied to the GPU's own logits.
+    fp32-activation mode: the logits agree to 1e-4 relative, and the GPU's decisions equal the oracle's rule applied
+    to the ORACLE's own logits -- the whole stochastic step end to end against an independent computation (a decision
+    may differ only where the oracle reports a uniform within 1e-4 of its threshold)."""
     from paper_2508_18588_amd import HS_ACCEPT_REJECTION
     from paper_2508_18588_amd.runtime import Engine, Policy
     from test_gpu_decode import gpu_ar_rollout, check_cache
@@ -143,13 +147,14 @@ def test_tree_rejection_sampling_end_to_end(toy):
     cands = [[h0[b][0], h1[b][0]] for b in range(4)]
     pol = Policy(window=8, m_min=3, k_fixed=8, k_max=8)
     T, pseed = float(np.float32(0.02)), 0xABCDEF12345
-    eng = Engine(shape, w, rope, max_batch=4, k_max=8, c_max=2, max_len=48 + 96, shuffle_pages_seed=12)
+    eng = Engine(shape, w, rope, max_batch=4, k_max=8, c_max=2, max_len=48 + 96, shuffle_pages_seed=12,
+                 precise=precise)
     sids = [11, 2 ** 40 + 5, 7, 2 ** 62 + 1]
     eng.load_sequences(list(prompts), budgets=[96] * 4, seq_ids=sids)
     eng.set_history(cands)
     eng.prefill(list(prompts))
     ob = OracleBatch(model, list(prompts), [96] * 4, 48 + 96 + 24)
-    accepted = steps = 0
+    accepted = steps = flagged = 0
     while any(b > 0 for b in ob.budget) and steps < 200:
         eng.draft(pol)
         eng.verify()
@@ -169,11 +174,16 @@ def test_tree_rejection_sampling_end_to_end(toy):
             assert st["pos"][sl].tolist() == tree["pos"].tolist()
             want = ob.logits(b, tree)
             assert np.abs(lg[sl] - want).max() <= LOGIT_TOL
+            if precise:
+                assert (np.abs(lg[sl] - want).max(1) <= 1e-4 * np.abs(want).max(1)).all()
             a, out, path, margin = oracle.accept_stochastic(tree["tok"], tree["parent"], tree["pos"],
-                                                            lg[sl].astype(np.float64), T, pseed, sids[b])
+                                                            want if precise else lg[sl].astype(np.float64), T, pseed,
+                                                            sids[b])
             n = st["n_out"][b]
             got = (int(st["accept_len"][b]), st["out_tok"][b, :n].tolist(), st["path_row"][b, :n].tolist())
-            assert got == (a, out.tolist(), path.tolist()) or margin < 1e-9, (b, got, a, out, path, margin)
+            near = 1e-4 if precise else 1e-9
+            flagged += got != (a, out.tolist(), path.tolist())
+            assert got == (a, out.tolist(), path.tolist()) or margin < near, (b, got, a, out, path, margin)
             ob.commit(b, tree, got[0], np.array(got[1]), np.array(got[2]), pol)
             accepted += got[0]
         steps += 1
@@ -185,7 +195,8 @@ def test_tree_rejection_sampling_end_to_end(toy):
     for layer in (0, 1):
         check_cache(eng, ob, layer)
     eng.close()
-    print("tree rejection e2e: steps", steps, "accepted", accepted)
+    print("tree rejection e2e: precise", precise, "steps", steps, "accepted", accepted, "near-threshold", flagged)
+    assert flagged <= 2
     assert accepted > 5   # sampling soon leaves the greedy history; the draft path was still exercised
 
 
