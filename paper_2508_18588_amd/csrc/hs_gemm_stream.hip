@@ -510,6 +510,10 @@ void launch_stream(const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, 
                        m_dev, m_max, n, k, tpc, n_groups, n_pass);
 }
 
+#ifndef HS_WIDE_GROUP_ROWS
+#define HS_WIDE_GROUP_ROWS 352   // measured cross-over at the 7B shape: 33 vs 40 us at 300 rows, 49 vs 37 us at 385
+#endif
+
 // Units per workgroup: the candidate that needs the fewest unit-times to cover the output on 256 compute units.
 int choose_units(int units, int chunks) {
     int best = 4, best_cost = 1 << 30;
@@ -532,7 +536,10 @@ void launch_stream_shape(const bf16_t* a, const bf16_t* w, const bf16_t* w2, voi
     // not pay a second pass over the weights.  Row tiles that do not exist cost nothing in either shape.
     const bool tall = rows_hint > 160;
 #define HS_ARGS a, w, w2, c, part, m_dev, m_max, n, k, chunks, tpc, rows_hint, st
-    if (PARTIAL && chunks > 1 && hs_gemm_narrow_groups(k)) {
+    // The 64-row groups of the short-reduction split-K shapes (QKV, O) pay at a few hundred rows, where they halve the
+    // partial sums; with many row passes every group re-reads the whole activation slab of its pass, and wider groups
+    // (half as many re-reads) win.  The K chunking -- the reduction order -- is the shape's either way.
+    if (PARTIAL && chunks > 1 && hs_gemm_narrow_groups(k) && rows_hint < HS_WIDE_GROUP_ROWS) {
         if (tall) launch_stream<EPI, PARTIAL, 2, 3, 2, 6>(HS_ARGS);
         else launch_stream<EPI, PARTIAL, 2, 2, 2, 8>(HS_ARGS);
     } else if (nu == 5) {
