@@ -4,7 +4,9 @@
 A "step" is one pass of the whole path -- hs_draft, hs_verify, hs_accept, hs_kv_commit -- over the whole
 in-flight batch.  The default workload is benchmark configuration 3 (7B-shaped decoder, batch 128, contexts
 uniform 2k..16k, 70 % history similarity, draft length set by the match length, greedy acceptance); all inputs
-are synthetic and seeded (see the design doc for the recipe) and resident in HBM before the timed region starts.
+are synthetic and seeded (weights N(0, 0.02) in bf16, random context K/V of the scale a prefill writes, previous-epoch
+text = the path's own greedy continuation mutated token by token and by span edits) and resident in HBM before the
+timed region starts.
 `--config 2`, `--config 4 --reuse R` and `--config 5` run the other benchmark configurations (5 repeats its first
 speculative step, see its workload string).
 

@@ -122,6 +122,56 @@ def test_calls_reject_bad_arguments_without_launching(lib):
     hs.hs_destroy(ctx)
 
 
+def test_flags_change_the_workspace_layout_and_new_entry_points_check_their_arguments(lib):
+    """Host-side behaviour of what sits around the four calls: the fp32-activation and workspace-logits flags change
+    hs_workspace_bytes and drop a binding that no longer fits; rejection sampling without logits is refused before
+    anything is launched; hs_accept_commit, hs_draft_static, hs_debug_capture and hs_debug_philox validate their
+    arguments; the LM head's row-maximum epilogue reports its number of column groups."""
+    desc, w, lim, keep = _good()
+    ctx = hs.hs_create(desc, w, lim)
+    base = hs.hs_workspace_bytes(ctx)
+    hs.hs_bind_workspace(ctx, 0x100000, base)
+    hs.hs_set_flags(ctx, hs.HS_FLAG_WORKSPACE_LOGITS)
+    with_logits = hs.hs_workspace_bytes(ctx)
+    assert with_logits >= base + lim.max_rows * desc.vocab * 4                   # an [rows][vocab] fp32 array appears
+    seq, step, cache = hs.hs_seq_state(), hs.hs_step(), hs.hs_kv_cache()
+    with pytest.raises(hs.HsError) as e:                                          # the old binding was dropped
+        hs.hs_verify(ctx, cache, seq, step)
+    assert e.value.status == hs.HS_ERR_CAPACITY and "workspace" in str(e.value)
+    hs.hs_set_flags(ctx, hs.HS_FLAG_FP32_ACTIVATIONS)                             # plain kernels keep logits too
+    assert hs.hs_workspace_bytes(ctx) > with_logits                               # and activations take 4 bytes
+    hs.hs_set_flags(ctx, 0)
+    assert hs.hs_workspace_bytes(ctx) == base
+    hs.hs_bind_workspace(ctx, 0x100000, 1 << 40)
+    pol = hs.hs_policy(8, 3, hs.HS_K_FIXED, 4, 4, 2, 32, 2)
+    ok_seq = hs.hs_seq_state(4, *([0x1000] * 7), None, 0, None)
+    ok_step = hs.hs_step(*([0x1000] * 9), None, *([0x1000] * 5), 0)              # no logits destination
+    with pytest.raises(hs.HsError) as e:
+        hs.hs_accept(ctx, hs.hs_accept_args(hs.HS_ACCEPT_REJECTION, 1.0, 0), ok_seq, ok_step)
+    assert e.value.status == hs.HS_ERR_INVALID_ARG and "logits" in str(e.value)
+    with pytest.raises(hs.HsError) as e:
+        hs.hs_accept_commit(ctx, hs.hs_accept_args(hs.HS_ACCEPT_REJECTION, 1.0, 0), hs.hs_kv_cache(0x1000, 0x1000, 8),
+                            ok_seq, ok_step, pol)
+    assert "logits" in str(e.value)
+    for call in (lambda: hs.hs_accept_commit(ctx, hs.hs_accept_args(0, 1.0, 0), cache, ok_seq, ok_step, pol),    # null cache
+                 lambda: hs.hs_accept_commit(ctx, hs.hs_accept_args(7, 1.0, 0), hs.hs_kv_cache(0x1000, 0x1000, 8),
+                                             ok_seq, ok_step, pol),                                              # mode
+                 lambda: hs.hs_draft_static(ctx, hs.hs_draft_args(1, 0x1008, 0x1000, pol), ok_seq, ok_step),      # alignment
+                 lambda: hs.hs_draft_static(ctx, hs.hs_draft_args(1, None, 0x1000, pol), ok_seq, ok_step)):
+        with pytest.raises(hs.HsError) as e:
+            call()
+        assert e.value.status == hs.HS_ERR_INVALID_ARG
+    with pytest.raises(hs.HsError) as e:
+        hs.hs_debug_capture(ctx, 0x1000, 16)
+    assert e.value.status == hs.HS_ERR_CAPACITY
+    assert hs.hs_debug_capture_bytes(ctx) == 4 * lim.max_rows * desc.d_model * 4
+    hs.hs_debug_capture(ctx, None, 0)                                             # off again
+    with pytest.raises(hs.HsError):
+        hs.hs_debug_philox(None, 1, 0x1000, 4)
+    assert hs.hs_debug_rowmax_groups(152064) == 951 and hs.hs_debug_rowmax_groups(0) == 0
+    hs.hs_destroy(ctx)
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(hs, "_lib", None)
     monkeypatch.setattr(hs, "LIB_PATH", "/nonexistent/libhistospec.so")
