@@ -235,7 +235,7 @@ def main():
     c0 = eng.counters.cpu().numpy().copy()
     len0 = eng.seq_len.cpu().numpy()[:B].astype(np.int64).copy()
     if not args.no_profile:
-        eng.set_profile(1)      # events around the attention kernel only: the timed steps pay for nothing else
+        eng.set_profile(1)      # events around the attention kernel of every fourth layer only (and the whole call)
     torch.cuda.synchronize()
     t2 = time.perf_counter()
     step_rows = []
@@ -310,6 +310,8 @@ def main():
                     "traffic": ATTN_TRAFFIC_BYTES_PER_LAUNCH if cfg == 3 else None,
                     "algorithmic_bytes_per_launch": int(att_bytes),
                     "avg_launch_ms": round(att_ms, 4), "launches": n[0],
+                    "launches_note": "the attention launch of every fourth layer of every timed step, bracketed by "
+                                     "HIP events on the launching stream (all layers do the same work)",
                     "flops_per_launch": int(att_flops),
                     "flop_per_byte": round(att_flops / att_bytes, 1),
                     "frac_of_bf16_mfma_peak": round(att_flops / (att_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}

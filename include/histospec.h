@@ -86,7 +86,7 @@ typedef struct hs_model_desc {
 typedef struct hs_weights {
     const void* embed;          /* DEVICE bf16 [vocab, d_model] */
     const void* lm_head;        /* DEVICE bf16 [vocab, d_model] */
-    const float* norm_f;        /* DEVICE f32 [d_model] */
+    const float* norm_f;        /* DEVICE f32 [d_model], 16-byte aligned (so are norm1[i], norm2[i]) */
     const void* const* wqkv;    /* bf16 [(n_q_heads + 2 n_kv_heads) head_dim, d_model]: q rows, then k, then v */
     const void* const* wo;      /* bf16 [d_model, n_q_heads head_dim] */
     const void* const* wgate;   /* bf16 [d_ffn, d_model] */
@@ -213,7 +213,8 @@ typedef struct hs_accept_args {
 
 /* Validates the shape and copies the descriptors.  Supported: head_dim 64 or 128, kv_block 16, n_q_heads a
  * multiple of n_kv_heads with at most 8 query heads per KV head, d_model / d_ffn / n_q_heads*head_dim multiples
- * of 64.  The length of the attention's split-KV partitions (256, 512 or 1024 keys) is chosen here from the limits
+ * of 64, d_model at most 16384.  The norm weight vectors must be 16-byte aligned (HS_ERR_INVALID_ARG otherwise).
+ * The length of the attention's split-KV partitions (256, 512 or 1024 keys) is chosen here from the limits
  * alone -- results of contexts created with different limits can differ in the last bits. */
 hs_status hs_create(const hs_model_desc* desc, const hs_weights* weights, const hs_limits* limits, hs_ctx** out);
 void hs_destroy(hs_ctx* ctx);
@@ -371,9 +372,9 @@ hs_status hs_debug_gemm(hs_ctx* ctx, int32_t epi, const void* a, const void* w, 
                         hs_stream stream);
 
 /* Kernel timing with HIP events on the call's stream.  hs_set_profile(ctx, level): 0 off; 1 brackets the attention
- * kernel of every layer and the whole hs_verify call (cheap enough for a timed run); 2 brackets every kernel
- * launch of hs_verify (each pair of events costs a few microseconds of stream time: use it on steps that are not
- * themselves being timed).  hs_get_profile waits for the last profiled call and returns, summed over all hs_verify
+ * kernel of every fourth layer (0, 4, 8, ...: all layers do the same work) and the whole hs_verify call (cheap enough
+ * for a timed run); 2 brackets every kernel launch of hs_verify (each pair of events costs about ten microseconds of
+ * stream time: use it on steps that are not themselves being timed).  hs_get_profile waits for the last profiled call and returns, summed over all hs_verify
  * calls since the previous hs_get_profile / hs_set_profile, total milliseconds and launch counts per class (classes
  * that the level does not bracket report zero):
  * 0 attention kernel, 1 projection GEMMs (QKV, O, gate/up, down), 2 LM-head GEMM, 3 everything else (norms,

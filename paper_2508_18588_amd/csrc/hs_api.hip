@@ -61,11 +61,12 @@ struct Prof {
     hs_ctx* ctx;
     hipStream_t st;
     bool open = false;
-    void begin(int cls) {
+    // level 1 brackets the whole call and the attention kernel of every fourth layer only (`sampled`): an event
+    // record costs about 5 microseconds of stream time on either side of a launch, which a timed run should not pay
+    // around all ~9 launches of each layer
+    void begin(int cls, bool sampled = true) {
         open = false;
-        // level 1 brackets the attention kernel (and the whole call) only: every pair of events costs a few
-        // microseconds of stream time, which a timed run should not pay around all ~15 launches per layer
-        if (!ctx->profile || (ctx->profile == 1 && cls != 0 && cls != 4)) return;
+        if (!ctx->profile || (ctx->profile == 1 && ((cls != 0 && cls != 4) || !sampled))) return;
         open = true;
         if (ctx->ev_used + 2 > (int)ctx->ev.size()) {
             hipEvent_t a, b;
@@ -119,7 +120,7 @@ hs_status hs_create(const hs_model_desc* desc, const hs_weights* w, const hs_lim
         !(d.rms_eps > 0.f))
         return HS_ERR_INVALID_ARG;
     if (d.kv_block != 16 || (d.head_dim != 64 && d.head_dim != 128) || d.n_q_heads % d.n_kv_heads != 0 ||
-        d.n_q_heads / d.n_kv_heads > 8 || d.d_model % 64 != 0 || d.d_ffn % 64 != 0 ||
+        d.n_q_heads / d.n_kv_heads > 8 || d.d_model % 64 != 0 || d.d_model > 16384 || d.d_ffn % 64 != 0 ||
         (d.n_q_heads * d.head_dim) % 64 != 0)
         return HS_ERR_UNSUPPORTED;
     const hs_limits& l = *lim;
@@ -145,6 +146,10 @@ hs_status hs_create(const hs_model_desc* desc, const hs_weights* w, const hs_lim
     for (int i = 0; i < d.n_layers; i++)
         if (!w->wqkv[i] || !w->wo[i] || !w->wgate[i] || !w->wup[i] || !w->wdown[i] || !w->norm1[i] || !w->norm2[i])
             return HS_ERR_INVALID_ARG;
+    // the norm weights are read with 16-byte loads
+    if (((uintptr_t)w->norm_f & 15u) != 0) return HS_ERR_INVALID_ARG;
+    for (int i = 0; i < d.n_layers; i++)
+        if ((((uintptr_t)w->norm1[i] | (uintptr_t)w->norm2[i]) & 15u) != 0) return HS_ERR_INVALID_ARG;
     hs_ctx* ctx = new (std::nothrow) hs_ctx();
     if (!ctx) return HS_ERR_CAPACITY;
     ctx->desc = d;
@@ -336,7 +341,7 @@ hs_status hs_verify(hs_ctx* ctx, const hs_kv_cache* cache, const hs_seq_state* s
         pr.begin(3);
         hs_launch_rope_kv(ctx, l, cache, seq, step, qkv, q, pend, st);
         pr.end();
-        pr.begin(0);
+        pr.begin(0, l % 4 == 0);
         hs_launch_attention(ctx, l, cache, seq, step, q, attn, st);
         pr.end();
         pr.begin(3);

@@ -659,59 +659,63 @@ __global__ __launch_bounds__(256, 1) void attn_prefill_mfma(
 }
 
 // Combine the partitions of one (row, query head) in partition order: one wavefront per (row, head), four per
-// workgroup.  Lane p holds partition p's (max, sum); weights are broadcast from there.
+// workgroup; rows are strided over the grid's x dimension (the row count is only known on the device).  Lane p
+// holds partition p's (max, sum); weights are broadcast from there.
 template <int HD>
 __global__ __launch_bounds__(256) void attn_merge(const _Float16* __restrict__ part_o, const float* __restrict__ part_ml,
                                                    const int32_t* __restrict__ row2seq, const int32_t* __restrict__ row_off,
                                                    const int32_t* __restrict__ seq_len, int batch, int max_parts,
                                                    int part_keys, int hq, bf16_t* __restrict__ out) {
-    const int row = blockIdx.x, head = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-    if (row >= row_off[batch] || head >= hq) return;
-    const int b = row2seq[row];
-    const int total = seq_len[b] - 1 + (row_off[b + 1] - row_off[b]);
-    const int nparts = min(max_parts, (total + part_keys - 1) / part_keys);
-    const size_t prow = ((size_t)row * hq + head) * max_parts;
-    float mg = -INFINITY;
-    for (int p0 = 0; p0 < nparts; p0 += 64) {
-        float m = (p0 + lane < nparts) ? part_ml[(prow + p0 + lane) * 2] : -INFINITY;
+    const int head = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (head >= hq) return;
+    const int m = row_off[batch];
+    for (int row = blockIdx.x; row < m; row += gridDim.x) {
+        const int b = row2seq[row];
+        const int total = seq_len[b] - 1 + (row_off[b + 1] - row_off[b]);
+        const int nparts = min(max_parts, (total + part_keys - 1) / part_keys);
+        const size_t prow = ((size_t)row * hq + head) * max_parts;
+        float mg = -INFINITY;
+        for (int p0 = 0; p0 < nparts; p0 += 64) {
+            float mp = (p0 + lane < nparts) ? part_ml[(prow + p0 + lane) * 2] : -INFINITY;
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-        mg = fmaxf(mg, m);
-    }
-    float den = 0.f, acc[HD / 64];
-#pragma unroll
-    for (int i = 0; i < HD / 64; i++) acc[i] = 0.f;
-    for (int p0 = 0; p0 < nparts; p0 += 64) {
-        float wl = 0.f, ll = 0.f;
-        if (p0 + lane < nparts) {
-            wl = fast_exp2(part_ml[(prow + p0 + lane) * 2] - mg);
-            ll = part_ml[(prow + p0 + lane) * 2 + 1];
+            for (int o = 32; o > 0; o >>= 1) mp = fmaxf(mp, __shfl_xor(mp, o));
+            mg = fmaxf(mg, mp);
         }
-        const int n = min(64, nparts - p0);
-        // partition order; the values of eight partitions are fetched before the first is added, so that the loop
-        // waits for memory once per eight partitions instead of once per partition
-        for (int pb = 0; pb < n; pb += 8) {
-            _Float16 v[8][HD / 64];
+        float den = 0.f, acc[HD / 64];
 #pragma unroll
-            for (int q = 0; q < 8; q++) {
-                const _Float16* po = part_o + (prow + p0 + min(pb + q, n - 1)) * HD;
-#pragma unroll
-                for (int i = 0; i < HD / 64; i++) v[q][i] = po[lane + 64 * i];
+        for (int i = 0; i < HD / 64; i++) acc[i] = 0.f;
+        for (int p0 = 0; p0 < nparts; p0 += 64) {
+            float wl = 0.f, ll = 0.f;
+            if (p0 + lane < nparts) {
+                wl = fast_exp2(part_ml[(prow + p0 + lane) * 2] - mg);
+                ll = part_ml[(prow + p0 + lane) * 2 + 1];
             }
+            const int n = min(64, nparts - p0);
+            // partition order; the values of eight partitions are fetched before the first is added, so that the loop
+            // waits for memory once per eight partitions instead of once per partition
+            for (int pb = 0; pb < n; pb += 8) {
+                _Float16 v[8][HD / 64];
 #pragma unroll
-            for (int q = 0; q < 8; q++) {
-                if (pb + q < n) {
-                    // the partition's weight in the whole: exp2(m_p - m) l_p; its output is stored normalised
-                    const float w = __shfl(wl, pb + q) * __shfl(ll, pb + q);
-                    den += w;
+                for (int q = 0; q < 8; q++) {
+                    const _Float16* po = part_o + (prow + p0 + min(pb + q, n - 1)) * HD;
 #pragma unroll
-                    for (int i = 0; i < HD / 64; i++) acc[i] += w * (float)v[q][i];
+                    for (int i = 0; i < HD / 64; i++) v[q][i] = po[lane + 64 * i];
+                }
+#pragma unroll
+                for (int q = 0; q < 8; q++) {
+                    if (pb + q < n) {
+                        // the partition's weight in the whole: exp2(m_p - m) l_p; its output is stored normalised
+                        const float w = __shfl(wl, pb + q) * __shfl(ll, pb + q);
+                        den += w;
+#pragma unroll
+                        for (int i = 0; i < HD / 64; i++) acc[i] += w * (float)v[q][i];
+                    }
                 }
             }
         }
-    }
 #pragma unroll
-    for (int i = 0; i < HD / 64; i++) out[((size_t)row * hq + head) * HD + lane + 64 * i] = f32_to_bf16(acc[i] / den);
+        for (int i = 0; i < HD / 64; i++) out[((size_t)row * hq + head) * HD + lane + 64 * i] = f32_to_bf16(acc[i] / den);
+    }
 }
 
 // Plain kernel for debugging and for the fp32-activation mode: one wavefront per (row, query head), keys visited one
@@ -890,7 +894,7 @@ void hs_launch_attention_merge(const hs_ctx* ctx, const hs_seq_state* seq, const
     const hs_model_desc& d = ctx->desc;
     const _Float16* part_o = reinterpret_cast<const _Float16*>(ctx->ws + ctx->lay.part_o);
     float* part_ml = reinterpret_cast<float*>(ctx->ws + ctx->lay.part_ml);
-    dim3 grid(ctx->lim.max_rows, (d.n_q_heads + 3) / 4);
+    dim3 grid(hs_row_grid(ctx, 256, (d.n_q_heads + 3) / 4), (d.n_q_heads + 3) / 4);
     if (d.head_dim == 128)
         hipLaunchKernelGGL((attn_merge<128>), grid, dim3(256), 0, st, part_o, part_ml, step->row2seq, step->row_off,
                            seq->seq_len, seq->batch, ctx->max_parts, ctx->att_part, d.n_q_heads, out);

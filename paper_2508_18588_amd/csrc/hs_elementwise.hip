@@ -1,6 +1,10 @@
 // Row-wise kernels of the verify forward pass: embedding gather, RMSNorm, rotary embedding + KV-cache write,
 // and the per-row argmax over the vocabulary.  All are bandwidth-trivial next to attention and the GEMMs; each
 // row is processed independently with a reduction order that depends only on the row's own length.
+// The row count lives on the device, so a launch cannot size its grid to it: the grid is what the chip holds at
+// once (hs_row_grid) and a workgroup takes rows blockIdx.x, blockIdx.x + gridDim.x, ...  A grid of max_rows
+// workgroups, most of which only find that their row does not exist, costs several rounds of workgroup launches
+// (a few microseconds) in each of the ~150 row-kernel launches of a step.
 #include "hs_internal.h"
 
 namespace {
@@ -25,61 +29,85 @@ __device__ inline float block_sum(float v, float* red) {
 __global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ embed, const int32_t* __restrict__ tok,
                                                      const int32_t* __restrict__ m_dev, float* __restrict__ x, int d,
                                                      int vocab) {
-    int row = blockIdx.x;
-    if (row >= *m_dev) return;
-    int t = tok[row];
-    if (t < 0 || t >= vocab) t = 0;
-    const bf16_t* e = embed + (size_t)t * d;
-    for (int i = threadIdx.x; i < d; i += 256) x[(size_t)row * d + i] = bf16_to_f32(e[i]);
+    const int m = *m_dev;
+    for (int row = blockIdx.x; row < m; row += gridDim.x) {
+        int t = tok[row];
+        if (t < 0 || t >= vocab) t = 0;
+        const bf16_t* e = embed + (size_t)t * d;
+        for (int i = threadIdx.x; i < d; i += 256) x[(size_t)row * d + i] = bf16_to_f32(e[i]);
+    }
 }
 
 // One workgroup per row.  With chunks > 0 the row of the residual stream first receives the pending partial sums of
 // the preceding projection: t = p0 + p1 + ... in chunk order, x += t -- the arithmetic of the stand-alone ordered
 // reduce, so that the split execution gives the same bits whichever kernel finishes it.
 // OutT = bf16_t (rounded activations) or float (fp32-activation mode).
+// The kernel is a chain of memory round trips, not a stream: a thread keeps its (up to NORM_ITEMS x 4) elements in
+// registers from the first load to the normalised store, and the norm weights are fetched with them.
+constexpr int NORM_ITEMS = 4;  // d_model <= 4 * NORM_THREADS * NORM_ITEMS = 16384 (checked by hs_create)
+
+__device__ __forceinline__ void put4(bf16_t* p, float4 v) {
+    uint2 o;
+    o.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+    o.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+    *reinterpret_cast<uint2*>(p) = o;
+}
+__device__ __forceinline__ void put4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+
 template <typename OutT>
 __global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ w,
                                                        OutT* __restrict__ out, const int32_t* __restrict__ m_dev,
-                                                       int d, float eps, const float* __restrict__ part, int chunks,
+                                                       int d, float eps,
+                                                       const float* __restrict__ part, int chunks,
                                                        size_t chunk_stride) {
     __shared__ float red[NORM_THREADS / 64];
-    int row = blockIdx.x;
-    if (row >= *m_dev) return;
-    float* xr = x + (size_t)row * d;
-    float ss = 0.f;
-    if (chunks > 0) {
-        // 16-byte loads, the chunk loop unrolled so that several partials of an element are in flight at once
-        // (one workgroup per row: the row count is small and the kernel lives on loads in flight)
+    const int m = *m_dev;
+    for (int row = blockIdx.x; row < m; row += gridDim.x) {
+        float* xr = x + (size_t)row * d;
         const float* pr = part + (size_t)row * d;
-        for (int i = threadIdx.x * 4; i < d; i += 4 * NORM_THREADS) {
-            float4 t = *reinterpret_cast<const float4*>(pr + i);
+        float4 v[NORM_ITEMS], g[NORM_ITEMS];
+#pragma unroll
+        for (int it = 0; it < NORM_ITEMS; it++) {
+            const int i = (threadIdx.x + it * NORM_THREADS) * 4;
+            if (i >= d) continue;
+            v[it] = *reinterpret_cast<const float4*>(xr + i);
+            g[it] = *reinterpret_cast<const float4*>(w + i);
+            if (chunks > 0) {
+                // several partials of an element in flight at once
+                float4 t = *reinterpret_cast<const float4*>(pr + i);
 #pragma unroll 8
-            for (int c = 1; c < chunks; c++) {
-                const float4 q = *reinterpret_cast<const float4*>(pr + c * chunk_stride + i);
-                t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+                for (int c = 1; c < chunks; c++) {
+                    const float4 q = *reinterpret_cast<const float4*>(pr + c * chunk_stride + i);
+                    t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+                }
+                v[it].x += t.x; v[it].y += t.y; v[it].z += t.z; v[it].w += t.w;
             }
-            float4 v = *reinterpret_cast<const float4*>(xr + i);
-            v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
-            *reinterpret_cast<float4*>(xr + i) = v;
-            ss += v.x * v.x;
-            ss += v.y * v.y;
-            ss += v.z * v.z;
-            ss += v.w * v.w;
         }
-    } else {
-        // same element-to-thread assignment and summation order as above: the norm must not depend on which
-        // execution the preceding projection used
-        for (int i = threadIdx.x * 4; i < d; i += 4 * NORM_THREADS) {
-            const float4 v = *reinterpret_cast<const float4*>(xr + i);
-            ss += v.x * v.x;
-            ss += v.y * v.y;
-            ss += v.z * v.z;
-            ss += v.w * v.w;
+        // the sum of squares: same element-to-thread assignment and order with and without pending partials -- the
+        // norm must not depend on which execution the preceding projection used
+        float ss = 0.f;
+#pragma unroll
+        for (int it = 0; it < NORM_ITEMS; it++) {
+            const int i = (threadIdx.x + it * NORM_THREADS) * 4;
+            if (i >= d) continue;
+            if (chunks > 0) *reinterpret_cast<float4*>(xr + i) = v[it];
+            ss += v[it].x * v[it].x;
+            ss += v[it].y * v[it].y;
+            ss += v[it].z * v[it].z;
+            ss += v[it].w * v[it].w;
+        }
+        ss = block_sum(ss, red);
+        const float r = rsqrtf(ss / (float)d + eps);
+#pragma unroll
+        for (int it = 0; it < NORM_ITEMS; it++) {
+            const int i = (threadIdx.x + it * NORM_THREADS) * 4;
+            if (i >= d) continue;
+            float4 o;
+            o.x = v[it].x * r * g[it].x; o.y = v[it].y * r * g[it].y;
+            o.z = v[it].z * r * g[it].z; o.w = v[it].w * r * g[it].w;
+            put4(out + (size_t)row * d + i, o);
         }
     }
-    ss = block_sum(ss, red);
-    float r = rsqrtf(ss / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += NORM_THREADS) put(out + (size_t)row * d + i, xr[i] * r * w[i]);
 }
 
 // One workgroup per row.  Rotates q and k heads at the row's position (pairs i, i + h/2), writes q as bf16,
@@ -96,62 +124,65 @@ __global__ __launch_bounds__(NORM_THREADS) void rope_kv_kernel(const float* __re
                                                        int h, int max_pos, int n_blocks,
                                                        const float* __restrict__ part, int chunks,
                                                        size_t chunk_stride) {
-    int row = blockIdx.x;
-    if (row >= row_off[batch]) return;
-    int b = row2seq[row];
-    int node = row - row_off[b];
-    int p = pos[row];
-    if (p < 0 || p >= max_pos) return;  // flagged by the draft step; nothing is written for such a row
-    int slot = seq_len[b] - 1 + node;
-    if (slot < 0 || (slot >> 4) >= max_blocks) return;
-    int page = block_table[(size_t)b * max_blocks + (slot >> 4)];
-    if (page < 0 || page >= n_blocks) return;
-    int in_page = slot & 15;
-    int half = h >> 1;
-    const float* cs = rope_cs + (size_t)p * half * 2;
-    const int nqkv = (hq + 2 * hkv) * h;
-    // the row's QKV vector: the projection's output, or the chunk-ordered sum of its pending partials, which is
-    // first gathered into LDS with 16-byte loads (several partials of an element in flight at once)
     extern __shared__ float row_buf[];
-    if (chunks > 0) {
-        const float* pr = part + (size_t)row * nqkv;
-        for (int i = threadIdx.x * 4; i < nqkv; i += 4 * NORM_THREADS) {
-            float4 t = *reinterpret_cast<const float4*>(pr + i);
+    const int m = row_off[batch];
+    // (the conditions that skip a row are the same for all threads of the workgroup)
+    for (int row = blockIdx.x; row < m; row += gridDim.x) {
+        if (chunks > 0 && row != (int)blockIdx.x) __syncthreads();  // row_buf of the previous row has been read
+        int b = row2seq[row];
+        int node = row - row_off[b];
+        int p = pos[row];
+        if (p < 0 || p >= max_pos) continue;  // flagged by the draft step; nothing is written for such a row
+        int slot = seq_len[b] - 1 + node;
+        if (slot < 0 || (slot >> 4) >= max_blocks) continue;
+        int page = block_table[(size_t)b * max_blocks + (slot >> 4)];
+        if (page < 0 || page >= n_blocks) continue;
+        int in_page = slot & 15;
+        int half = h >> 1;
+        const float* cs = rope_cs + (size_t)p * half * 2;
+        const int nqkv = (hq + 2 * hkv) * h;
+        // the row's QKV vector: the projection's output, or the chunk-ordered sum of its pending partials, which is
+        // first gathered into LDS with 16-byte loads (several partials of an element in flight at once)
+        if (chunks > 0) {
+            const float* pr = part + (size_t)row * nqkv;
+            for (int i = threadIdx.x * 4; i < nqkv; i += 4 * NORM_THREADS) {
+                float4 t = *reinterpret_cast<const float4*>(pr + i);
 #pragma unroll 8
-            for (int c = 1; c < chunks; c++) {
-                const float4 q4 = *reinterpret_cast<const float4*>(pr + c * chunk_stride + i);
-                t.x += q4.x; t.y += q4.y; t.z += q4.z; t.w += q4.w;
+                for (int c = 1; c < chunks; c++) {
+                    const float4 q4 = *reinterpret_cast<const float4*>(pr + c * chunk_stride + i);
+                    t.x += q4.x; t.y += q4.y; t.z += q4.z; t.w += q4.w;
+                }
+                *reinterpret_cast<float4*>(row_buf + i) = t;
             }
-            *reinterpret_cast<float4*>(row_buf + i) = t;
+            __syncthreads();
         }
-        __syncthreads();
-    }
-    const float* src = qkv + (size_t)row * nqkv;
-    auto val = [&](int e) -> float { return chunks > 0 ? row_buf[e] : src[e]; };
-    // q heads
-    for (int i = threadIdx.x; i < hq * half; i += NORM_THREADS) {
-        int head = i / half, j = i % half;
-        float c = cs[2 * j], s = cs[2 * j + 1];
-        float a = val(head * h + j), bb = val(head * h + j + half);
-        T* dst = q_out + (size_t)row * hq * h + head * h;
-        put(dst + j, a * c - bb * s);
-        put(dst + j + half, bb * c + a * s);
-    }
-    // k heads -> cache [page][kv head][16][h]
-    const int koff = hq * h;
-    for (int i = threadIdx.x; i < hkv * half; i += NORM_THREADS) {
-        int head = i / half, j = i % half;
-        float c = cs[2 * j], s = cs[2 * j + 1];
-        float a = val(koff + head * h + j), bb = val(koff + head * h + j + half);
-        T* dst = kc + layer_off + (((size_t)page * hkv + head) * 16 + in_page) * h;
-        put(dst + j, a * c - bb * s);
-        put(dst + j + half, bb * c + a * s);
-    }
-    // v heads -> cache [page][kv head][h][16]
-    const int voff = koff + hkv * h;
-    for (int i = threadIdx.x; i < hkv * h; i += NORM_THREADS) {
-        int head = i / h, j = i % h;
-        put(vc + layer_off + (((size_t)page * hkv + head) * h + j) * 16 + in_page, val(voff + head * h + j));
+        const float* src = qkv + (size_t)row * nqkv;
+        auto val = [&](int e) -> float { return chunks > 0 ? row_buf[e] : src[e]; };
+        // q heads
+        for (int i = threadIdx.x; i < hq * half; i += NORM_THREADS) {
+            int head = i / half, j = i % half;
+            float c = cs[2 * j], s = cs[2 * j + 1];
+            float a = val(head * h + j), bb = val(head * h + j + half);
+            T* dst = q_out + (size_t)row * hq * h + head * h;
+            put(dst + j, a * c - bb * s);
+            put(dst + j + half, bb * c + a * s);
+        }
+        // k heads -> cache [page][kv head][16][h]
+        const int koff = hq * h;
+        for (int i = threadIdx.x; i < hkv * half; i += NORM_THREADS) {
+            int head = i / half, j = i % half;
+            float c = cs[2 * j], s = cs[2 * j + 1];
+            float a = val(koff + head * h + j), bb = val(koff + head * h + j + half);
+            T* dst = kc + layer_off + (((size_t)page * hkv + head) * 16 + in_page) * h;
+            put(dst + j, a * c - bb * s);
+            put(dst + j + half, bb * c + a * s);
+        }
+        // v heads -> cache [page][kv head][h][16]
+        const int voff = koff + hkv * h;
+        for (int i = threadIdx.x; i < hkv * h; i += NORM_THREADS) {
+            int head = i / h, j = i % h;
+            put(vc + layer_off + (((size_t)page * hkv + head) * h + j) * 16 + in_page, val(voff + head * h + j));
+        }
     }
 }
 
@@ -161,32 +192,34 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
                                                        const int32_t* __restrict__ m_dev, int vocab) {
     __shared__ float sv[16];
     __shared__ int si[16];
-    int row = blockIdx.x;
-    if (row >= *m_dev) return;
-    const float* l = logits + (size_t)row * vocab;
-    float bv = -INFINITY;
-    int bi = 0x7fffffff;
-    auto take = [&](float v, int i) { if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; } };
-    if ((vocab & 3) == 0) {
-        const float4* l4 = reinterpret_cast<const float4*>(l);
-        for (int i = threadIdx.x; i < vocab / 4; i += 1024) {
-            float4 v = l4[i];
-            take(v.x, 4 * i); take(v.y, 4 * i + 1); take(v.z, 4 * i + 2); take(v.w, 4 * i + 3);
+    const int m = *m_dev;
+    for (int row = blockIdx.x; row < m; row += gridDim.x) {
+        if (row != (int)blockIdx.x) __syncthreads();  // the previous row's candidates have been read
+        const float* l = logits + (size_t)row * vocab;
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+        auto take = [&](float v, int i) { if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; } };
+        if ((vocab & 3) == 0) {
+            const float4* l4 = reinterpret_cast<const float4*>(l);
+            for (int i = threadIdx.x; i < vocab / 4; i += 1024) {
+                float4 v = l4[i];
+                take(v.x, 4 * i); take(v.y, 4 * i + 1); take(v.z, 4 * i + 2); take(v.w, 4 * i + 3);
+            }
+        } else {
+            for (int i = threadIdx.x; i < vocab; i += 1024) take(l[i], i);
         }
-    } else {
-        for (int i = threadIdx.x; i < vocab; i += 1024) take(l[i], i);
-    }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        float ov = __shfl_xor(bv, o);
-        int oi = __shfl_xor(bi, o);
-        take(ov, oi);
-    }
-    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int w = 1; w < 16; w++) take(sv[w], si[w]);
-        out[row] = bi;
+        for (int o = 32; o > 0; o >>= 1) {
+            float ov = __shfl_xor(bv, o);
+            int oi = __shfl_xor(bi, o);
+            take(ov, oi);
+        }
+        if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < 16; w++) take(sv[w], si[w]);
+            out[row] = bi;
+        }
     }
 }
 
@@ -268,7 +301,7 @@ void hs_launch_prefill_rows(const hs_ctx* ctx, const hs_seq_state* seq, int32_t*
 }
 
 void hs_launch_embed(const hs_ctx* ctx, const hs_step* step, int batch, float* x, hipStream_t st) {
-    hipLaunchKernelGGL(embed_kernel, dim3(ctx->lim.max_rows), dim3(256), 0, st, ctx->embed, step->tok,
+    hipLaunchKernelGGL(embed_kernel, dim3(hs_row_grid(ctx, 256)), dim3(256), 0, st, ctx->embed, step->tok,
                        step->row_off + batch, x, ctx->desc.d_model, ctx->desc.vocab);
 }
 
@@ -277,10 +310,10 @@ void hs_launch_rmsnorm(const hs_ctx* ctx, float* x, const float* w, void* out, c
     const float* part = reinterpret_cast<const float*>(ctx->ws + ctx->lay.gemm_part);
     const size_t stride = (size_t)ctx->lim.max_rows * ctx->desc.d_model;
     if (hs_fp32_activations(ctx))
-        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), 0, st, x, w, (float*)out,
+        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(hs_row_grid(ctx, NORM_THREADS)), dim3(NORM_THREADS), 0, st, x, w, (float*)out,
                            m_dev, ctx->desc.d_model, ctx->desc.rms_eps, part, pending_chunks, stride);
     else
-        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), 0, st, x, w,
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(hs_row_grid(ctx, NORM_THREADS)), dim3(NORM_THREADS), 0, st, x, w,
                            (bf16_t*)out, m_dev, ctx->desc.d_model, ctx->desc.rms_eps, part, pending_chunks, stride);
 }
 
@@ -297,16 +330,16 @@ void hs_launch_rope_kv(const hs_ctx* ctx, int layer, const hs_kv_cache* cache, c
         d.n_kv_heads, d.head_dim, ctx->lim.max_pos, cache->n_blocks, part, pending_chunks,                       \
         (size_t)ctx->lim.max_rows * nqkv
     if (hs_fp32_activations(ctx))
-        hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), lds, st,
+        hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(hs_row_grid(ctx, NORM_THREADS)), dim3(NORM_THREADS), lds, st,
                            HS_ROPE_ARGS(float));
     else
-        hipLaunchKernelGGL(rope_kv_kernel<bf16_t>, dim3(ctx->lim.max_rows), dim3(NORM_THREADS), lds, st,
+        hipLaunchKernelGGL(rope_kv_kernel<bf16_t>, dim3(hs_row_grid(ctx, NORM_THREADS)), dim3(NORM_THREADS), lds, st,
                            HS_ROPE_ARGS(bf16_t));
 #undef HS_ROPE_ARGS
 }
 
 void hs_launch_argmax(const hs_ctx* ctx, const float* logits, int32_t* argmax, const int32_t* m_dev,
                       hipStream_t st) {
-    hipLaunchKernelGGL(argmax_kernel, dim3(ctx->lim.max_rows), dim3(1024), 0, st, logits, argmax, m_dev,
+    hipLaunchKernelGGL(argmax_kernel, dim3(hs_row_grid(ctx, 1024)), dim3(1024), 0, st, logits, argmax, m_dev,
                        ctx->desc.vocab);
 }

@@ -78,6 +78,14 @@ static inline bool hs_head_fused(const hs_ctx* ctx, const hs_step* step) {
     return !step->logits && !hs_logits_in_workspace(ctx);
 }
 
+// Grid of a row-strided kernel (workgroup i takes rows i, i + grid, ...) whose workgroups have `threads` threads and
+// of which `per_row` work on one row: what the device holds at once (2048 threads per compute unit), at most one
+// set per row.  The row count itself is only known on the device.
+static inline int hs_row_grid(const hs_ctx* ctx, int threads, int per_row = 1) {
+    const int resident = ctx->n_cu * (2048 / threads) / per_row;
+    return resident < 1 ? 1 : (resident < ctx->lim.max_rows ? resident : ctx->lim.max_rows);
+}
+
 // ---- launchers (each enqueues on `st`; shapes have been validated by the caller) ----
 
 // GEMM family: C[M,N] (+)= A[M,K] . W[N,K]^T, A and W bf16, fp32 accumulation in a fixed k order.
