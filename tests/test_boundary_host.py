@@ -67,6 +67,10 @@ def test_create_validates_shape_and_limits(lib):
     assert status(d=bad) == hs.HS_ERR_UNSUPPORTED
     bad = hs.hs_model_desc(0, 256, 4, 4, 64, 1024, 4096, 16, 1e-6)
     assert status(d=bad) == hs.HS_ERR_INVALID_ARG
+    bad = hs.hs_model_desc(2, 16448, 4, 4, 64, 1024, 4096, 16, 1e-6)     # d_model beyond the row kernels' 16384
+    assert status(d=bad) == hs.HS_ERR_UNSUPPORTED
+    w3 = hs.hs_weights(0x1000, 0x1000, 0x1004, w.wqkv, w.wo, w.wgate, w.wup, w.wdown, w.norm1, w.norm2, 0x1000)
+    assert status(ww=w3) == hs.HS_ERR_INVALID_ARG                         # norm weights not 16-byte aligned
     assert status(ll=hs.hs_limits(4, 33, 1, 200, 32, 512, 8)) == hs.HS_ERR_INVALID_ARG      # k_max > 32
     assert status(ll=hs.hs_limits(4, 32, 2, 400, 32, 512, 8)) == hs.HS_ERR_UNSUPPORTED      # 65 nodes
     assert status(ll=hs.hs_limits(4, 4, 1, 19, 32, 512, 8)) == hs.HS_ERR_CAPACITY           # too few rows
