@@ -339,8 +339,8 @@ __device__ inline void attn_wave_stream(const AttnArgs& a, const int4* __restric
 // One partition of one (sequence, KV head) by the WORKGROUP (R > 32): 128-key tiles shared by the four wavefronts, the
 // unit's 32-row tiles (un.rt0 .. un.rt0 + 3) dealt to them round-robin, one tile of register prefetch.  (RTW row
 // tiles per wavefront; the launcher instantiates RTW = 1.)
-template <int HD, int RTW>
-__device__ inline void attn_unit_wg(const AttnArgs& a, const AttnUnit& un, bf16_t* sK, bf16_t* sV, int tid) {
+template <int HD, int RTW, int NLIVE>
+__device__ inline void attn_unit_wg_n(const AttnArgs& a, const AttnUnit& un, bf16_t* sK, bf16_t* sV, int tid) {
     constexpr int KS = HD + 8, VS = 20, NKS = HD / 16, NDT = HD / 32;
     // keys per shared tile: with one row tile per wavefront there are registers for a 128-key tile in flight (twice
     // the bytes on their way per workgroup), with two only for 64
@@ -381,36 +381,73 @@ __device__ inline void attn_unit_wg(const AttnArgs& a, const AttnUnit& un, bf16_
         l_run[t] = 0.f;
     }
 
-    // a tile of TILE keys = TILE/16 pages = TILE*HD/8 16-byte chunks of K and of V^T; chunk c = tid + 256*i lies in
-    // page c / (2*HD), which is uniform within a wavefront
-    u32x4 rk[NCK], rv[NCK];
-    const int wave_c0 = tid & ~63;
-#define HS_G_FETCH(KB)                                                                                            \
+    // Staging.  A tile of TILE keys = TILE/16 pages, each 2*HD 16-byte chunks of K and as many of V^T.  A wavefront
+    // stages a run of whole pages.  With four live row tiles (NLIVE = 4) every wavefront stages a quarter of the
+    // tile; in a unit with fewer (a sequence of 33..96 query rows per KV head, or the last tile group of a longer
+    // one) the wavefronts without a row tile do nothing but stage, and take most of the pages off the ones that
+    // compute: loads, address arithmetic and LDS writes leave the instruction streams that carry the softmax and
+    // the MFMAs.  The two kinds of wavefront run separate loops (so that the staging registers of the one and the
+    // accumulators of the other do not add up) with the same two barriers per tile.
+    //   pages per tile = TILE/16 = 8:   4 live tiles (or 1): 2 pages each;  3: 1 each + 5;  2: 1 each + 3 + 3
+    // NLIVE = 4: every wavefront stages a quarter; NLIVE = 2: two or three live tiles (n_live), one routine for both.
+    constexpr int NPG = TILE / 16;
+    constexpr int PC = NLIVE == 4 ? NPG / 4 : NPG / 8;                            // pages of a computing wavefront
+    constexpr int PI = NLIVE == 4 ? 1 : NPG - 3 * PC;                             // most pages of a staging-only one
+    constexpr int CPP = 2 * HD / 64;                                              // 64-lane chunk rows per page
+    const int n_live = NLIVE == 4 ? 4 : min(4, nrt - un.rt0);
+    const int npi = __builtin_amdgcn_readfirstlane(NLIVE == 4 ? 0 : (NPG - n_live * PC) / (4 - n_live));
+    const bool computes = slot < n_live;
+    const int page0 = __builtin_amdgcn_readfirstlane(computes ? slot * PC : n_live * PC + (slot - n_live) * npi);
+    // lane p: the page of the partition's keys 16 p .. 16 p + 15 (a partition has at most 64 pages); one vector
+    // load per unit instead of a scalar load per page and tile
+    const int my_page = safe_page_lane(bt, k_begin + 16 * lane, total, a.max_blocks, a.n_blocks);
+    // lane parts of the addresses: chunk row r of a page holds chunks 64 r .. 64 r + 63
+    const int lane_g = lane * 8;                                              // elements, global side
+    const int lane_k = (lane / (HD / 8)) * KS + (lane % (HD / 8)) * 8;        // sK: 64 / (HD/8) keys per chunk row
+    const int lane_v = (lane >> 1) * VS + (lane & 1) * 8;                     // sV: 32 dims per chunk row
+#define HS_G_FETCH(KB, NP, NPRT)   /* NP: compile-time bound, NPRT: the wavefront's pages (>= 3 when guarded) */  \
     {                                                                                                             \
-        _Pragma("unroll") for (int i = 0; i < NCK; i++) {                                                         \
-            const int kk = (wave_c0 + 256 * i) / (2 * HD);                                                        \
-            const int within = (tid + 256 * i) % (2 * HD);                                                        \
-            const size_t pofs = (size_t)safe_page(bt, (KB) + 16 * kk, total, a.max_blocks, a.n_blocks) * page_stride; \
-            rk[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kbase_ptr + pofs + within * 8));                           \
-            rv[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vbase_ptr + pofs + within * 8));                           \
+        _Pragma("unroll") for (int pg = 0; pg < NP; pg++) {                                                       \
+            if (pg >= 3 && pg >= (NPRT)) break;                                                                   \
+            const size_t pofs = (size_t)__builtin_amdgcn_readlane(my_page, (((KB) - k_begin) >> 4) + page0 + pg) * page_stride; \
+            _Pragma("unroll") for (int r = 0; r < CPP; r++) {                                                     \
+                rk[pg * CPP + r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kbase_ptr + pofs + r * 512 + lane_g)); \
+                rv[pg * CPP + r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vbase_ptr + pofs + r * 512 + lane_g)); \
+            }                                                                                                     \
         }                                                                                                         \
     }
-    HS_G_FETCH(k_begin)
+#define HS_G_STAGE(NP, NPRT)                                                                                      \
+    {                                                                                                             \
+        bf16_t* pk = sK + page0 * 16 * KS + lane_k;                                                               \
+        bf16_t* pv = sV + page0 * HD * VS + lane_v;                                                               \
+        _Pragma("unroll") for (int pg = 0; pg < NP; pg++)                                                         \
+            _Pragma("unroll") for (int r = 0; r < CPP; r++) {                                                     \
+                if (pg >= 3 && pg >= (NPRT)) break;                                                     \
+                *reinterpret_cast<u32x4*>(pk + (pg * 16 + r * (512 / HD)) * KS) = rk[pg * CPP + r];               \
+                u32x2* dst = reinterpret_cast<u32x2*>(pv + (pg * HD + r * 32) * VS);                              \
+                dst[0] = u32x2{rv[pg * CPP + r].x, rv[pg * CPP + r].y};                                           \
+                dst[1] = u32x2{rv[pg * CPP + r].z, rv[pg * CPP + r].w};                                           \
+            }                                                                                                     \
+    }
+    if (!computes) {
+        // staging only: no row tile, nothing to store at the end
+        u32x4 rk[PI * CPP], rv[PI * CPP];
+        HS_G_FETCH(k_begin, PI, npi)
+        for (int kbase = k_begin; kbase < k_end; kbase += TILE) {
+            __syncthreads();  // previous tile (or previous unit) fully consumed
+            HS_G_STAGE(PI, npi)
+            __syncthreads();
+            if (kbase + TILE < k_end) HS_G_FETCH(kbase + TILE, PI, npi)
+        }
+        return;
+    }
+    u32x4 rk[PC * CPP], rv[PC * CPP];
+    HS_G_FETCH(k_begin, PC, PC)
     for (int kbase = k_begin; kbase < k_end; kbase += TILE) {
         __syncthreads();  // previous tile (or previous unit) fully consumed
-#pragma unroll
-        for (int i = 0; i < NCK; i++) {
-            const int kk = (wave_c0 + 256 * i) / (2 * HD);
-            const int within = (tid + 256 * i) % (2 * HD);
-            int key = kk * 16 + within / (HD / 8), c16 = within % (HD / 8);
-            *reinterpret_cast<u32x4*>(&sK[key * KS + c16 * 8]) = rk[i];
-            int dim = within >> 1, hf = within & 1;
-            u32x2* dst = reinterpret_cast<u32x2*>(&sV[(kk * HD + dim) * VS + hf * 8]);
-            dst[0] = u32x2{rv[i].x, rv[i].y};
-            dst[1] = u32x2{rv[i].z, rv[i].w};
-        }
+        HS_G_STAGE(PC, PC)
         __syncthreads();
-        if (kbase + TILE < k_end) HS_G_FETCH(kbase + TILE)
+        if (kbase + TILE < k_end) HS_G_FETCH(kbase + TILE, PC, PC)
 #pragma unroll
         for (int sub = 0; sub < TILE / 32; sub++) {
             const int kb = kbase + 32 * sub;
@@ -423,6 +460,7 @@ __device__ inline void attn_unit_wg(const AttnArgs& a, const AttnUnit& un, bf16_
             }
         }
     }
+#undef HS_G_STAGE
 #undef HS_G_FETCH
 #pragma unroll
     for (int t = 0; t < RTW; t++) {
@@ -430,6 +468,15 @@ __device__ inline void attn_unit_wg(const AttnArgs& a, const AttnUnit& un, bf16_
         store_partial<HD>(o[t], m_run[t], l_run[t], a.part_o, a.part_ml, r0, un.rt0 + slot + 4 * t, R, G, a.hq, j,
                           a.max_parts, part, half, l32);
     }
+}
+
+// The unit's number of live row tiles (1..4; a group of four tiles per unit) selects the staging split.
+template <int HD, int RTW>
+__device__ inline void attn_unit_wg(const AttnArgs& a, const AttnUnit& un, bf16_t* sK, bf16_t* sV, int tid) {
+    const int nrt = (un.nn * (a.hq / a.hkv) + 31) >> 5;
+    const int n_live = RTW == 1 ? min(4, nrt - un.rt0) : 4;
+    if (n_live == 3 || n_live == 2) attn_unit_wg_n<HD, RTW, 2>(a, un, sK, sV, tid);
+    else attn_unit_wg_n<HD, RTW, 4>(a, un, sK, sV, tid);   // also a single live tile: everyone stages a quarter
 }
 
 // The units of one step, built once per hs_verify call (the same for every layer): a unit = one partition of one
