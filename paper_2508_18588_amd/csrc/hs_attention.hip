@@ -534,11 +534,11 @@ __global__ __launch_bounds__(256) void attn_worklist_kernel(const int32_t* __res
         __syncthreads();
         if (tid == 255) { carry_a = ba + ia; carry_b = bb + ib; }
         const int nb = min(256, batch - b0);
-        for (int i = 0; i < nb; i++) {
+        for (int i = wave; i < nb; i += 4) {     // a wavefront per sequence: a sequence has a few dozen units
             const int n = s_nu[i];
             int4* dst = (n < 0 ? list_a : list_b) + 2 * (size_t)s_off[i];
             const int cnt = n < 0 ? -n : n, grp = s_grp[i];
-            for (int u = tid; u < cnt; u += 256) {
+            for (int u = lane; u < cnt; u += 64) {
                 // v = (partition, head); the tile groups of one (partition, head) are neighbours (grp is 1 or 2: at
                 // most 256 query rows per KV head)
                 const int v = grp == 1 ? u : (grp == 2 ? (u >> 1) : u / grp);
