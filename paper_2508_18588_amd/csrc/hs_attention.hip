@@ -24,7 +24,9 @@
 //     are dealt to the 4 wavefronts.  A sequence with more than 128 query rows per KV head is cut into units of
 //     four row tiles, each of which walks the partition's keys on its own: holding two row tiles per wavefront
 //     instead would cost every workgroup unit of the launch half the resident workgroups (registers), which was
-//     measured to be far dearer than reading the K/V of the few very long drafts twice.
+//     measured to be far dearer than reading the K/V of the few very long drafts twice.  In a unit with two or three
+//     live row tiles the wavefronts without a tile only stage K/V (most of each tile); the computing ones keep one
+//     page per tile.
 // Both run the identical per-row arithmetic on the identical partitions: masked keys contribute exact zeros and
 // partitions merge in index order, so a row's result is bit-identical whether it is verified next to other draft
 // rows or decoded alone.
