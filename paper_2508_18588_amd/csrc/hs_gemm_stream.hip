@@ -424,24 +424,26 @@ __global__ __launch_bounds__(256) void hs_gemm_stream(const bf16_t* __restrict__
     p.m_max = m_max;
     p.N = N;
     p.K = K;
-    // Workgroup id -> (weight group, row pass): ids are dealt round-robin to the 8 XCDs (each with its own L2); an
-    // XCD takes a weight group and runs its row passes back to back, so that the passes which stream the same
-    // weight slab meet in one L2.
+    // Workgroup id -> (weight group, row pass): ids are dealt round-robin to the 8 XCDs (each with its own L2).
+    // Unsplit K: an XCD takes a weight group and runs its row passes back to back, so that the passes which stream
+    // the same weight slab meet in one L2.
     // (With a single pass the id is the group: no padding of the grid, a workgroup that only exits still has to
     // wait for a compute unit with this kernel's LDS free.)
     int group = blockIdx.x, pass = 0, chunk = blockIdx.y;
-    if (n_pass == 1 && gridDim.y > 1) {
-        // Split-K, one pass: the workgroups that land on one XCD (ids congruent mod 8) take consecutive
-        // (chunk, group) pairs, i.e. one or two K chunks -- the slice of the activations they re-read then fits
-        // that XCD's L2 (all chunks together, e.g. 8 MB for the down projection at 220 rows, do not).
+    if (gridDim.y > 1) {
+        // Split-K: the workgroups that land on one XCD (ids congruent mod 8) take consecutive (chunk, group, pass)
+        // triples, pass fastest, i.e. one or two K chunks -- the slices of the activations they re-read then fit that
+        // XCD's L2 (all chunks together, e.g. 8 MB for the down projection at 220 rows and 27 MB at 720, do not), and
+        // the row passes that stream the same weight slice run side by side.  (grid.x = groups x passes, no padding.)
         const int total = gridDim.x * gridDim.y, id = blockIdx.x + gridDim.x * blockIdx.y;
         const int xcd = id & 7, slot = id >> 3;
         const int full = total >> 3, extra = total & 7;          // XCDs 0 .. extra-1 hold one workgroup more
         const int w = xcd * full + min(xcd, extra) + slot;
         chunk = w / (int)gridDim.x;
-        group = w - chunk * (int)gridDim.x;
-    }
-    if (n_pass > 1) {
+        const int rem = w - chunk * (int)gridDim.x;
+        group = rem / n_pass;
+        pass = rem - group * n_pass;
+    } else if (n_pass > 1) {
         const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
         group = (local / n_pass) * 8 + xcd;
         pass = local % n_pass;
@@ -505,7 +507,7 @@ void launch_stream(const bf16_t* a, const bf16_t* w, const bf16_t* w2, void* c, 
     int n_pass = (rows_hint + 128 * MT - 1) / (128 * MT);
     if (n_pass < 1) n_pass = 1;
     if (n_pass > (m_max + 128 * MT - 1) / (128 * MT)) n_pass = (m_max + 128 * MT - 1) / (128 * MT);
-    dim3 grid(n_pass > 1 ? ((n_groups + 7) / 8) * 8 * n_pass : n_groups, chunks);
+    dim3 grid(chunks > 1 ? n_groups * n_pass : (n_pass > 1 ? ((n_groups + 7) / 8) * 8 * n_pass : n_groups), chunks);
     hipLaunchKernelGGL((hs_gemm_stream<EPI, PARTIAL, NU, MT, SA, SW>), grid, dim3(256), lds, st, a, w, w2, c, part,
                        m_dev, m_max, n, k, tpc, n_groups, n_pass);
 }
