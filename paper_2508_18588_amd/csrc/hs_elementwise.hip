@@ -128,22 +128,13 @@ __global__ __launch_bounds__(NORM_THREADS) void rope_kv_kernel(const float* __re
     const int m = row_off[batch];
     // (the conditions that skip a row are the same for all threads of the workgroup)
     for (int row = blockIdx.x; row < m; row += gridDim.x) {
-        if (chunks > 0 && row != (int)blockIdx.x) __syncthreads();  // row_buf of the previous row has been read
-        int b = row2seq[row];
-        int node = row - row_off[b];
-        int p = pos[row];
-        if (p < 0 || p >= max_pos) continue;  // flagged by the draft step; nothing is written for such a row
-        int slot = seq_len[b] - 1 + node;
-        if (slot < 0 || (slot >> 4) >= max_blocks) continue;
-        int page = block_table[(size_t)b * max_blocks + (slot >> 4)];
-        if (page < 0 || page >= n_blocks) continue;
-        int in_page = slot & 15;
-        int half = h >> 1;
-        const float* cs = rope_cs + (size_t)p * half * 2;
+        // The row's QKV vector: the projection's output, or the chunk-ordered sum of its pending partials, which is
+        // first gathered into LDS with 16-byte loads (several partials of an element in flight at once).  The
+        // gather comes first: it depends on nothing but the row, so its loads are on their way while the chain
+        // row -> sequence -> slot -> page below is followed.
         const int nqkv = (hq + 2 * hkv) * h;
-        // the row's QKV vector: the projection's output, or the chunk-ordered sum of its pending partials, which is
-        // first gathered into LDS with 16-byte loads (several partials of an element in flight at once)
         if (chunks > 0) {
+            if (row != (int)blockIdx.x) __syncthreads();  // row_buf of the previous row has been read
             const float* pr = part + (size_t)row * nqkv;
             for (int i = threadIdx.x * 4; i < nqkv; i += 4 * NORM_THREADS) {
                 float4 t = *reinterpret_cast<const float4*>(pr + i);
@@ -154,8 +145,18 @@ __global__ __launch_bounds__(NORM_THREADS) void rope_kv_kernel(const float* __re
                 }
                 *reinterpret_cast<float4*>(row_buf + i) = t;
             }
-            __syncthreads();
         }
+        int b = row2seq[row];
+        int node = row - row_off[b];
+        int p = pos[row];
+        int slot = seq_len[b] - 1 + node;
+        int page = (slot >= 0 && (slot >> 4) < max_blocks) ? block_table[(size_t)b * max_blocks + (slot >> 4)] : -1;
+        if (chunks > 0) __syncthreads();
+        // (a position flagged by the draft step, a slot beyond the block table, a missing page: nothing is written)
+        if (p < 0 || p >= max_pos || page < 0 || page >= n_blocks) continue;
+        int in_page = slot & 15;
+        int half = h >> 1;
+        const float* cs = rope_cs + (size_t)p * half * 2;
         const float* src = qkv + (size_t)row * nqkv;
         auto val = [&](int e) -> float { return chunks > 0 ? row_buf[e] : src[e]; };
         // q heads
