@@ -356,6 +356,45 @@ def test_batch_of_300_ragged_sequences_mixed_unit_kinds():
     assert stats["rows"] > 3 * live + 900          # the planted drafts were taken (12 extra rows each, first step)
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("head_dim", [64, 128])
+def test_workgroup_attention_units_with_one_to_four_live_row_tiles(head_dim):
+    """Drafts of 4..32 tokens on 4 query heads per KV head: 20..132 query rows per KV head, i.e. streamed wavefront
+    units next to workgroup units with two, three and four live row tiles and, for the longest draft, a second unit
+    of one tile -- every staging split of the workgroup path (wavefronts that only stage K/V next to those that
+    compute) -- over contexts of 1..11 tiles of 128 keys with ragged ends.  Two decode steps in lock-step with the
+    oracle."""
+    from paper_2508_18588_amd.runtime import Engine, Policy
+    shape = ModelShape(n_layers=2, d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=head_dim, d_ffn=384, vocab=512)
+    w = make_weights(shape, 61, norm_jitter=0.1)
+    rope = rope_table(2048, shape.head_dim)
+    model = oracle.Model(shape, w, rope)
+    rng = np.random.default_rng(62 + head_dim)
+    draft_lens = [4, 8, 12, 16, 22, 27, 32, 0]
+    B = 24
+    lens = rng.integers(100, 1400, B)
+    toks = [rng.integers(0, shape.vocab, int(n)).astype(np.int32) for n in lens]
+    budgets = [40] * B
+    cands = []
+    for b in range(B):
+        k = draft_lens[b % len(draft_lens)]
+        if k:   # a copy of the text's last tokens followed by k tokens: hs_draft takes exactly k (the history ends)
+            cands.append([np.concatenate([toks[b][-6:], rng.integers(0, shape.vocab, k)]).astype(np.int32)])
+        else:
+            cands.append([np.zeros(0, np.int32)])
+    pol = Policy(window=6, m_min=3, k_fixed=32, k_max=32)
+    eng = Engine(shape, w, rope, max_batch=B, k_max=32, c_max=1, max_len=int(lens.max()) + 80, shuffle_pages_seed=63)
+    eng.load_sequences(toks, budgets=budgets)
+    eng.set_history(cands)
+    eng.prefill_chunked(128)
+    ob = OracleBatch(model, toks, budgets, int(lens.max()) + 120)
+    stats = lockstep(eng, ob, cands, pol, max_steps=2)
+    eng.close()
+    print("live-tiles", head_dim, stats)
+    assert stats["steps"] == 2
+    assert stats["rows"] >= B + 3 * sum(draft_lens)      # every planted draft was taken in the first step
+
+
 def test_split_and_serial_gemm_execution_agree_bitwise():
     """The narrow projections cut K into a fixed number of chunks; with few rows each chunk runs in its own
     workgroup and an ordered reduce adds them, with many rows one workgroup folds the chunks itself.  Both must
