@@ -56,7 +56,24 @@ struct stream_args {
     float* part;
     int M, m_max, N, K, n0, m0, kt0, kt1, chunk, group, n_groups;
     int w_once;  // the launch reads every weight byte once (one row pass): non-temporal weight loads
+    int w_pre;   // the weight-only part of the prologue has been issued already (by the kernel, before M was known)
 };
+
+// The 1 KB blocks of weight tile kt that wavefront `wave` fetches: block wave + 4j = quarter `wave` of unit j, into
+// stage kt % SW of the weight ring.  (A SwiGLU unit holds 16 gate rows then the 16 up rows of the same columns, so a
+// wavefront's blocks are all gate rows -- wavefronts 0, 1 -- or all up rows -- 2, 3.)
+template <int NU, int MT, int SA, int SW>
+__device__ __forceinline__ void issue_weight_tile(const stream_args& p, const unsigned char* w_mine, unsigned smem_off,
+                                                  const unsigned (&w_off)[NU], int wave, int kt) {
+    constexpr int W_RING = SA * 4 * MT * TILE_BYTES, W_STAGE = NU * TILE_BYTES;
+    const unsigned dst = smem_off + W_RING + (kt % SW) * W_STAGE + wave * 1024;
+    const unsigned char* base = w_mine + (size_t)kt * ROW_BYTES;
+#pragma unroll
+    for (int j = 0; j < NU; j++) {
+        if (p.w_once) load_to_lds_16_stream(base, w_off[j], dst + j * 4096);
+        else load_to_lds_16(base, w_off[j], dst + j * 4096);
+    }
+}
 
 // One K chunk of one row pass for a wavefront that owns NMI live row tiles (0 = loads and barriers only).
 template <int EPI, bool PARTIAL, int NU, int MT, int SA, int SW, int NMI>
@@ -91,18 +108,8 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
             }
         }
     };
-    // weight tile: block wave + 4j = quarter `wave` of unit j; a SwiGLU unit holds 16 gate rows then the 16 up rows
-    // of the same columns, so a wavefront's blocks are all gate rows (wavefronts 0, 1) or all up rows (2, 3)
     const unsigned char* w_mine = uniform_ptr((EPI == HS_EPI_SWIGLU_BF16 && wave >= 2) ? p.wb[1] : p.wb[0]);
-    auto issue_w = [&](int kt) {
-        const unsigned dst = smem_off + W_RING + (kt % SW) * W_STAGE + wave * 1024;
-        const unsigned char* base = w_mine + (size_t)kt * ROW_BYTES;
-#pragma unroll
-        for (int j = 0; j < NLW; j++) {
-            if (p.w_once) load_to_lds_16_stream(base, w_off[j], dst + j * 4096);
-            else load_to_lds_16(base, w_off[j], dst + j * 4096);
-        }
-    };
+    auto issue_w = [&](int kt) { issue_weight_tile<NU, MT, SA, SW>(p, w_mine, smem_off, w_off, wave, kt); };
     // Hand-over number h (h < kt0 before the loop, then in the middle of tile h): first the activation tile h+SA,
     // then the weight tile h+SW.  The issue order fixes the wait counts below.
     auto issue_for = [&](int h) {
@@ -134,8 +141,10 @@ __device__ __forceinline__ void stream_chunk(const stream_args& p, unsigned char
 
     // prologue: the hand-overs a longer-running loop would have made before tile kt0; of the last one only the
     // activation part (a multiplying wavefront issues its weight part during the first half of tile kt0, see below)
+    // (its first SW - SA hand-overs carry weight tiles only: the kernel issues those itself before it knows M)
 #pragma unroll
-    for (int h = -SW; h < -1; h++) issue_for(p.kt0 + h);
+    for (int h = -SW; h < -1; h++)
+        if (h >= -SA || !p.w_pre) issue_for(p.kt0 + h);
     wait_tile(p.kt0);
     __builtin_amdgcn_s_barrier();
     if (NMI == 0) issue_for(p.kt0 - 1);
@@ -471,6 +480,15 @@ __global__ __launch_bounds__(256) void hs_gemm_stream(const bf16_t* __restrict__
         w_off[j] = (unsigned)min(gn, N - 1) * (unsigned)(K * 2) + ((lpos ^ swz(row)) << 4);
     }
 
+    // The weight-only hand-overs of the first chunk's prologue go out now: they do not depend on the row count,
+    // whose load from device memory (first statement above) is still on its way -- nothing above has used it.
+    {
+        const unsigned char* w_mine = uniform_ptr((EPI == HS_EPI_SWIGLU_BF16 && wave >= 2) ? p.wb[1] : p.wb[0]);
+#pragma unroll
+        for (int h = -SW; h < -SA; h++)
+            if (p.kt0 + h + SW < p.kt1) issue_weight_tile<NU, MT, SA, SW>(p, w_mine, smem_off, w_off, wave, p.kt0 + h + SW);
+    }
+    p.w_pre = 1;
     for (p.m0 = pass * 128 * MT; p.m0 < p.M; p.m0 += n_pass * 128 * MT) {
         int nmi = 0;
 #pragma unroll
@@ -484,7 +502,9 @@ __global__ __launch_bounds__(256) void hs_gemm_stream(const bf16_t* __restrict__
         else if (MT >= 3)
             stream_chunk<EPI, PARTIAL, NU, MT, SA, SW, (MT >= 3 ? 3 : 1)>(p, smem, smem_off, w_off, wave, lane);
         __syncthreads();  // the rings are reused by the next row pass
+        p.w_pre = 0;
     }
+    HS_WAIT_VMCNT(0);     // (a workgroup without rows leaves with its early weight loads landed)
 }
 
 namespace {
